@@ -1,0 +1,297 @@
+// DeepSqueeze reference step on the CPU -- TEST INFRASTRUCTURE, not product code.
+//
+// A plain, slow, one-loop-per-sentence implementation of one iteration of
+// DeepSqueeze (Tang et al., arXiv:1907.07346, Algorithm 1) for n simulated
+// workers.  It exists only so that tests, the smoke check and the benchmark's
+// CPU-baseline leg have something independent to compare the GPU library with.
+// It shares no code, header, table or constant generator with the HIP path.
+//
+// State is held as in the paper's matrix notation (Section "Mathematical
+// formulation"), transposed: row i of X, G, Delta is worker i's vector of N
+// parameters.  One call performs, for every worker i,
+//
+//   line 5   v_i      = x_i - gamma * g_i + delta_i
+//   line 6   C[v_i]   = compress(v_i);   delta_i = v_i - C[v_i]
+//   line 7-8 the packed message of C[v_i] is "sent" (written to `msg`)
+//   line 9   x_i      = x_i - gamma * g_i + eta * sum_{j in N(i)} (W_ij - I_ij) C[v_j]
+//
+// with i in N(i) (the note in line 8), so the worker's own term enters through
+// its *compressed* value with coefficient W_ii - 1.
+//
+// The paper leaves C_omega generic (Assumption 1.6 only asks for a bounded
+// signal-to-noise factor).  The four operators implemented here, and the exact
+// floating-point evaluation order used for `real = float`, are this
+// repository's readings; every one is stated next to the code that does it.
+//
+// Everything is templated on `real`: double is used to check the algebraic
+// identities the paper states, float (same expression order as the GPU
+// kernels, contraction off, explicit fma) is used for bit-level parity.
+//
+// Build: g++ -O2 -ffp-contract=off -shared -fPIC ds_oracle.cpp -o libds_oracle.so
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+// as 1, 2, 3", SC'11).  Counter-based: out = f(counter, key), no state.
+// ---------------------------------------------------------------------------
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;   // round multipliers
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;   // key schedule (Weyl) increments
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = M0 * c0;                     // 32x32 -> 64
+        const uint64_t p1 = M1 * c2;
+        const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n1 = lo1;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        const uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// The random word that decides the stochastic rounding of element j of worker
+// i at iteration t.  Reading (the paper draws no random numbers itself):
+// counter = (floor(j/4), i, t mod 2^32, 'QUNT'), key = (seed low, seed high),
+// element j takes output word j mod 4.
+const uint32_t kQuantTag = 0x51554E54u;
+
+uint32_t rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
+    const uint32_t ctr[4] = {(uint32_t)(j / 4), i, (uint32_t)t, kQuantTag};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    philox4x32_10(ctr, key, out);
+    return out[j % 4];
+}
+
+enum Kind { IDENTITY = 0, QUANT_MAXABS = 1, SIGN_MEANABS = 2, TOPK = 3 };
+
+template <typename real> real fma_(real a, real b, real c);
+template <> float  fma_<float>(float a, float b, float c)    { return std::fmaf(a, b, c); }
+template <> double fma_<double>(double a, double b, double c) { return std::fma(a, b, c); }
+
+template <typename real> struct Msg {           // append-only byte sink, may be disabled
+    uint8_t* base; uint64_t cap; uint64_t used; bool overflow;
+    void put(const void* p, size_t nbytes) {
+        if (!base) return;
+        if (used + nbytes > cap) { overflow = true; return; }
+        std::memcpy(base + used, p, nbytes);
+        used += nbytes;
+    }
+    void put_u32(uint32_t w) { put(&w, 4); }
+    void put_f32(real s)     { float f = (float)s; put(&f, 4); }
+};
+
+// ---------------------------------------------------------------------------
+// C_omega, operator 1: stochastic b-bit uniform quantisation of one block with
+// a max-abs scale.  Grid: L+1 = 2^b equally spaced levels from -s to +s (no
+// zero level); v is mapped to t = (v/s + 1) * L/2 in [0, L], rounded down or up
+// at random so that E[q] = t, and decoded as (2q - L) * (s/L).
+// Message: [f32 s][ceil(m*b/32) u32 words], code of element e in bits
+// [b*(e mod 32/b), +b) of word floor(e*b/32).
+// ---------------------------------------------------------------------------
+template <typename real>
+void compress_block_quant(const real* v, real* cv, uint64_t m, int bits,
+                          uint64_t seed, uint64_t t, uint32_t i, uint64_t j0, Msg<real>& msg) {
+    const int L = (1 << bits) - 1;
+    real s = 0;
+    for (uint64_t e = 0; e < m; ++e) s = std::max(s, (real)std::fabs(v[e]));
+    const uint64_t nwords = (m * bits + 31) / 32;
+    std::vector<uint32_t> words(nwords, 0u);
+    const real hl = (real)0.5 * (real)L;
+    const real unit = s / (real)L;
+    const real inv = (s > 0) ? hl / s : (real)0;
+    for (uint64_t e = 0; e < m; ++e) {
+        int q = 0;
+        if (s > 0) {
+            real tt = fma_<real>(v[e], inv, hl);
+            tt = (tt > (real)0) ? tt : (real)0;          // also sends NaN to 0
+            tt = (tt < (real)L) ? tt : (real)L;
+            const real q0 = std::floor(tt);
+            const real fr = tt - q0;                     // exact
+            const real u = (real)(rounding_word(seed, t, i, j0 + e) >> 8) * (real)(1.0 / 16777216.0);
+            q = (int)q0 + ((u < fr) ? 1 : 0);
+            q = std::min(q, L);
+        }
+        cv[e] = (real)(2 * q - L) * unit;                // all-zero block: -L * 0 = -0
+        const uint64_t bitpos = e * (uint64_t)bits;
+        words[bitpos / 32] |= (uint32_t)q << (bitpos % 32);
+    }
+    msg.put_f32(s);
+    for (uint64_t w = 0; w < nwords; ++w) msg.put_u32(words[w]);
+}
+
+// ---------------------------------------------------------------------------
+// C_omega, operator 2: one sign bit per element and the block's mean absolute
+// value as scale (the 1-bit SGD family the paper's related-work section names).
+// The mean is sum/m with m the number of real elements; the sum is taken by a
+// balanced binary tree over the block padded with +0 to `block` entries
+// (adjacent pairs first), so that the float result does not depend on who
+// computes it.  A set bit means "negative" (the IEEE sign bit, so -0 counts as
+// negative).  Message: [f32 s][ceil(m/32) u32 words].
+// ---------------------------------------------------------------------------
+template <typename real>
+void compress_block_sign(const real* v, real* cv, uint64_t m, uint64_t block, Msg<real>& msg) {
+    std::vector<real> a(block, (real)0);
+    for (uint64_t e = 0; e < m; ++e) a[e] = std::fabs(v[e]);
+    for (uint64_t len = block; len > 1; len /= 2)
+        for (uint64_t p = 0; p < len / 2; ++p) a[p] = a[2 * p] + a[2 * p + 1];
+    const real s = a[0] / (real)m;
+    const uint64_t nwords = (m + 31) / 32;
+    std::vector<uint32_t> words(nwords, 0u);
+    for (uint64_t e = 0; e < m; ++e) {
+        const bool neg = std::signbit(v[e]);
+        cv[e] = neg ? -s : s;
+        if (neg) words[e / 32] |= 1u << (e % 32);
+    }
+    msg.put_f32(s);
+    for (uint64_t w = 0; w < nwords; ++w) msg.put_u32(words[w]);
+}
+
+// ---------------------------------------------------------------------------
+// C_omega, operator 3: top-k by magnitude over the whole vector of one worker.
+// Order: larger |v| first, equal |v| -> lower index first; the first k are
+// kept with their exact value, all others become +0.
+// Message: k pairs (u32 index, f32 value), ascending index.
+// ---------------------------------------------------------------------------
+template <typename real>
+void compress_row_topk(const real* v, real* cv, uint64_t N, uint64_t k, Msg<real>& msg) {
+    std::vector<uint64_t> order(N);
+    for (uint64_t j = 0; j < N; ++j) order[j] = j;
+    auto before = [v](uint64_t a, uint64_t b) {
+        const real fa = std::fabs(v[a]), fb = std::fabs(v[b]);
+        if (fa != fb) return fa > fb;
+        return a < b;
+    };
+    if (k < N) std::nth_element(order.begin(), order.begin() + k, order.end(), before);
+    std::vector<uint8_t> keep(N, 0);
+    for (uint64_t r = 0; r < k && r < N; ++r) keep[order[r]] = 1;
+    for (uint64_t j = 0; j < N; ++j) {
+        cv[j] = keep[j] ? v[j] : (real)0;
+        if (keep[j]) { msg.put_u32((uint32_t)j); msg.put_f32(v[j]); }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One iteration for all workers.  Dense n x N row-major arrays throughout.
+// W comes as CSR (rowptr, col, val) *including* the diagonal entry of every
+// row, columns ascending; the mixing coefficient of line 9 is
+// a_ij = W_ij - I_ij, formed once in `real`.
+// ---------------------------------------------------------------------------
+template <typename real>
+int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
+         int kind, int bits, uint64_t block, uint64_t k,
+         real gamma, real eta, uint64_t seed, uint64_t t,
+         real* x, real* delta, const real* g,
+         real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes) {
+    if (n < 1 || N < 1 || !rowptr || !col || !wval || !x || !delta || !g) return 1;
+    if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && (block < 1 || (block & (block - 1)))) return 1;
+    if (kind == QUANT_MAXABS && (bits < 1 || bits > 8 || 32 % bits)) return 1;
+    if (kind == TOPK && (k < 1 || k > N)) return 1;
+    for (int i = 0; i < n; ++i) {                         // CSR sanity: sorted, has diagonal
+        bool diag = false;
+        for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+            if (col[e] < 0 || col[e] >= n) return 1;
+            if (e > rowptr[i] && col[e] <= col[e - 1]) return 1;
+            diag |= (col[e] == i);
+        }
+        if (!diag) return 1;
+    }
+
+    const uint64_t total = (uint64_t)n * N;
+    std::vector<real> xh(total), v(total), cv_local;
+    real* cv = cv_out;
+    if (!cv) { cv_local.resize(total); cv = cv_local.data(); }
+    Msg<real> msg{msg_buf, msg_cap, 0, false};
+
+    // Algorithm 1, line 5: the error-compensated variable, evaluated as
+    // (x - gamma g) + delta with the product fused into the first sum.
+    for (int i = 0; i < n; ++i)
+        for (uint64_t j = 0; j < N; ++j) {
+            const uint64_t p = (uint64_t)i * N + j;
+            xh[p] = fma_<real>(-gamma, g[p], x[p]);
+            v[p] = xh[p] + delta[p];
+        }
+
+    // Line 6, first half, and lines 7-8: compress, and write what is sent.
+    for (int i = 0; i < n; ++i) {
+        const real* vi = &v[(uint64_t)i * N];
+        real* ci = &cv[(uint64_t)i * N];
+        if (kind == IDENTITY) {
+            for (uint64_t j = 0; j < N; ++j) { ci[j] = vi[j]; msg.put_f32(vi[j]); }
+        } else if (kind == QUANT_MAXABS || kind == SIGN_MEANABS) {
+            for (uint64_t j0 = 0; j0 < N; j0 += block) {
+                const uint64_t m = std::min<uint64_t>(block, N - j0);
+                if (kind == QUANT_MAXABS)
+                    compress_block_quant<real>(vi + j0, ci + j0, m, bits, seed, t, (uint32_t)i, j0, msg);
+                else
+                    compress_block_sign<real>(vi + j0, ci + j0, m, block, msg);
+            }
+        } else if (kind == TOPK) {
+            compress_row_topk<real>(vi, ci, N, k, msg);
+        } else {
+            return 1;
+        }
+    }
+
+    // Line 6, second half: what compression lost is carried to the next step.
+    for (uint64_t p = 0; p < total; ++p) delta[p] = v[p] - cv[p];
+
+    // Line 9: gossip on the compressed values, neighbours in ascending index
+    // order (own index included), accumulated by a chain of fused multiply-adds.
+    for (int i = 0; i < n; ++i)
+        for (uint64_t j = 0; j < N; ++j) {
+            real acc = 0;
+            for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                const int nb = col[e];
+                const real a = (nb == i) ? (wval[e] - (real)1) : wval[e];
+                acc = fma_<real>(a, cv[(uint64_t)nb * N + j], acc);
+            }
+            const uint64_t p = (uint64_t)i * N + j;
+            x[p] = fma_<real>(eta, acc, xh[p]);
+        }
+
+    if (msg_bytes) *msg_bytes = msg.used;
+    return msg.overflow ? 2 : 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+void dso_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
+    philox4x32_10(ctr, key, out);
+}
+
+uint32_t dso_rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
+    return rounding_word(seed, t, i, j);
+}
+
+int dso_step_f32(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const float* wval,
+                 int kind, int bits, uint64_t block, uint64_t k, float gamma, float eta,
+                 uint64_t seed, uint64_t t, float* x, float* delta, const float* g,
+                 float* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
+    return step<float>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t,
+                       x, delta, g, cv, msg, msg_cap, msg_bytes);
+}
+
+int dso_step_f64(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const double* wval,
+                 int kind, int bits, uint64_t block, uint64_t k, double gamma, double eta,
+                 uint64_t seed, uint64_t t, double* x, double* delta, const double* g,
+                 double* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
+    return step<double>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t,
+                        x, delta, g, cv, msg, msg_cap, msg_bytes);
+}
+
+}  // extern "C"

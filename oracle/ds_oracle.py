@@ -1,0 +1,178 @@
+"""ctypes front end of the CPU oracle (``ds_oracle.cpp``) -- test infrastructure.
+
+The arithmetic of the method lives in the C++ file; this module only builds it
+with g++, marshals numpy arrays, and offers the small dense helpers (mixing
+matrices of a ring and of a 2-D torus, CSR conversion) that tests need to state
+the paper's matrix identities.  Nothing here is used by the GPU library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+KIND_IDENTITY = 0      # C[v] = v: DeepSqueeze reduces to D-PSGD (paper, "Consistence with D-PSGD")
+KIND_QUANT_MAXABS = 1  # stochastic b-bit block quantisation, max-abs scale
+KIND_SIGN_MEANABS = 2  # sign bit + block mean-abs scale
+KIND_TOPK = 3          # k largest magnitudes of the whole vector
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ds_oracle.cpp")
+_LIB = os.path.join(_HERE, "libds_oracle.so")
+_lib = None
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the oracle with g++ (contraction off, no fast-math). Returns the .so path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC",
+               _SRC, "-o", _LIB]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build_oracle())
+    u64, i32, u32 = ctypes.c_uint64, ctypes.c_int, ctypes.c_uint32
+    vp = ctypes.c_void_p
+    for name, real in (("dso_step_f32", ctypes.c_float), ("dso_step_f64", ctypes.c_double)):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [i32, u64, vp, vp, vp, i32, i32, u64, u64, real, real, u64, u64,
+                       vp, vp, vp, vp, vp, u64, ctypes.POINTER(u64)]
+    lib.dso_philox4x32_10.restype = None
+    lib.dso_philox4x32_10.argtypes = [vp, vp, vp]
+    lib.dso_rounding_word.restype = u32
+    lib.dso_rounding_word.argtypes = [u64, u64, u32, u64]
+    _lib = lib
+    return lib
+
+
+def philox4x32_10(counter, key):
+    """Philox4x32-10 block function: 4 counter words, 2 key words -> 4 output words."""
+    lib = _load()
+    c = np.asarray(counter, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    assert c.shape == (4,) and k.shape == (2,)
+    out = np.zeros(4, dtype=np.uint32)
+    lib.dso_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
+    return out
+
+
+def rounding_word(seed: int, t: int, i: int, j: int) -> int:
+    """The 32-bit word that decides the stochastic rounding of element (i, j) at step t."""
+    return int(_load().dso_rounding_word(seed, t, i, j))
+
+
+# --- dense helpers for the tests' matrix identities --------------------------------------------
+
+def ring_matrix(n: int) -> np.ndarray:
+    """W of a ring: 1/3 on the diagonal and on the two cyclic neighbours (float64)."""
+    assert n >= 3
+    W = np.zeros((n, n))
+    for i in range(n):
+        for j in (i - 1, i, i + 1):
+            W[i, j % n] = 1.0 / 3.0
+    return W
+
+
+def torus_matrix(rows: int, cols: int) -> np.ndarray:
+    """W of a rows x cols 2-D torus (node id = r*cols + c): 1/5 on self and the 4 neighbours."""
+    assert rows >= 3 and cols >= 3
+    n = rows * cols
+    W = np.zeros((n, n))
+    for r in range(rows):
+        for c in range(cols):
+            i = r * cols + c
+            for rr, cc in ((r, c), (r - 1, c), (r + 1, c), (r, c - 1), (r, c + 1)):
+                W[i, (rr % rows) * cols + (cc % cols)] = 0.2
+    return W
+
+
+def dense_to_csr(W: np.ndarray):
+    """CSR (rowptr, col, val) of W with ascending columns; the diagonal is always stored."""
+    n = W.shape[0]
+    rowptr, col, val = [0], [], []
+    for i in range(n):
+        for j in range(n):
+            if W[i, j] != 0.0 or i == j:
+                col.append(j)
+                val.append(W[i, j])
+        rowptr.append(len(col))
+    return (np.asarray(rowptr, dtype=np.int32), np.asarray(col, dtype=np.int32),
+            np.asarray(val, dtype=np.float64))
+
+
+def message_bytes(kind: int, n: int, N: int, bits: int = 0, block: int = 0, k: int = 0) -> int:
+    """Size of one step's packed messages for all n workers."""
+    if kind == KIND_IDENTITY:
+        return n * N * 4
+    if kind == KIND_TOPK:
+        return n * k * 8
+    b = bits if kind == KIND_QUANT_MAXABS else 1
+    full, tail = divmod(N, block)
+    per_row = full * (4 + 4 * ((block * b + 31) // 32))
+    if tail:
+        per_row += 4 + 4 * ((tail * b + 31) // 32)
+    return n * per_row
+
+
+@dataclass
+class OracleState:
+    """x, delta (n x N), the step counter and the fixed parameters of a run."""
+    n: int
+    N: int
+    W: np.ndarray                      # dense n x n, float64
+    kind: int
+    gamma: float
+    eta: float
+    bits: int = 0
+    block: int = 0
+    k: int = 0
+    seed: int = 0
+    dtype: type = np.float32
+    t: int = 0
+    x: np.ndarray = field(default=None, repr=False)
+    delta: np.ndarray = field(default=None, repr=False)
+
+    def __post_init__(self):
+        if self.x is None:             # Algorithm 1, line 1 and Assumption 1.4: start from zero
+            self.x = np.zeros((self.n, self.N), dtype=self.dtype)
+        if self.delta is None:
+            self.delta = np.zeros((self.n, self.N), dtype=self.dtype)
+        self._csr = dense_to_csr(np.asarray(self.W, dtype=np.float64))
+
+
+def step(st: OracleState, g: np.ndarray, want_cv: bool = True, want_msg: bool = True):
+    """Advance `st` by one iteration with gradients g (n x N). Returns (C[v], message bytes)."""
+    lib = _load()
+    dt = np.dtype(st.dtype)
+    assert dt in (np.dtype(np.float32), np.dtype(np.float64))
+    g = np.ascontiguousarray(g, dtype=dt)
+    assert g.shape == (st.n, st.N)
+    assert st.x.dtype == dt and st.delta.dtype == dt and st.x.flags.c_contiguous and st.delta.flags.c_contiguous
+    rowptr, col, val = st._csr
+    wval = np.ascontiguousarray(val, dtype=dt)     # fp32 run: W rounded once to fp32
+    cv = np.empty((st.n, st.N), dtype=dt) if want_cv else None
+    cap = message_bytes(st.kind, st.n, st.N, st.bits, st.block, st.k) if want_msg else 0
+    msg = np.zeros(cap, dtype=np.uint8) if want_msg else None
+    used = ctypes.c_uint64(0)
+    fn = lib.dso_step_f32 if dt == np.dtype(np.float32) else lib.dso_step_f64
+    rc = fn(st.n, st.N, rowptr.ctypes.data, col.ctypes.data, wval.ctypes.data,
+            st.kind, st.bits, st.block, st.k, st.gamma, st.eta, st.seed, st.t,
+            st.x.ctypes.data, st.delta.ctypes.data, g.ctypes.data,
+            cv.ctypes.data if want_cv else None,
+            msg.ctypes.data if want_msg else None, cap, ctypes.byref(used))
+    if rc != 0:
+        raise RuntimeError(f"oracle step failed with code {rc}")
+    st.t += 1
+    if want_msg:
+        assert used.value == cap, (used.value, cap)
+    return cv, msg
