@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Throughput of the DeepSqueeze step (ds_step) on one MI355X.
+
+One "step" is one ds_step call: the whole fused compress-and-gossip pass (Algorithm 1, lines 5-9)
+over all n workers of the chosen benchmark configuration, gradients already resident in HBM.
+Prints ONE JSON line on stdout: worker-parameter updates per second, the HBM roofline of the
+dominant kernel (algorithmic bytes / measured time against the 8 TB/s nameplate) and the CPU
+oracle timed on a bounded sample of the same workload as a reported baseline.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes_per_param(w) -> float:
+    """Bytes the method must move per worker-parameter: read x, g, delta; write x, delta; write the message."""
+    from paper_1907_07346_amd import workloads as wl
+    if w.kind == wl.KIND_QUANT_MAXABS:
+        msg = w.bits / 8 + 4 / w.block
+    elif w.kind == wl.KIND_SIGN_MEANABS:
+        msg = 1 / 8 + 4 / w.block
+    elif w.kind == wl.KIND_TOPK:
+        msg = 8 * w.k / w.N
+    else:
+        msg = 4.0
+    return 20.0 + msg
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The CPU oracle, as it stands, on the first `Ns` columns of the same workload (single thread)."""
+    import numpy as np
+
+    import oracle
+    from paper_1907_07346_amd import workloads as wl
+    blk = w.block if w.block else 1024
+    Ns = min(w.N, max(blk, (2_000_000 // w.n) // blk * blk))
+    ws = w.scaled(Ns)
+    W = oracle.ring_matrix(ws.n) if ws.topo == wl.TOPO_RING else oracle.torus_matrix(*ws.torus)
+    st = oracle.OracleState(n=ws.n, N=ws.N, W=W, kind=ws.kind, gamma=ws.gamma, eta=ws.eta, bits=ws.bits,
+                            block=ws.block, k=ws.k, seed=ws.seed)
+    c = wl.centres(ws) if ws.grad == "quadratic" else None
+    gs = [wl.gradient(ws, t, st.x, c) for t in range(2)]
+    oracle.step(st, gs[0], want_cv=False, want_msg=True)           # warm-up (page faults, code)
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.step(st, gs[steps % 2], want_cv=False, want_msg=True)
+        steps += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or steps >= 50:
+            break
+    return {"value": ws.n * ws.N * steps / el, "unit": "worker-param updates/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {Ns} of {w.N} columns, all {w.n} workers, {steps} steps in {el:.1f} s "
+                      f"(g++ -O2, one thread; host has {os.cpu_count()} logical cores)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configuration list")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (counter calibration)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (n simulated workers on one device); "
+              "--gpus must be 1, no multi-GPU figure exists.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_1907_07346_amd import binding as b
+    from paper_1907_07346_amd import workloads as wl
+
+    torch.cuda.set_device(0)
+    w = wl.configs()[args.config]
+    K, Wm = args.steps, args.warmup
+
+    # plain copy yardstick (and the only thing run under --copy-only)
+    nbytes = 1 << 30
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        b.ds_bench_copy(dst, src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    reps = 20
+    for _ in range(reps):
+        b.ds_bench_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
+    if args.copy_only:
+        print(json.dumps({"copy_GBps": copy_gbs, "bytes_per_launch": 2 * nbytes}))
+        return
+
+    ds = b.DeepSqueeze.from_workload(w)
+    _, _, ld = ds.ds_state_ptrs()
+    nbuf = 3
+    gs = []
+    for t in range(nbuf):                                   # gradients resident in HBM, pitch = state pitch
+        g = torch.zeros((w.n, ld), dtype=torch.float32, device="cuda")
+        g[:, :w.N] = wl.device_gradient(w, t)
+        gs.append(g)
+    torch.cuda.synchronize()
+    for t in range(Wm):
+        ds.ds_step(gs[t % nbuf])
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()                                            # same stream ds_step launches on
+    for t in range(K):
+        ds.ds_step(gs[t % nbuf])
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall * 1e3 / K
+    value = w.worker_params * K / wall
+
+    beta = algorithmic_bytes_per_param(w)
+    bytes_per_launch = beta * w.worker_params
+    achieved = bytes_per_launch / (dev_ms * 1e-3 / K) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(w.name)
+    out = {
+        "metric": "worker-param updates/sec and achieved HBM GB/s (% peak) per ds_step",
+        "value": value, "unit": "worker-param updates/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "N": w.N, "plan": ds.ds_plan_name(),
+                   "compressor": {1: f"quant{w.bits}b/B{w.block}", 2: f"sign/B{w.block}", 3: f"top-{w.k}", 0: "identity"}[w.kind]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_param": beta, "device_ms_per_step": dev_ms / K, "plain_copy_GBps": copy_gbs,
+                     "frac_of_plain_copy": achieved / copy_gbs},
+    }
+    ds.ds_destroy()
+    del gs
+    torch.cuda.empty_cache()
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,166 @@
+/*
+ * dsq.h -- C ABI of libdsq: the per-iteration hot path of DeepSqueeze
+ * (Tang, Lian, Qiu, Yuan, Zhang, Zhang, Liu: "DeepSqueeze: Decentralization
+ * meets error-compensated compression", arXiv:1907.07346) on one AMD MI355X.
+ *
+ * The library simulates the n workers of the paper's Equation (1) as the rows
+ * of an n x N fp32 state on a single GPU.  One ds_step() call is one pass of
+ * the loop body of Algorithm 1 (lines 5-9) for all workers:
+ *
+ *   v_i     = x_i - gamma g_i + delta_i                              (line 5)
+ *   C[v_i]  = C_omega(v_i),   delta_i = v_i - C[v_i]                 (line 6)
+ *   message_i = packed C[v_i]  ("send"/"receive" = written to HBM)   (lines 7-8)
+ *   x_i     = x_i - gamma g_i + eta sum_{j in N(i)} (W_ij - I_ij) C[v_j],
+ *             N(i) containing i itself                               (line 9)
+ *
+ * All pointers named *_dev are device pointers of the current HIP device; all
+ * others are host pointers.  No torch types, no C++ types.  Every function
+ * returns a ds_status (or a plain value), never throws and never aborts.
+ * A handle is not thread-safe; calls on one handle must not overlap.
+ */
+#ifndef DSQ_H
+#define DSQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ds_handle ds_handle;   /* opaque; owned by the library, freed by ds_destroy */
+
+typedef enum {
+    DS_OK = 0,
+    DS_EINVAL = 1,   /* bad argument or unsupported configuration; see ds_last_error */
+    DS_ENOMEM = 2,   /* device or host allocation failed */
+    DS_EHIP = 3,     /* a HIP runtime call failed */
+    DS_ESTATE = 4    /* call not valid in the handle's current state (e.g. no step taken yet) */
+} ds_status;
+
+/* Communication graph.  W is the symmetric doubly stochastic mixing matrix of
+ * the paper's Algorithm section and Assumption 1.2. */
+typedef enum {
+    DS_TOPO_RING = 0,     /* W_ii = W_i,i+1 = W_i,i-1 = 1/3 (indices mod n), n >= 3            */
+    DS_TOPO_TORUS2D = 1,  /* node r*cols+c; self and the 4 wrap-around neighbours weigh 1/5;   */
+                          /* torus_rows, torus_cols >= 3, torus_rows*torus_cols == n           */
+    DS_TOPO_CSR = 2       /* W given by the caller in CSR form                                 */
+} ds_topology;
+
+/* Compression operator C_omega (the paper leaves it generic, Assumption 1.6). */
+typedef enum {
+    DS_COMP_IDENTITY = 0,     /* C[v] = v: the step is plain D-PSGD; message = v in fp32        */
+    DS_COMP_QUANT_MAXABS = 1, /* stochastic `bits`-bit uniform quantisation per block of `block` */
+                              /* elements, scale = max |v| of the block; bits in {2, 4}          */
+    DS_COMP_SIGN_MEANABS = 2, /* sign bit per element, scale = mean |v| of the block            */
+    DS_COMP_TOPK = 3          /* the k largest |v| of each worker's whole vector, ties to the   */
+                              /* lower index; message = k (u32 index, f32 value) pairs          */
+} ds_comp_kind;
+
+typedef struct {
+    int32_t  kind;    /* ds_comp_kind */
+    int32_t  bits;    /* QUANT_MAXABS: 2 or 4; otherwise ignored                                */
+    int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 256 <= block <= 2048          */
+    int32_t  reserved;
+    uint64_t k;       /* TOPK: 1 <= k <= N; otherwise ignored                                   */
+} ds_comp;
+
+typedef struct {
+    int32_t  n;               /* number of workers (rows), >= 1                                  */
+    int32_t  topo;            /* ds_topology                                                     */
+    uint64_t N;               /* parameters per worker (columns), >= 1                           */
+    int32_t  torus_rows;      /* DS_TOPO_TORUS2D only                                            */
+    int32_t  torus_cols;
+    /* DS_TOPO_CSR only (host pointers, copied by ds_init): CSR of W, n rows, every row holding
+     * its diagonal entry (possibly 0), columns strictly ascending.  ds_init checks W >= 0,
+     * symmetry and row sums == 1 within 1e-6.  Must be NULL for RING / TORUS2D.               */
+    const int32_t* W_rowptr;
+    const int32_t* W_col;
+    const float*   W_val;
+    ds_comp  comp;
+    float    gamma;           /* learning rate                                                   */
+    float    eta;             /* averaging rate; the paper's Theorem 1 wants eta <= 1/2: a larger */
+                              /* value is accepted and noted in ds_last_error                    */
+    uint64_t seed;            /* key of the stochastic-rounding random stream                    */
+} ds_config;
+
+/* ---- host-only helpers (no GPU needed) ------------------------------------------------------ */
+
+/* Checks a configuration the way ds_init does.  On failure writes a message of at most
+ * errbuf_len-1 characters into errbuf (if non-NULL) and returns DS_EINVAL. */
+ds_status ds_validate_config(const ds_config* cfg, char* errbuf, uint64_t errbuf_len);
+
+/* Writes the CSR of W for a ring or torus configuration (the matrix ds_init would use).
+ * rowptr: n+1 entries; col, val: capacity `cap` entries; *nnz receives the count.
+ * Returns DS_EINVAL if the topology is invalid or cap is too small. */
+ds_status ds_build_topology(const ds_config* cfg, int32_t* rowptr, int32_t* col, float* val,
+                            uint64_t cap, uint64_t* nnz);
+
+/* Bytes of all n workers' packed messages of one step (row i's message starts at
+ * i * ds_message_bytes(cfg) / n).  Layout per worker:
+ *   QUANT / SIGN: for each block, in column order: [f32 scale][ceil(m*b/32) u32 words], m = number
+ *                 of elements in the block (the last one may be ragged), b = bits (1 for SIGN);
+ *                 the code of element e of the block sits in bits [b*(e mod 32/b), +b) of word
+ *                 floor(e*b/32); QUANT code q in [0, 2^b-1] decodes to (2q - (2^b-1)) * scale/(2^b-1);
+ *                 SIGN bit 1 means negative and decodes to -scale; unused high bits are 0.
+ *   TOPK:         k pairs (u32 index, f32 value) in ascending index order.
+ *   IDENTITY:     N fp32 values.
+ * Returns 0 for an invalid configuration. */
+uint64_t ds_message_bytes(const ds_config* cfg);
+
+/* ---- the hot path --------------------------------------------------------------------------- */
+
+/* Creates the state on the current HIP device: x = 0, delta = 0, t = 0 (Algorithm 1, line 1;
+ * Assumption 1.4).  Allocates x, delta (n rows with an internal pitch), the message buffer and
+ * scratch with hipMalloc.  *out is NULL on failure. */
+ds_status ds_init(const ds_config* cfg, ds_handle** out);
+
+/* One iteration of Algorithm 1 (lines 5-9) for all n workers with the gradients g_dev.
+ * g_dev: caller-owned DEVICE pointer, n rows of fp32, row pitch g_ld >= N elements, g_ld a multiple
+ * of 4, base 16-byte aligned; read-only.  Work is enqueued on hip_stream (a hipStream_t, NULL = the
+ * default stream) and the call returns without synchronising; g_dev must stay valid until that
+ * work has finished.  Advances the step counter t by 1. */
+ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_stream);
+
+/* Copies the state to dense host arrays of n*N fp32 each (delta_host may be NULL).  Synchronises
+ * with the stream of the last ds_step. */
+ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host);
+
+/* Overwrites the state from dense host arrays (n*N fp32 each; NULL leaves that array unchanged)
+ * and sets the step counter.  With the counter-based random stream this makes a run restartable:
+ * read_state at step t, write_state into a fresh handle, and the continuation is bit-identical. */
+ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_host, uint64_t t);
+
+/* Copies the packed messages of the last ds_step (layout: ds_message_bytes) into host_buf of
+ * capacity cap; *bytes receives the size.  DS_ESTATE before the first step, DS_EINVAL if cap is
+ * too small.  Synchronises like ds_read_state. */
+ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t* bytes);
+
+/* Borrows the device arrays: row i of x starts at x_dev + i*ld.  Ownership stays with the
+ * handle; columns >= N of each row are padding the caller must leave zero. */
+ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t* ld);
+
+/* Borrows the device message buffer (ds_message_bytes bytes, layout as above). */
+ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes);
+
+/* Step counter t (number of ds_step calls since init or the value set by ds_write_state). */
+uint64_t ds_step_count(const ds_handle* h);
+
+/* Name of the kernel plan ds_step uses for this handle (static string, for reports). */
+const char* ds_plan_name(const ds_handle* h);
+
+/* Text of the last error or warning on this handle ("" if none).  Valid until the next call. */
+const char* ds_last_error(const ds_handle* h);
+
+/* Measurement aid, not part of the method: a plain streaming copy of `bytes` (a multiple of 16,
+ * both pointers 16-byte aligned, device memory) enqueued on hip_stream.  Benchmarks use it to
+ * report the HBM bandwidth a trivial kernel reaches on the same GPU, and profiles use it to
+ * calibrate the hardware traffic counters against a known byte count. */
+ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream);
+
+/* Frees everything the handle owns (synchronises first).  NULL is a no-op. */
+void ds_destroy(ds_handle* h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSQ_H */

@@ -1,0 +1,223 @@
+// C ABI of libdsq: handle life cycle, state transfer and the ds_step dispatcher.
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "dsq_internal.h"
+
+struct ds_handle {
+    ds_config cfg{};
+    dsq::Graph graph;
+    uint64_t ld = 0;                 // row pitch of x and delta, in floats
+    uint64_t msg_row_bytes = 0;
+    uint64_t t = 0;
+    bool stepped = false;
+    int device = 0;
+    hipStream_t last_stream = nullptr;
+    float* x = nullptr;
+    float* delta = nullptr;
+    uint8_t* msg = nullptr;
+    int32_t* d_rowptr = nullptr;
+    int32_t* d_col = nullptr;
+    float* d_coef = nullptr;
+    dsq::TilePlan tile;
+    dsq::TopkState* topk = nullptr;
+    std::string err;
+    std::string plan_name;
+};
+
+namespace {
+
+ds_status fail(ds_handle* h, ds_status st, const std::string& msg) {
+    if (h) h->err = msg;
+    return st;
+}
+
+ds_status hip_fail(ds_handle* h, hipError_t e, const char* what) {
+    return fail(h, e == hipErrorOutOfMemory ? DS_ENOMEM : DS_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define DSQ_HIP(h, call)                                              \
+    do {                                                              \
+        hipError_t e_ = (call);                                       \
+        if (e_ != hipSuccess) return hip_fail((h), e_, #call);        \
+    } while (0)
+
+void release(ds_handle* h) {
+    if (!h) return;
+    if (h->topk) dsq::topk_destroy(h->topk);
+    if (h->x) (void)hipFree(h->x);
+    if (h->delta) (void)hipFree(h->delta);
+    if (h->msg) (void)hipFree(h->msg);
+    if (h->d_rowptr) (void)hipFree(h->d_rowptr);
+    if (h->d_col) (void)hipFree(h->d_col);
+    if (h->d_coef) (void)hipFree(h->d_coef);
+    delete h;
+}
+
+// Plain streaming copy (float4 per lane, grid-stride): the yardstick for achievable HBM bandwidth.
+__global__ void __launch_bounds__(256) copy_kernel(float4* __restrict__ dst, const float4* __restrict__ src, uint64_t n4) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+
+extern "C" {
+
+ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream) {
+    if (!dst_dev || !src_dev || (bytes & 15) || ((reinterpret_cast<uintptr_t>(dst_dev) | reinterpret_cast<uintptr_t>(src_dev)) & 15))
+        return DS_EINVAL;
+    const uint64_t n4 = bytes / 16;
+    if (n4 == 0) return DS_OK;
+    const uint64_t want = (n4 + 255) / 256;
+    const unsigned blocks = (unsigned)(want < 256u * 32u ? want : 256u * 32u);
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<float4*>(dst_dev), static_cast<const float4*>(src_dev), n4);
+    return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
+}
+
+ds_status ds_init(const ds_config* cfg, ds_handle** out) {
+    if (!out) return DS_EINVAL;
+    *out = nullptr;
+    ds_handle* h = new (std::nothrow) ds_handle();
+    if (!h) return DS_ENOMEM;
+    auto bail = [&](ds_status st) { release(h); return st; };
+
+    std::string err, warn;
+    if (dsq::validate_config(cfg, err, &warn) != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(DS_EINVAL); }
+    h->cfg = *cfg;
+    if (dsq::build_graph(cfg, h->graph, err) != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(DS_EINVAL); }
+    h->cfg.W_rowptr = nullptr; h->cfg.W_col = nullptr; h->cfg.W_val = nullptr;   // the copy lives in graph
+    h->ld = (cfg->N + dsq::kPitchAlign - 1) / dsq::kPitchAlign * dsq::kPitchAlign;
+    h->msg_row_bytes = dsq::message_row_bytes(cfg);
+
+    if (cfg->comp.kind == DS_COMP_TOPK) {
+        h->plan_name = "topk/radix-select";
+    } else {
+        if (!dsq::choose_tile_plan(h->cfg, h->graph.max_degree, h->tile, err)) {
+            std::fprintf(stderr, "ds_init: %s\n", err.c_str());
+            return bail(DS_EINVAL);
+        }
+        h->plan_name = h->tile.name;
+    }
+
+    hipError_t e = hipGetDevice(&h->device);
+    if (e != hipSuccess) { std::fprintf(stderr, "ds_init: no HIP device: %s\n", hipGetErrorString(e)); return bail(DS_EHIP); }
+    const size_t state_bytes = (size_t)cfg->n * h->ld * sizeof(float);
+    const size_t nnz = h->graph.col.size();
+    const size_t msg_bytes = (size_t)cfg->n * h->msg_row_bytes;
+    hipError_t errs[6] = {
+        hipMalloc(&h->x, state_bytes), hipMalloc(&h->delta, state_bytes), hipMalloc(&h->msg, msg_bytes ? msg_bytes : 4),
+        hipMalloc(&h->d_rowptr, (cfg->n + 1) * sizeof(int32_t)), hipMalloc(&h->d_col, nnz * sizeof(int32_t)),
+        hipMalloc(&h->d_coef, nnz * sizeof(float))};
+    for (hipError_t ee : errs)
+        if (ee != hipSuccess) { std::fprintf(stderr, "ds_init: hipMalloc: %s\n", hipGetErrorString(ee)); return bail(ee == hipErrorOutOfMemory ? DS_ENOMEM : DS_EHIP); }
+    bool ok = hipMemset(h->x, 0, state_bytes) == hipSuccess && hipMemset(h->delta, 0, state_bytes) == hipSuccess &&
+              hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4) == hipSuccess &&
+              hipMemcpy(h->d_rowptr, h->graph.rowptr.data(), (cfg->n + 1) * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(h->d_col, h->graph.col.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+              hipMemcpy(h->d_coef, h->graph.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice) == hipSuccess &&
+              hipDeviceSynchronize() == hipSuccess;
+    if (!ok) { std::fprintf(stderr, "ds_init: device initialisation failed\n"); return bail(DS_EHIP); }
+
+    if (cfg->comp.kind == DS_COMP_TOPK) {
+        const ds_status st = dsq::topk_create(h->cfg, h->ld, &h->topk, err);
+        if (st != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(st); }
+    }
+    h->err = warn;
+    *out = h;
+    return DS_OK;
+}
+
+ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_stream) {
+    if (!h) return DS_EINVAL;
+    if (!g_dev) return fail(h, DS_EINVAL, "g_dev is NULL");
+    if (g_ld < h->cfg.N || (g_ld & 3)) return fail(h, DS_EINVAL, "g_ld must be >= N and a multiple of 4");
+    if (reinterpret_cast<uintptr_t>(g_dev) & 15) return fail(h, DS_EINVAL, "g_dev must be 16-byte aligned");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    if (h->cfg.comp.kind == DS_COMP_TOPK) {
+        dsq::TopkArgs a{};
+        a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
+        a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
+        a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.k = h->cfg.comp.k; a.n = h->cfg.n;
+        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
+        const ds_status st = dsq::topk_step(h->topk, a, h->graph, stream, h->err);
+        if (st != DS_OK) return st;
+    } else {
+        dsq::TileArgs a{};
+        a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
+        a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
+        a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes; a.n = h->cfg.n;
+        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
+        a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32); a.t_lo = (uint32_t)h->t;
+        h->tile.launch(a, h->tile.rows_per_wave, stream);
+    }
+    DSQ_HIP(h, hipGetLastError());
+    h->t += 1;
+    h->stepped = true;
+    h->last_stream = stream;
+    return DS_OK;
+}
+
+ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host) {
+    if (!h) return DS_EINVAL;
+    if (!x_host && !delta_host) return fail(h, DS_EINVAL, "nothing to read");
+    DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
+    const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
+    if (x_host) DSQ_HIP(h, hipMemcpy2D(x_host, row, h->x, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
+    if (delta_host) DSQ_HIP(h, hipMemcpy2D(delta_host, row, h->delta, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
+    return DS_OK;
+}
+
+ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_host, uint64_t t) {
+    if (!h) return DS_EINVAL;
+    DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
+    const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
+    if (x_host) DSQ_HIP(h, hipMemcpy2D(h->x, pitch, x_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
+    if (delta_host) DSQ_HIP(h, hipMemcpy2D(h->delta, pitch, delta_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
+    DSQ_HIP(h, hipDeviceSynchronize());
+    h->t = t;
+    return DS_OK;
+}
+
+ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t* bytes) {
+    if (!h) return DS_EINVAL;
+    if (!h->stepped) return fail(h, DS_ESTATE, "no step has been taken yet");
+    const uint64_t total = h->msg_row_bytes * (uint64_t)h->cfg.n;
+    if (bytes) *bytes = total;
+    if (!host_buf || cap < total) return fail(h, DS_EINVAL, "message buffer too small");
+    DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
+    DSQ_HIP(h, hipMemcpy(host_buf, h->msg, total, hipMemcpyDeviceToHost));
+    return DS_OK;
+}
+
+ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t* ld) {
+    if (!h) return DS_EINVAL;
+    if (x_dev) *x_dev = h->x;
+    if (delta_dev) *delta_dev = h->delta;
+    if (ld) *ld = h->ld;
+    return DS_OK;
+}
+
+ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes) {
+    if (!h) return DS_EINVAL;
+    if (msg_dev) *msg_dev = h->msg;
+    if (bytes) *bytes = h->msg_row_bytes * (uint64_t)h->cfg.n;
+    return DS_OK;
+}
+
+uint64_t ds_step_count(const ds_handle* h) { return h ? h->t : 0; }
+
+const char* ds_plan_name(const ds_handle* h) { return h ? h->plan_name.c_str() : ""; }
+
+const char* ds_last_error(const ds_handle* h) { return h ? h->err.c_str() : "handle is NULL"; }
+
+void ds_destroy(ds_handle* h) {
+    if (!h) return;
+    (void)hipDeviceSynchronize();
+    release(h);
+}
+
+}  // extern "C"

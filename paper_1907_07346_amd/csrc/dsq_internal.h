@@ -1,0 +1,79 @@
+// Internal declarations shared by the host side and the kernel launchers of libdsq.
+// Nothing here is part of the C ABI (that is include/dsq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "dsq.h"
+
+namespace dsq {
+
+constexpr int kWave = 64;                 // gfx950 wavefront
+constexpr int kSweep = 4 * kWave;         // columns one wave covers with one float4 per lane
+constexpr uint64_t kPitchAlign = 4096;    // x / delta row pitch is a multiple of this many floats
+constexpr int kMinBlock = 256, kMaxBlock = 2048;
+
+// Host-side description of W - I in CSR form (diagonal always present, columns ascending).
+struct Graph {
+    std::vector<int32_t> rowptr, col;
+    std::vector<float> w;      // W_ij as given / built
+    std::vector<float> coef;   // a_ij = W_ij - I_ij in fp32 (the coefficients of Algorithm 1, line 9)
+    int max_degree = 0;        // entries per row, diagonal included
+};
+
+// Validation and topology construction (pure host code, usable without a GPU).
+ds_status validate_config(const ds_config* cfg, std::string& err, std::string* warn);
+ds_status build_graph(const ds_config* cfg, Graph& g, std::string& err);
+uint64_t message_row_bytes(const ds_config* cfg);
+
+// Arguments of the fused tile kernels (block quantiser / sign / identity).
+struct TileArgs {
+    float* x;                  // n x ld
+    float* delta;              // n x ld
+    const float* g;            // n x g_ld
+    uint8_t* msg;              // n x msg_row_bytes
+    const int32_t* rowptr;     // device CSR of W - I
+    const int32_t* col;
+    const float* coef;
+    uint64_t ld, g_ld, N, msg_row_bytes;
+    int n;
+    float gamma, eta;
+    uint32_t seed_lo, seed_hi, t_lo;
+};
+
+// A compiled variant of the fused tile kernel, chosen once at init.
+struct TilePlan {
+    const char* name = "";
+    void (*launch)(const TileArgs&, int rows_per_wave, hipStream_t) = nullptr;
+    int tile_cols = 0;         // columns per workgroup
+    int waves = 0;             // waves per workgroup
+    int rows_per_wave = 0;     // rows each wave owns (held in registers when the variant says so)
+};
+
+// Picks the variant for (n, compressor); returns false with `err` set if no variant fits.
+bool choose_tile_plan(const ds_config& cfg, int max_degree, TilePlan& plan, std::string& err);
+
+// ---- top-k path ---------------------------------------------------------------------------------
+struct TopkArgs {
+    float* x;
+    float* delta;
+    const float* g;
+    uint8_t* msg;              // n x k pairs (u32 index, f32 value)
+    const int32_t* rowptr;
+    const int32_t* col;
+    const float* coef;
+    uint64_t ld, g_ld, N, k;
+    int n;
+    float gamma, eta;
+};
+
+struct TopkState;              // device scratch of the radix select (histograms, per-chunk counts)
+ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::string& err);
+void topk_destroy(TopkState* s);
+ds_status topk_step(TopkState* s, const TopkArgs& a, const Graph& graph, hipStream_t stream, std::string& err);
+
+}  // namespace dsq

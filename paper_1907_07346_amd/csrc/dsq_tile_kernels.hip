@@ -1,0 +1,435 @@
+// Fused compress-and-gossip tile kernels for the block compressors of libdsq (gfx950).
+//
+// One workgroup owns a tile of TC consecutive parameter columns for ALL n workers.
+// Because every scale block is column-local and the mixing matrix W only couples
+// different workers at the same column, the whole loop body of DeepSqueeze's
+// Algorithm 1 (lines 5-9) can be finished for the tile in one pass over HBM:
+//
+//   phase 1 (per worker row, one wave per row at a time)
+//     line 5   xh = x - gamma g,  v = xh + delta            (float4 streams, registers)
+//     line 6   per block: scale by a wave64 reduction, codes, C[v], delta = v - C[v] -> HBM
+//     line 7   packed message -> HBM, and the codes + decode units -> LDS
+//   barrier    ("receive": every row's codes of this tile are now in LDS)
+//   phase 2    line 9: x = xh + eta * sum_j (W_ij - I_ij) C[v_j], decoding the neighbours'
+//              codes from LDS, with xh still in registers                      -> HBM
+//
+// Traffic per worker-parameter: 12 B read (x, g, delta), 8 B written (x, delta) plus the
+// packed message.  The floating-point expression order below is fixed (contraction off,
+// explicit fmaf) so that codes, scales and messages are reproducible bit for bit.
+
+#include "dsq_internal.h"
+
+namespace dsq {
+namespace {
+
+// ---- Philox4x32-10 (Salmon et al., SC'11), counter-based, no state --------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+constexpr uint32_t kQuantStreamTag = 0x51554E54u;   // 4th counter word of the rounding stream
+
+// ---- wave64 reductions; every lane ends with the result ---------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+// Pairwise tree in lane order: level k adds the sums of adjacent groups of 2^k lanes.  Both
+// partners of an exchange compute a+b (commutative), so all lanes hold identical bits.
+__device__ __forceinline__ float wave_sum_tree(float v) {
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) v = v + __shfl_xor(v, o);
+    return v;
+}
+
+template <int KIND, int BITS> struct CodeTraits;
+template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 4> { using lane_t = uint16_t; static constexpr int row_bytes_per_sweep = 128; };
+template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 2> { using lane_t = uint8_t;  static constexpr int row_bytes_per_sweep = 64; };
+template <> struct CodeTraits<DS_COMP_SIGN_MEANABS, 1> { using lane_t = uint32_t; static constexpr int row_bytes_per_sweep = 32; };
+template <> struct CodeTraits<DS_COMP_IDENTITY, 32>    { using lane_t = float4;   static constexpr int row_bytes_per_sweep = 1024; };
+
+__device__ __forceinline__ float comp(const float4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
+__device__ __forceinline__ void set_comp(float4& v, int c, float f) { if (c == 0) v.x = f; else if (c == 1) v.y = f; else if (c == 2) v.z = f; else v.w = f; }
+
+template <int KIND, int BITS, int B, int SW, int NW>
+struct Tile {
+    static constexpr int TC = SW * kSweep;                 // columns per tile
+    static constexpr int SPB = B / kSweep;                 // sweeps per scale block
+    static constexpr int BPT = SW / SPB;                   // scale blocks per tile
+    static constexpr int L = BITS < 31 ? (1 << (BITS & 15)) - 1 : 0;   // top quantisation level
+    using CT = CodeTraits<KIND, BITS>;
+    static constexpr int ROW_CODE_BYTES = SW * CT::row_bytes_per_sweep;
+    static constexpr int MSG_BLOCK_BYTES = 4 + B * (BITS & 15) / 8;   // [scale][codes] of a full block
+    static_assert(B % kSweep == 0 && SW % SPB == 0, "tile must hold whole blocks");
+
+    static __host__ __device__ constexpr size_t lds_bytes(int n) {
+        return (size_t)n * ROW_CODE_BYTES + (size_t)n * BPT * sizeof(float);
+    }
+
+    // ---- phase 1 for one row: returns xh (x - gamma g) in registers ---------------------------
+    template <bool FULL>
+    static __device__ __forceinline__ void compress_row(const TileArgs& a, int i, uint64_t col0, int lane,
+                                                        uint8_t* lds_codes, float* lds_units, float4 (&xh)[SW]) {
+        float4 xv[SW], gv[SW], dv[SW];
+        const float* xr = a.x + (uint64_t)i * a.ld + col0 + 4 * lane;
+        const float* dr = a.delta + (uint64_t)i * a.ld + col0 + 4 * lane;
+        const float* gr = a.g + (uint64_t)i * a.g_ld + col0 + 4 * lane;
+#pragma unroll
+        for (int s = 0; s < SW; ++s) {
+            xv[s] = *reinterpret_cast<const float4*>(xr + s * kSweep);
+            dv[s] = *reinterpret_cast<const float4*>(dr + s * kSweep);
+            if (FULL) {
+                gv[s] = *reinterpret_cast<const float4*>(gr + s * kSweep);
+            } else {
+                const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                gv[s].x = (j + 0 < a.N) ? gr[s * kSweep + 0] : 0.f;
+                gv[s].y = (j + 1 < a.N) ? gr[s * kSweep + 1] : 0.f;
+                gv[s].z = (j + 2 < a.N) ? gr[s * kSweep + 2] : 0.f;
+                gv[s].w = (j + 3 < a.N) ? gr[s * kSweep + 3] : 0.f;
+            }
+        }
+        float4 v[SW];
+#pragma unroll
+        for (int s = 0; s < SW; ++s) {                      // Algorithm 1, line 5
+            xh[s].x = fmaf(-a.gamma, gv[s].x, xv[s].x);  v[s].x = xh[s].x + dv[s].x;
+            xh[s].y = fmaf(-a.gamma, gv[s].y, xv[s].y);  v[s].y = xh[s].y + dv[s].y;
+            xh[s].z = fmaf(-a.gamma, gv[s].z, xv[s].z);  v[s].z = xh[s].z + dv[s].z;
+            xh[s].w = fmaf(-a.gamma, gv[s].w, xv[s].w);  v[s].w = xh[s].w + dv[s].w;
+        }
+
+        uint8_t* msg_row = a.msg + (uint64_t)i * a.msg_row_bytes;
+        uint8_t* lds_row = lds_codes + (size_t)i * ROW_CODE_BYTES;
+        float* dout = a.delta + (uint64_t)i * a.ld + col0 + 4 * lane;
+
+#pragma unroll
+        for (int b = 0; b < BPT; ++b) {
+            const uint64_t bcol0 = col0 + (uint64_t)b * B;            // first column of the block
+            const bool block_live = FULL || (bcol0 < a.N);
+            const uint64_t m = FULL ? (uint64_t)B : (block_live ? (a.N - bcol0 < (uint64_t)B ? a.N - bcol0 : (uint64_t)B) : 0);
+            const uint32_t nwords = (uint32_t)((m * BITS + 31) / 32);
+            uint8_t* msg_blk = msg_row + (bcol0 / B) * MSG_BLOCK_BYTES;
+
+            if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
+                float mx = 0.f;
+#pragma unroll
+                for (int s = b * SPB; s < (b + 1) * SPB; ++s)
+                    mx = fmaxf(fmaxf(fmaxf(mx, fabsf(v[s].x)), fmaxf(fabsf(v[s].y), fabsf(v[s].z))), fabsf(v[s].w));
+                const float scale = wave_max(mx);
+                const float hl = 0.5f * (float)L;
+                const float unit = scale / (float)L;
+                const float inv = (scale > 0.f) ? hl / scale : 0.f;
+                if (lane == 0) {
+                    lds_units[i * BPT + b] = unit;
+                    if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
+                }
+#pragma unroll
+                for (int s = b * SPB; s < (b + 1) * SPB; ++s) {
+                    const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                    uint32_t rnd[4];
+                    philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, a.t_lo, kQuantStreamTag, a.seed_lo, a.seed_hi, rnd);
+                    uint32_t codes = 0;
+                    float4 dnew;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float vc = comp(v[s], c);
+                        float tt = fmaf(vc, inv, hl);
+                        tt = (tt > 0.f) ? tt : 0.f;
+                        tt = (tt < (float)L) ? tt : (float)L;
+                        const float q0 = floorf(tt);
+                        const float fr = tt - q0;
+                        const float u = (float)(rnd[c] >> 8) * (1.0f / 16777216.0f);
+                        int q = (int)q0 + ((u < fr) ? 1 : 0);
+                        q = q < L ? q : L;
+                        if (!(scale > 0.f)) q = 0;
+                        float cv = (float)(2 * q - L) * unit;
+                        if (!FULL && !(j + c < a.N)) { q = 0; cv = 0.f; }
+                        codes |= (uint32_t)q << (BITS * c);
+                        set_comp(dnew, c, vc - cv);                  // line 6: delta = v - C[v]
+                    }
+                    *reinterpret_cast<float4*>(dout + s * kSweep) = dnew;
+                    using lane_t = typename CT::lane_t;
+                    reinterpret_cast<lane_t*>(lds_row)[s * kWave + lane] = (lane_t)codes;
+                    const int in_blk = (s - b * SPB) * kWave + lane;  // lane-slot inside the block
+                    const uint32_t word = (uint32_t)in_blk * (uint32_t)sizeof(lane_t) / 4u;
+                    if (FULL || word < nwords)
+                        reinterpret_cast<lane_t*>(msg_blk + 4)[in_blk] = (lane_t)codes;
+                }
+            } else if constexpr (KIND == DS_COMP_SIGN_MEANABS) {
+                // balanced pairwise tree over the block: inside the lane, across lanes, across sweeps
+                float part[SPB];
+#pragma unroll
+                for (int s = 0; s < SPB; ++s) {
+                    const float4& q = v[b * SPB + s];
+                    part[s] = wave_sum_tree((fabsf(q.x) + fabsf(q.y)) + (fabsf(q.z) + fabsf(q.w)));
+                }
+#pragma unroll
+                for (int w = 1; w < SPB; w <<= 1)
+#pragma unroll
+                    for (int s = 0; s + w < SPB; s += 2 * w) part[s] = part[s] + part[s + w];
+                const float scale = block_live ? part[0] / (float)m : 0.f;
+                if (lane == 0) {
+                    lds_units[i * BPT + b] = scale;
+                    if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
+                }
+#pragma unroll
+                for (int s = b * SPB; s < (b + 1) * SPB; ++s) {
+                    const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                    uint32_t nib = 0;
+                    float4 dnew;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float vc = comp(v[s], c);
+                        uint32_t neg = __float_as_uint(vc) >> 31;
+                        float cv = neg ? -scale : scale;
+                        if (!FULL && !(j + c < a.N)) { neg = 0; cv = 0.f; }
+                        nib |= neg << c;
+                        set_comp(dnew, c, vc - cv);
+                    }
+                    *reinterpret_cast<float4*>(dout + s * kSweep) = dnew;
+                    uint32_t word = nib << (4 * (lane & 7));          // 8 lanes share one 32-bit word
+                    word |= __shfl_xor(word, 1);
+                    word |= __shfl_xor(word, 2);
+                    word |= __shfl_xor(word, 4);
+                    if ((lane & 7) == 0) {
+                        reinterpret_cast<uint32_t*>(lds_row)[s * 8 + (lane >> 3)] = word;
+                        const uint32_t widx = (uint32_t)(s - b * SPB) * 8u + (uint32_t)(lane >> 3);
+                        if (FULL || widx < nwords) reinterpret_cast<uint32_t*>(msg_blk + 4)[widx] = word;
+                    }
+                }
+            } else {   // DS_COMP_IDENTITY: C[v] = v, delta = 0, the message is v itself
+#pragma unroll
+                for (int s = b * SPB; s < (b + 1) * SPB; ++s) {
+                    const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                    float4 dnew;
+                    dnew.x = v[s].x - v[s].x; dnew.y = v[s].y - v[s].y; dnew.z = v[s].z - v[s].z; dnew.w = v[s].w - v[s].w;
+                    *reinterpret_cast<float4*>(dout + s * kSweep) = dnew;
+                    reinterpret_cast<float4*>(lds_row)[s * kWave + lane] = v[s];
+                    float* mrow = reinterpret_cast<float*>(msg_row);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (FULL || j + c < a.N) mrow[j + c] = comp(v[s], c);
+                }
+            }
+        }
+    }
+
+    // ---- phase 2 for one row: gossip on the decoded neighbours (Algorithm 1, line 9) ----------
+    template <bool FULL>
+    static __device__ __forceinline__ void gossip_row(const TileArgs& a, int i, uint64_t col0, int lane,
+                                                      const uint8_t* lds_codes, const float* lds_units,
+                                                      const float4 (&xh)[SW]) {
+        const int e0 = a.rowptr[i], e1 = a.rowptr[i + 1];
+        float* xout = a.x + (uint64_t)i * a.ld + col0 + 4 * lane;
+#pragma unroll
+        for (int s = 0; s < SW; ++s) {
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int e = e0; e < e1; ++e) {
+                const int nb = a.col[e];
+                const float w = a.coef[e];
+                const uint8_t* nrow = lds_codes + (size_t)nb * ROW_CODE_BYTES;
+                if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
+                    using lane_t = typename CT::lane_t;
+                    const uint32_t codes = reinterpret_cast<const lane_t*>(nrow)[s * kWave + lane];
+                    const float unit = lds_units[nb * BPT + s / SPB];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int q = (int)((codes >> (BITS * c)) & (uint32_t)L);
+                        acc[c] = fmaf(w, (float)(2 * q - L) * unit, acc[c]);
+                    }
+                } else if constexpr (KIND == DS_COMP_SIGN_MEANABS) {
+                    const uint32_t word = reinterpret_cast<const uint32_t*>(nrow)[s * 8 + (lane >> 3)];
+                    const uint32_t nib = word >> (4 * (lane & 7));
+                    const float scale = lds_units[nb * BPT + s / SPB];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) acc[c] = fmaf(w, ((nib >> c) & 1u) ? -scale : scale, acc[c]);
+                } else {
+                    const float4 cv = reinterpret_cast<const float4*>(nrow)[s * kWave + lane];
+                    acc[0] = fmaf(w, cv.x, acc[0]); acc[1] = fmaf(w, cv.y, acc[1]);
+                    acc[2] = fmaf(w, cv.z, acc[2]); acc[3] = fmaf(w, cv.w, acc[3]);
+                }
+            }
+            float4 xn;
+            xn.x = fmaf(a.eta, acc[0], xh[s].x); xn.y = fmaf(a.eta, acc[1], xh[s].y);
+            xn.z = fmaf(a.eta, acc[2], xh[s].z); xn.w = fmaf(a.eta, acc[3], xh[s].w);
+            if (!FULL) {                                             // keep the pitch padding at zero
+                const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                if (!(j + 0 < a.N)) xn.x = 0.f;
+                if (!(j + 1 < a.N)) xn.y = 0.f;
+                if (!(j + 2 < a.N)) xn.z = 0.f;
+                if (!(j + 3 < a.N)) xn.w = 0.f;
+            }
+            *reinterpret_cast<float4*>(xout + s * kSweep) = xn;
+        }
+    }
+
+    // Re-forms xh from x and g (used when a wave owns more rows than it can hold in registers).
+    template <bool FULL>
+    static __device__ __forceinline__ void reload_xh(const TileArgs& a, int i, uint64_t col0, int lane, float4 (&xh)[SW]) {
+        const float* xr = a.x + (uint64_t)i * a.ld + col0 + 4 * lane;
+        const float* gr = a.g + (uint64_t)i * a.g_ld + col0 + 4 * lane;
+#pragma unroll
+        for (int s = 0; s < SW; ++s) {
+            const float4 xv = *reinterpret_cast<const float4*>(xr + s * kSweep);
+            float4 gv;
+            if (FULL) {
+                gv = *reinterpret_cast<const float4*>(gr + s * kSweep);
+            } else {
+                const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                gv.x = (j + 0 < a.N) ? gr[s * kSweep + 0] : 0.f;
+                gv.y = (j + 1 < a.N) ? gr[s * kSweep + 1] : 0.f;
+                gv.z = (j + 2 < a.N) ? gr[s * kSweep + 2] : 0.f;
+                gv.w = (j + 3 < a.N) ? gr[s * kSweep + 3] : 0.f;
+            }
+            xh[s].x = fmaf(-a.gamma, gv.x, xv.x); xh[s].y = fmaf(-a.gamma, gv.y, xv.y);
+            xh[s].z = fmaf(-a.gamma, gv.z, xv.z); xh[s].w = fmaf(-a.gamma, gv.w, xv.w);
+        }
+    }
+
+    template <int RPW, bool FULL>
+    static __device__ __forceinline__ void run(const TileArgs& a, int rpw_runtime, uint64_t col0, uint8_t* lds) {
+        const int lane = threadIdx.x & (kWave - 1);
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        uint8_t* lds_codes = lds;
+        float* lds_units = reinterpret_cast<float*>(lds + (size_t)a.n * ROW_CODE_BYTES);
+        if constexpr (RPW > 0) {
+            float4 xh[RPW][SW];
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) {
+                const int i = wave + r * NW;
+                if (i < a.n) compress_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh[r]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < RPW; ++r) {
+                const int i = wave + r * NW;
+                if (i < a.n) gossip_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh[r]);
+            }
+        } else {
+            float4 xh[SW];
+            for (int r = 0; r < rpw_runtime; ++r) {
+                const int i = wave + r * NW;
+                if (i < a.n) compress_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh);
+            }
+            __syncthreads();
+            for (int r = 0; r < rpw_runtime; ++r) {
+                const int i = wave + r * NW;
+                if (i < a.n) {
+                    reload_xh<FULL>(a, i, col0, lane, xh);
+                    gossip_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh);
+                }
+            }
+        }
+    }
+};
+
+template <int KIND, int BITS, int B, int SW, int NW, int RPW>
+__global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int rpw_runtime) {
+    using T = Tile<KIND, BITS, B, SW, NW>;
+    extern __shared__ __align__(16) uint8_t lds[];
+    const uint64_t col0 = (uint64_t)blockIdx.x * T::TC;
+    if (col0 + T::TC <= a.N) T::template run<RPW, true>(a, rpw_runtime, col0, lds);
+    else                     T::template run<RPW, false>(a, rpw_runtime, col0, lds);
+}
+
+template <int KIND, int BITS, int B, int SW, int NW, int RPW>
+void launch_tile(const TileArgs& a, int rpw_runtime, hipStream_t stream) {
+    using T = Tile<KIND, BITS, B, SW, NW>;
+    const unsigned tiles = (unsigned)((a.N + T::TC - 1) / T::TC);
+    const size_t lds = T::lds_bytes(a.n);
+    auto kern = fused_tile_kernel<KIND, BITS, B, SW, NW, RPW>;
+    static bool attr_set = false;
+    if (lds > 48 * 1024 && !attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * kWave), lds, stream, a, rpw_runtime);
+}
+
+template <int KIND, int BITS, int B, int SW, int NW, int RPW>
+TilePlan make_plan(const char* name) {
+    TilePlan p;
+    p.name = name;
+    p.launch = &launch_tile<KIND, BITS, B, SW, NW, RPW>;
+    p.tile_cols = SW * kSweep;
+    p.waves = NW;
+    p.rows_per_wave = RPW;
+    return p;
+}
+
+constexpr size_t kMaxLds = 160 * 1024;
+
+// Variant table for one (KIND, BITS, B): picks waves per workgroup and rows per wave from n.
+template <int KIND, int BITS, int B>
+bool pick_for_block(int n, TilePlan& plan, std::string& err) {
+    constexpr int SW = (B / kSweep) < 1 ? 1 : (B / kSweep);    // one scale block per tile
+    using T8 = Tile<KIND, BITS, B, SW, 8>;
+    if (T8::lds_bytes(n) > kMaxLds) {
+        err = "n is too large for the fused tile kernel: the codes of all n rows of one tile must fit in 160 KB of LDS";
+        return false;
+    }
+    if constexpr (SW >= 8) {
+        // a 2048-column block needs 32+ registers per lane for v alone: 8-wave workgroups only
+        if (n <= 8) plan = make_plan<KIND, BITS, B, SW, 8, 1>("tile/8w/1row");
+        else {
+            plan = make_plan<KIND, BITS, B, SW, 8, 0>("tile/8w/looped");
+            plan.rows_per_wave = (n + 7) / 8;
+        }
+    } else {
+        if (n <= 8)       plan = make_plan<KIND, BITS, B, SW, 8, 1>("tile/8w/1row");
+        else if (n <= 16) plan = make_plan<KIND, BITS, B, SW, 16, 1>("tile/16w/1row");
+        else if (n <= 32 && SW <= 4) plan = make_plan<KIND, BITS, B, SW, 16, 2>("tile/16w/2rows");
+        else if (n <= 64 && SW <= 2) plan = make_plan<KIND, BITS, B, SW, 16, 4>("tile/16w/4rows");
+        else {
+            plan = make_plan<KIND, BITS, B, SW, 16, 0>("tile/16w/looped");
+            plan.rows_per_wave = (n + 15) / 16;
+        }
+    }
+    return true;
+}
+
+template <int KIND, int BITS>
+bool pick_for_kind(int block, int n, TilePlan& plan, std::string& err) {
+    switch (block) {
+        case 256:  return pick_for_block<KIND, BITS, 256>(n, plan, err);
+        case 512:  return pick_for_block<KIND, BITS, 512>(n, plan, err);
+        case 1024: return pick_for_block<KIND, BITS, 1024>(n, plan, err);
+        case 2048: return pick_for_block<KIND, BITS, 2048>(n, plan, err);
+        default: err = "block must be a power of two between 256 and 2048"; return false;
+    }
+}
+
+}  // namespace
+
+bool choose_tile_plan(const ds_config& cfg, int /*max_degree*/, TilePlan& plan, std::string& err) {
+    switch (cfg.comp.kind) {
+        case DS_COMP_QUANT_MAXABS:
+            if (cfg.comp.bits == 4) return pick_for_kind<DS_COMP_QUANT_MAXABS, 4>(cfg.comp.block, cfg.n, plan, err);
+            if (cfg.comp.bits == 2) return pick_for_kind<DS_COMP_QUANT_MAXABS, 2>(cfg.comp.block, cfg.n, plan, err);
+            err = "bits must be 2 or 4";
+            return false;
+        case DS_COMP_SIGN_MEANABS:
+            return pick_for_kind<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, cfg.n, plan, err);
+        case DS_COMP_IDENTITY:
+            return pick_for_block<DS_COMP_IDENTITY, 32, 256>(cfg.n, plan, err);
+        default:
+            err = "no tile kernel for this compressor";
+            return false;
+    }
+}
+
+}  // namespace dsq

@@ -1,0 +1,439 @@
+"""GPU parity: libdsq (through its C ABI) against the CPU oracle, element by element.
+
+Bar (from the benchmark spec): messages -- scales, packed codes, top-k index/value pairs -- are
+compared bit for bit; x and delta must agree within 1e-6 relative per element per step
+(|a-b| <= 1e-6 max(|a|,|b|) + 1e-12, the floor only covering exact and signed zeros) and within
+1e-5 relative L2 after a whole run.  The kernels are written to reproduce the oracle's fp32
+expression order, so the tests also report how many elements differ in any bit at all.
+"""
+import os
+import sys
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1907_07346_amd import binding as b
+from paper_1907_07346_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL, FLOOR = 1e-6, 1e-12
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def dense_W(w: wl.Config):
+    return oracle.ring_matrix(w.n) if w.topo == wl.TOPO_RING else oracle.torus_matrix(*w.torus)
+
+
+def oracle_state(w: wl.Config, W=None, **kw):
+    return oracle.OracleState(n=w.n, N=w.N, W=dense_W(w) if W is None else W, kind=w.kind, gamma=w.gamma,
+                              eta=w.eta, bits=w.bits, block=w.block, k=w.k, seed=w.seed, **kw)
+
+
+def assert_close(name, got, want):
+    got64, want64 = got.astype(np.float64), want.astype(np.float64)
+    bound = REL * np.maximum(np.abs(got64), np.abs(want64)) + FLOOR
+    bad = np.abs(got64 - want64) > bound
+    nbits = int((got.view(np.uint32) != want.view(np.uint32)).sum())
+    if bad.any():
+        idx = np.argwhere(bad)[:5]
+        raise AssertionError(f"{name}: {int(bad.sum())} of {bad.size} elements outside 1e-6 relative; first at "
+                             f"{idx.tolist()}: got {got[tuple(idx[0])]!r} want {want[tuple(idx[0])]!r}; "
+                             f"{nbits} differ bitwise")
+    return nbits
+
+
+def upload(g: np.ndarray, pitch=None):
+    t = torch.from_numpy(np.ascontiguousarray(g)).cuda()
+    if pitch is None:
+        pitch = (g.shape[1] + 3) // 4 * 4                  # the library wants 16-byte aligned rows
+    if pitch != g.shape[1]:
+        buf = torch.zeros((g.shape[0], pitch), dtype=torch.float32, device="cuda")
+        buf[:, :g.shape[1]] = t
+        return buf
+    return t
+
+
+def lock_step(w: wl.Config, steps, W=None, start="random", pitch=None, bitwise=True, csr=None):
+    """Each step: both sides start from the oracle's state, take one step, everything is compared."""
+    if csr is not None:
+        cfg, keep = b.make_config(w.n, w.N, wl.TOPO_CSR, w.kind, w.gamma, w.eta, bits=w.bits, block=w.block,
+                                  k=w.k, seed=w.seed, W_csr=csr)
+        ds = b.DeepSqueeze(cfg, keep)
+    else:
+        ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w, W)
+    if start == "random":
+        st.x, st.delta = wl.random_state(w, seed=17)
+    c = wl.centres(w) if w.grad == "quadratic" else None
+    total_bits = 0
+    for t in range(steps):
+        ds.ds_write_state(st.x, st.delta, st.t)
+        g = wl.gradient(w, st.t, st.x, c)
+        gd = upload(g, pitch)
+        ds.ds_step(gd)
+        _, msg = oracle.step(st, g, want_cv=False)
+        x, d = ds.ds_read_state()
+        gmsg = ds.ds_read_messages()
+        assert np.array_equal(gmsg, msg), f"{w.name} step {t}: packed messages differ in " \
+            f"{int((gmsg != msg).sum())} bytes (first at {int(np.argmax(gmsg != msg))})"
+        total_bits += assert_close(f"{w.name} step {t} x", x, st.x)
+        total_bits += assert_close(f"{w.name} step {t} delta", d, st.delta)
+        assert ds.ds_step_count() == st.t
+    if bitwise:
+        assert total_bits == 0, f"{w.name}: {total_bits} state elements differ bitwise from the oracle"
+    ds.ds_destroy()
+    return total_bits
+
+
+def free_run(w: wl.Config, steps, W=None):
+    """Both sides run on their own from x0 = delta0 = 0; compared after the last step (relative L2)."""
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w, W)
+    c = wl.centres(w) if w.grad == "quadratic" else None
+    for t in range(steps):
+        if w.grad == "quadratic":
+            xg, _ = ds.ds_read_state(want_delta=False)
+            g_gpu, g_cpu = wl.gradient(w, t, xg, c), wl.gradient(w, t, st.x, c)
+        else:
+            g_gpu = g_cpu = wl.gradient(w, t)
+        ds.ds_step(upload(g_gpu))
+        oracle.step(st, g_cpu, want_cv=False, want_msg=False)
+    x, d = ds.ds_read_state()
+    for name, got, want in (("x", x, st.x), ("delta", d, st.delta)):
+        num = np.linalg.norm(got.astype(np.float64) - want.astype(np.float64))
+        den = np.linalg.norm(want.astype(np.float64))
+        assert num <= 1e-5 * den, f"{w.name} free run {name}: relative L2 {num / den:.3e}"
+    nbits = int((x.view(np.uint32) != st.x.view(np.uint32)).sum() + (d.view(np.uint32) != st.delta.view(np.uint32)).sum())
+    ds.ds_destroy()
+    return nbits
+
+
+def small(kind, n, N, *, topo=wl.TOPO_RING, torus=(0, 0), bits=0, block=0, k=0, grad="normal", seed=5,
+          gamma=0.1, eta=0.4):
+    return wl.Config(f"small_k{kind}_n{n}_N{N}_b{bits}_B{block}", n=n, N=N, topo=topo, torus=torus, kind=kind,
+                     gamma=gamma, eta=eta, steps=3, grad=grad, grad_scale=0.5, bits=bits, block=block, k=k, seed=seed)
+
+
+# ------------------------------------------------------------------------------------ small shapes
+
+SMALL = [
+    small(wl.KIND_QUANT_MAXABS, 8, 512 * 5 + 37, bits=4, block=512),
+    small(wl.KIND_QUANT_MAXABS, 16, 1024 * 3 + 74, bits=2, block=1024),
+    small(wl.KIND_QUANT_MAXABS, 3, 256 * 4, bits=4, block=256),
+    small(wl.KIND_QUANT_MAXABS, 5, 100, bits=2, block=256),                       # one ragged block
+    small(wl.KIND_QUANT_MAXABS, 20, 1024 * 2 + 1, bits=4, block=1024),            # 2 rows per wave
+    small(wl.KIND_QUANT_MAXABS, 64, 512 * 3 + 300, bits=4, block=512, topo=wl.TOPO_TORUS2D, torus=(8, 8)),
+    small(wl.KIND_QUANT_MAXABS, 70, 512 * 2 + 5, bits=2, block=512),              # looped rows (re-read x, g)
+    small(wl.KIND_QUANT_MAXABS, 12, 2048 * 2 + 2000, bits=4, block=2048),         # 8-wave looped variant
+    small(wl.KIND_QUANT_MAXABS, 15, 512 * 4 + 4, bits=2, block=512, topo=wl.TOPO_TORUS2D, torus=(3, 5)),
+    small(wl.KIND_SIGN_MEANABS, 8, 256 * 7 + 40, block=256),
+    small(wl.KIND_SIGN_MEANABS, 16, 1024 * 2 + 999, block=1024),
+    small(wl.KIND_SIGN_MEANABS, 3, 2, block=256),
+    small(wl.KIND_SIGN_MEANABS, 33, 512 * 3 + 1, block=512),
+    small(wl.KIND_SIGN_MEANABS, 9, 2048 + 7, block=2048, topo=wl.TOPO_TORUS2D, torus=(3, 3)),
+    small(wl.KIND_IDENTITY, 8, 1000),
+    small(wl.KIND_IDENTITY, 40, 256 * 3 + 3),
+    small(wl.KIND_TOPK, 8, 30_011, k=300),
+    small(wl.KIND_TOPK, 32, 8192 * 2 + 5, k=163),
+    small(wl.KIND_TOPK, 3, 5, k=1),
+    small(wl.KIND_TOPK, 4, 9000, k=9000),                                          # k = N: everything is sent
+    small(wl.KIND_TOPK, 16, 20_000, k=200, topo=wl.TOPO_TORUS2D, torus=(4, 4)),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_lock_step_small_shapes(w):
+    say("case", w.name)
+    lock_step(w, steps=3)
+
+
+@pytest.mark.parametrize("w", [SMALL[0], SMALL[9], SMALL[16]], ids=lambda w: w.name)
+def test_gradient_pitch_larger_than_N(w):
+    say("case", w.name)
+    lock_step(w, steps=2, pitch=((w.N + 3) // 4) * 4 + 64)
+
+
+def test_general_graph_csr():
+    # symmetric doubly stochastic W of an irregular graph (degrees 2..5), given in CSR form
+    n = 10
+    r = np.random.default_rng(3)
+    A = np.zeros((n, n), bool)
+    for i in range(n):
+        A[i, (i + 1) % n] = A[(i + 1) % n, i] = True
+    for _ in range(6):
+        i, j = r.integers(0, n, 2)
+        if i != j:
+            A[i, j] = A[j, i] = True
+    deg = A.sum(1)
+    W = np.zeros((n, n))
+    for i in range(n):
+        for j in range(n):
+            if A[i, j]:
+                W[i, j] = 1.0 / (1 + max(deg[i], deg[j]))
+        W[i, i] = 1.0 - W[i].sum()
+    rp, co, va = oracle.dense_to_csr(W)
+    for w in (small(wl.KIND_QUANT_MAXABS, n, 512 * 3 + 9, bits=4, block=512),
+              small(wl.KIND_SIGN_MEANABS, n, 777, block=256),
+              small(wl.KIND_TOPK, n, 12_345, k=77)):
+        say("case", w.name)
+        # the oracle rounds W to fp32 exactly like the CSR handed to the library
+        lock_step(w, steps=2, W=W, csr=(rp, co, va.astype(np.float32)))
+
+
+# ------------------------------------------------------------------------------------ worked examples
+
+def test_hand_expanded_example_on_gpu(golden_dir):
+    # the two iterations of Algorithm 1 stored in tests/golden (n = 3 ring, N = 2, sign + mean-abs)
+    steps, cur = [], None
+    for line in open(os.path.join(golden_dir, "alg1_sign_ring3.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, rest = line.split(None, 1)
+        if key == "t":
+            cur = {}
+            steps.append(cur)
+            continue
+        cur[key] = np.array([[float(Fraction(tok)) for tok in row.split()] for row in rest.split("|")])
+    cfg, _ = b.make_config(3, 2, wl.TOPO_RING, wl.KIND_SIGN_MEANABS, 1.0, 0.5, block=256)
+    ds = b.DeepSqueeze(cfg)
+    for rec in steps:
+        ds.ds_step(upload(rec["g"].astype(np.float32), pitch=4))
+        x, d = ds.ds_read_state()
+        np.testing.assert_allclose(x, rec["x"], rtol=0, atol=2e-6)
+        np.testing.assert_allclose(d, rec["d"], rtol=0, atol=2e-6)
+        msg = ds.ds_read_messages().reshape(3, 8)
+        for i in range(3):
+            s = np.frombuffer(msg[i, :4].tobytes(), np.float32)[0]
+            word = int(np.frombuffer(msg[i, 4:].tobytes(), np.uint32)[0])
+            assert abs(s - rec["s"][i, 0]) < 2e-6
+            assert word == sum(1 << e for e in range(2) if rec["v"][i, e] < 0)
+
+
+def test_quantiser_worked_example_on_gpu(golden_dir):
+    rec = {l.split()[0]: l.split()[1:] for l in open(os.path.join(golden_dir, "quant_2bit_micro.txt")) if l[0] != "#"}
+    v = np.array([[float(t) for t in rec["v"]]] * 3, dtype=np.float32)
+    seen = set()
+    for seed in range(12):
+        cfg, _ = b.make_config(3, 4, wl.TOPO_RING, wl.KIND_QUANT_MAXABS, 0.0, 0.5, bits=2, block=1024, seed=seed)
+        ds = b.DeepSqueeze(cfg)
+        ds.ds_write_state(v, None, 0)
+        ds.ds_step(upload(np.zeros((3, 4), np.float32)))
+        _, d = ds.ds_read_state()
+        msg = ds.ds_read_messages().reshape(3, 8)
+        for i in range(3):
+            case = "up" if d[i, 2] < 0 else "down"
+            seen.add(case)
+            r = rec[case]
+            assert msg[i, :4].tobytes() == np.float32(3.0).tobytes()
+            assert msg[i, 4] == int(r[16], 16) and list(msg[i, 5:]) == [0, 0, 0]
+            np.testing.assert_array_equal(d[i], np.array([float(c) for c in r[11:15]], np.float32))
+    assert seen == {"up", "down"}
+
+
+# ------------------------------------------------------------------------------------ degenerate inputs
+
+def test_all_zero_and_denormal_blocks():
+    w = small(wl.KIND_QUANT_MAXABS, 4, 512 * 3, bits=4, block=512)
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w)
+    x = np.zeros((4, w.N), np.float32)
+    r = np.random.default_rng(2)
+    x[:, 512:1024] = (r.standard_normal((4, 512)) * 1e-40).astype(np.float32)     # denormal scale
+    x[:, 1024:] = r.standard_normal((4, 512)).astype(np.float32)
+    x[1, 1024:] = 0.0
+    x[2, 1030] = -0.0
+    st.x = x.copy()
+    ds.ds_write_state(x, None, 0)
+    g = np.zeros_like(x)
+    ds.ds_step(upload(g))
+    _, msg = oracle.step(st, g)
+    assert np.array_equal(ds.ds_read_messages(), msg)
+    xg, dg = ds.ds_read_state()
+    assert_close("x", xg, st.x)
+    assert_close("delta", dg, st.delta)
+    for kind, kw in ((wl.KIND_SIGN_MEANABS, dict(block=256)), (wl.KIND_TOPK, dict(k=40))):
+        w = small(kind, 4, 1500, **kw)
+        ds = b.DeepSqueeze.from_workload(w)
+        st = oracle_state(w)
+        g = np.zeros((4, 1500), np.float32)               # v == 0 everywhere: ties -> lowest indices
+        ds.ds_step(upload(g))
+        _, msg = oracle.step(st, g)
+        assert np.array_equal(ds.ds_read_messages(), msg)
+        xg, dg = ds.ds_read_state()
+        assert_close("x", xg, st.x)
+        assert_close("delta", dg, st.delta)
+
+
+def test_topk_ties_take_the_lower_index():
+    w = small(wl.KIND_TOPK, 3, 20_000, k=333)
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w)
+    r = np.random.default_rng(4)
+    x = r.integers(-3, 4, (3, w.N)).astype(np.float32)    # massive ties at the threshold
+    x[1] = 2.0                                            # a row of equal magnitudes
+    x[2, ::2] *= -1
+    st.x = x.copy()
+    ds.ds_write_state(x, None, 0)
+    g = np.zeros_like(x)
+    ds.ds_step(upload(g))
+    _, msg = oracle.step(st, g)
+    gm = ds.ds_read_messages()
+    assert np.array_equal(gm, msg)
+    pairs = np.frombuffer(gm.tobytes(), dtype=np.dtype([("j", "<u4"), ("v", "<f4")])).reshape(3, w.k)
+    assert list(pairs["j"][1]) == list(range(w.k))
+    xg, dg = ds.ds_read_state()
+    assert_close("x", xg, st.x)
+    assert_close("delta", dg, st.delta)
+
+
+# ------------------------------------------------------------------------------------ API behaviour
+
+def test_api_errors_and_restart():
+    w = small(wl.KIND_QUANT_MAXABS, 8, 512 * 4 + 3, bits=4, block=512)
+    ds = b.DeepSqueeze.from_workload(w)
+    assert ds.ds_plan_name().startswith("tile/")
+    buf = np.empty(b.ds_message_bytes(ds.cfg), np.uint8)
+    import ctypes
+    assert b.lib().ds_read_messages(ds._h, buf.ctypes.data, buf.size, None) == b.DS_ESTATE
+    g = upload(wl.gradient(w, 0))
+    assert ds.ds_step_raw(0, w.N + 1, 0) == b.DS_EINVAL                         # NULL gradient
+    assert ds.ds_step_raw(g.data_ptr(), w.N - 1, 0) == b.DS_EINVAL              # pitch < N
+    assert ds.ds_step_raw(g.data_ptr() + 4, 2052, 0) == b.DS_EINVAL             # misaligned
+    assert "aligned" in ds.ds_last_error()
+    assert ds.ds_step_count() == 0
+    # restart: 4 steps straight == 2 steps, state moved into a fresh handle, 2 more steps
+    gs = [wl.gradient(w, t) for t in range(4)]
+    gp = [upload(g_, pitch=2052) for g_ in gs]
+    for g_ in gp:
+        ds.ds_step(g_)
+    xa, da = ds.ds_read_state()
+    ds2 = b.DeepSqueeze.from_workload(w)
+    for g_ in gp[:2]:
+        ds2.ds_step(g_)
+    x2, d2 = ds2.ds_read_state()
+    ds3 = b.DeepSqueeze.from_workload(w)
+    ds3.ds_write_state(x2, d2, 2)
+    for g_ in gp[2:]:
+        ds3.ds_step(g_)
+    xb, db = ds3.ds_read_state()
+    assert np.array_equal(xa.view(np.uint32), xb.view(np.uint32)) and np.array_equal(da.view(np.uint32), db.view(np.uint32))
+    cfg, _ = b.make_config(8, 1024, wl.TOPO_RING, wl.KIND_SIGN_MEANABS, 0.1, 0.9, block=256)
+    big_eta = b.DeepSqueeze(cfg)
+    assert "eta" in big_eta.ds_last_error()
+
+
+def test_step_on_a_side_stream_and_determinism():
+    w = small(wl.KIND_TOPK, 8, 50_000, k=500)
+    outs = []
+    for _ in range(2):
+        ds = b.DeepSqueeze.from_workload(w)
+        s = torch.cuda.Stream()
+        gs = [upload(wl.gradient(w, t)) for t in range(3)]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s):
+            for g in gs:
+                ds.ds_step(g, s)
+        s.synchronize()
+        outs.append(ds.ds_read_state() + (ds.ds_read_messages(),))
+    for a_, b_ in zip(outs[0], outs[1]):
+        assert np.array_equal(a_, b_)
+
+
+# ------------------------------------------------------------------------------------ the five configurations
+
+def test_config0_full_size_100_steps():
+    w = wl.configs()[0]
+    say("case", w.name, "lock-step")
+    lock_step(w, steps=5, start="zero")
+    say("case", w.name, "free run")
+    nbits = free_run(w, w.steps)
+    say(w.name, "free run: state elements differing bitwise:", nbits)
+
+
+SCALED = [(1, 1024 * 37 + 74, None), (2, 256 * 201 + 40, None), (3, 512 * 21 + 100, None), (4, 150_001, None)]
+
+
+@pytest.mark.parametrize("idx,N,steps", SCALED, ids=lambda v: str(v))
+def test_configs_scaled_full_length_free_run(idx, N, steps):
+    w = wl.configs()[idx].scaled(N)
+    say("case", w.name, "free run", w.steps, "steps")
+    nbits = free_run(w, w.steps if steps is None else steps)
+    say(w.name, "free run: state elements differing bitwise:", nbits)
+    say("case", w.name, "lock-step")
+    lock_step(w, steps=3)
+
+
+def _full_size_inputs(w, idx):
+    say("case", w.name, "full size: generating inputs")
+    scale = 0.05
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234 + idx)
+    x0 = torch.randn((w.n, w.N), generator=gen, device="cuda").mul_(scale).cpu().numpy()
+    d0 = torch.randn((w.n, w.N), generator=gen, device="cuda").mul_(0.1 * scale).cpu().numpy()
+    g = wl.device_gradient(w, 3)
+    torch.cuda.synchronize()
+    return x0, d0, g
+
+
+def _gpu_one_step(w, x0, d0, g, t):
+    ds = b.DeepSqueeze.from_workload(w)
+    ds.ds_write_state(x0, d0, t)
+    say("case", w.name, "gpu step, plan", ds.ds_plan_name())
+    ds.ds_step(g)
+    x, d = ds.ds_read_state()
+    gm = ds.ds_read_messages()
+    ds.ds_destroy()
+    return x, d, gm
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_block_configs_full_size_one_step(idx):
+    """Full benchmark shapes in the launch configuration bench.py times; every output is compared."""
+    w = wl.configs()[idx]
+    x0, d0, g = _full_size_inputs(w, idx)
+    x, d, gm = _gpu_one_step(w, x0, d0, g, 3)
+    g_host = g.cpu().numpy()
+    del g
+    torch.cuda.empty_cache()
+    st = oracle_state(w, x=x0, delta=d0, t=3)
+    say("case", w.name, "oracle step")
+    _, msg = oracle.step(st, g_host, want_cv=False)
+    assert np.array_equal(gm, msg), f"{int((gm != msg).sum())} message bytes differ"
+    nb = assert_close("x", x, st.x) + assert_close("delta", d, st.delta)
+    say(w.name, "full size: state elements differing bitwise:", nb)
+    assert nb == 0
+
+
+def test_topk_config_full_size_sampled_rows():
+    """Config 4 at full size.  The oracle needs about a minute for all 32 rows, so it is run on
+    sampled rows: a worker and its two ring neighbours form a 3-row problem whose middle row has
+    exactly the neighbourhood it has in the full ring (top-k draws no random numbers, so row
+    numbering does not matter).  Messages and delta are compared for all three rows, x for the
+    worker in the middle."""
+    w = wl.configs()[4]
+    x0, d0, g = _full_size_inputs(w, 4)
+    x, d, gm = _gpu_one_step(w, x0, d0, g, 3)
+    gm = gm.reshape(w.n, -1)
+    third = np.float64(np.float32(1.0 / 3.0))
+    for target in (0, 13):
+        rows = sorted({(target - 1) % w.n, target, (target + 1) % w.n})   # ascending, as the full CSR row
+        mid = rows.index(target)
+        W = np.eye(3)
+        W[mid, :] = third
+        g_rows = g[rows].cpu().numpy()
+        sub = oracle.OracleState(n=3, N=w.N, W=W, kind=w.kind, gamma=w.gamma, eta=w.eta, k=w.k,
+                                 x=x0[rows].copy(), delta=d0[rows].copy(), t=3)
+        say("case", w.name, "oracle on rows", rows)
+        _, msg = oracle.step(sub, g_rows, want_cv=False)
+        assert np.array_equal(gm[rows].ravel(), msg), f"rows {rows}: messages differ"
+        nb = assert_close(f"delta rows {rows}", d[rows], sub.delta)
+        nb += assert_close(f"x row {target}", x[target:target + 1], sub.x[mid:mid + 1])
+        assert nb == 0

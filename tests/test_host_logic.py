@@ -1,0 +1,135 @@
+"""CPU-side checks of libdsq: the library loads without a GPU, exports every symbol the header
+declares, validates configurations, builds the ring / torus mixing matrices and sizes messages.
+No kernel is launched here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1907_07346_amd import binding as b
+from paper_1907_07346_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "dsq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ds_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert len(names) >= 14 and "ds_init" in names and "ds_step" in names and "ds_read_state" in names
+    L = b.lib()
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(b.EXPORTS) == names
+
+
+def test_validate_accepts_the_five_benchmark_configs():
+    for w in wl.configs():
+        cfg, _ = b.config_from_workload(w)
+        st, msg = b.ds_validate_config(cfg)
+        assert st == b.DS_OK, (w.name, msg)
+
+
+@pytest.mark.parametrize("kw,needle", [
+    (dict(n=0), "n must"), (dict(N=0), "N must"), (dict(n=2), "ring needs"),
+    (dict(topo=wl.TOPO_TORUS2D, n=8, torus=(2, 4)), "torus sides"),
+    (dict(topo=wl.TOPO_TORUS2D, n=10, torus=(3, 3)), "must equal n"),
+    (dict(bits=3), "bits"), (dict(block=300), "power of two"), (dict(block=128), "power of two"),
+    (dict(block=8192), "power of two"), (dict(kind=wl.KIND_TOPK, k=0), "k must"),
+    (dict(kind=wl.KIND_TOPK, k=10 ** 9), "k must"), (dict(gamma=float("nan")), "finite"),
+    (dict(eta=float("inf")), "finite"), (dict(kind=9), "unknown compressor"), (dict(topo=7), "unknown topology"),
+])
+def test_validate_rejects(kw, needle):
+    base = dict(n=8, N=4096, topo=wl.TOPO_RING, kind=wl.KIND_QUANT_MAXABS, gamma=0.1, eta=0.5, bits=4, block=512)
+    base.update(kw)
+    cfg, _ = b.make_config(**base)
+    st, msg = b.ds_validate_config(cfg)
+    assert st == b.DS_EINVAL and needle in msg, msg
+
+
+def _csr_cfg(W, **kw):
+    rp, co, va = oracle.dense_to_csr(W)
+    return b.make_config(W.shape[0], 1024, wl.TOPO_CSR, wl.KIND_IDENTITY, 0.1, 0.5, W_csr=(rp, co, va), **kw)
+
+
+def test_validate_csr_matrices():
+    W = oracle.ring_matrix(5)
+    cfg, keep = _csr_cfg(W)
+    assert b.ds_validate_config(cfg)[0] == b.DS_OK
+    bad = W.copy(); bad[0, 1] += 0.1                      # row sum != 1 and asymmetric
+    cfg, keep = _csr_cfg(bad)
+    assert b.ds_validate_config(cfg)[0] == b.DS_EINVAL
+    asym = 0.5 * np.eye(4) + 0.5 * np.roll(np.eye(4), 1, axis=1)   # doubly stochastic but not symmetric
+    cfg, keep = _csr_cfg(asym)
+    st, msg = b.ds_validate_config(cfg)
+    assert st == b.DS_EINVAL and "symmetric" in msg
+    neg = W.copy(); neg[0, 0] = -1 / 3; neg[0, 1] = 1.0; neg[1, 0] = 1.0; neg[1, 1] = -1 / 3
+    cfg, keep = _csr_cfg(neg)
+    assert b.ds_validate_config(cfg)[0] == b.DS_EINVAL
+    # missing diagonal entry
+    rp, co, va = oracle.dense_to_csr(W)
+    mask = np.ones(len(co), bool); mask[list(co[:3]).index(0)] = False
+    rp2 = rp.copy(); rp2[1:] -= 1
+    cfg, keep = b.make_config(5, 1024, wl.TOPO_CSR, wl.KIND_IDENTITY, 0.1, 0.5, W_csr=(rp2, co[mask], va[mask]))
+    assert b.ds_validate_config(cfg)[0] == b.DS_EINVAL
+
+
+@pytest.mark.parametrize("n", [3, 8, 16, 32])
+def test_ring_topology_matches_definition_and_spectrum(n):
+    cfg, _ = b.make_config(n, 4096, wl.TOPO_RING, wl.KIND_IDENTITY, 0.1, 0.5)
+    rp, co, va = b.ds_build_topology(cfg)
+    W = np.zeros((n, n))
+    for i in range(n):
+        assert list(co[rp[i]:rp[i + 1]]) == sorted(co[rp[i]:rp[i + 1]])      # ascending columns
+        W[i, co[rp[i]:rp[i + 1]]] = va[rp[i]:rp[i + 1]]
+    np.testing.assert_allclose(W, oracle.ring_matrix(n), atol=1e-7)
+    ev = np.sort(np.linalg.eigvalsh(W))
+    np.testing.assert_allclose(ev, np.sort(1 / 3 + 2 / 3 * np.cos(2 * np.pi * np.arange(n) / n)), atol=1e-6)
+
+
+def test_torus_topology_matches_definition():
+    cfg, _ = b.make_config(64, 4096, wl.TOPO_TORUS2D, wl.KIND_IDENTITY, 0.1, 0.4, torus=(8, 8))
+    rp, co, va = b.ds_build_topology(cfg)
+    W = np.zeros((64, 64))
+    for i in range(64):
+        assert rp[i + 1] - rp[i] == 5
+        W[i, co[rp[i]:rp[i + 1]]] = va[rp[i]:rp[i + 1]]
+    np.testing.assert_allclose(W, oracle.torus_matrix(8, 8), atol=1e-7)
+    cfg, _ = b.make_config(15, 4096, wl.TOPO_TORUS2D, wl.KIND_IDENTITY, 0.1, 0.4, torus=(3, 5))
+    rp, co, va = b.ds_build_topology(cfg)
+    W = np.zeros((15, 15))
+    for i in range(15):
+        W[i, co[rp[i]:rp[i + 1]]] = va[rp[i]:rp[i + 1]]
+    np.testing.assert_allclose(W, oracle.torus_matrix(3, 5), atol=1e-7)
+
+
+def test_message_sizes():
+    for w in wl.configs() + [wl.configs()[1].scaled(1024 * 3 + 74), wl.configs()[2].scaled(40)]:
+        cfg, _ = b.config_from_workload(w)
+        assert b.ds_message_bytes(cfg) == oracle.message_bytes(w.kind, w.n, w.N, w.bits, w.block, w.k)
+    # the figures quoted for the benchmark: 260 B per 512 4-bit codes, 260 B per 1024 2-bit codes, 36 B per 256 signs
+    c, _ = b.make_config(3, 512, wl.TOPO_RING, wl.KIND_QUANT_MAXABS, 0.1, 0.5, bits=4, block=512)
+    assert b.ds_message_bytes(c) == 3 * 260
+    c, _ = b.make_config(3, 1024, wl.TOPO_RING, wl.KIND_QUANT_MAXABS, 0.1, 0.5, bits=2, block=1024)
+    assert b.ds_message_bytes(c) == 3 * 260
+    c, _ = b.make_config(3, 256, wl.TOPO_RING, wl.KIND_SIGN_MEANABS, 0.1, 0.5, block=256)
+    assert b.ds_message_bytes(c) == 3 * 36
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    for idx, N in [(0, 1000), (1, 999), (2, 500), (3, 300), (4, 2000)]:
+        w = wl.configs()[idx].scaled(N)
+        c = wl.centres(w) if w.grad == "quadratic" else None
+        x = np.zeros((w.n, w.N), np.float32)
+        g1, g2 = wl.gradient(w, 3, x, c), wl.gradient(w, 3, x, c)
+        assert g1.shape == (w.n, N) and g1.dtype == np.float32
+        np.testing.assert_array_equal(g1, g2)
+        assert not np.array_equal(g1, wl.gradient(w, 4, x, c))
+    w = wl.configs()[4]
+    assert w.k == 255_570 and wl.configs()[1].N == 11_173_962
