@@ -378,7 +378,9 @@ def _full_size_inputs(w, idx):
     gen.manual_seed(1234 + idx)
     x0 = torch.randn((w.n, w.N), generator=gen, device="cuda").mul_(scale).cpu().numpy()
     d0 = torch.randn((w.n, w.N), generator=gen, device="cuda").mul_(0.1 * scale).cpu().numpy()
-    g = wl.device_gradient(w, 3)
+    pitch = (w.N + 3) // 4 * 4                              # rows must be 16-byte aligned
+    g = torch.zeros((w.n, pitch), dtype=torch.float32, device="cuda")
+    g[:, :w.N] = wl.device_gradient(w, 3)
     torch.cuda.synchronize()
     return x0, d0, g
 
@@ -400,7 +402,7 @@ def test_block_configs_full_size_one_step(idx):
     w = wl.configs()[idx]
     x0, d0, g = _full_size_inputs(w, idx)
     x, d, gm = _gpu_one_step(w, x0, d0, g, 3)
-    g_host = g.cpu().numpy()
+    g_host = np.ascontiguousarray(g[:, :w.N].cpu().numpy())
     del g
     torch.cuda.empty_cache()
     st = oracle_state(w, x=x0, delta=d0, t=3)
@@ -428,7 +430,7 @@ def test_topk_config_full_size_sampled_rows():
         mid = rows.index(target)
         W = np.eye(3)
         W[mid, :] = third
-        g_rows = g[rows].cpu().numpy()
+        g_rows = np.ascontiguousarray(g[rows][:, :w.N].cpu().numpy())
         sub = oracle.OracleState(n=3, N=w.N, W=W, kind=w.kind, gamma=w.gamma, eta=w.eta, k=w.k,
                                  x=x0[rows].copy(), delta=d0[rows].copy(), t=3)
         say("case", w.name, "oracle on rows", rows)
