@@ -43,6 +43,29 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 constexpr uint32_t kQuantStreamTag = 0x51554E54u;   // 4th counter word of the rounding stream
 
+// 16-byte streaming accesses.  x, g and delta are touched exactly once per step, so they are
+// marked non-temporal: on gfx950 that keeps the streams from displacing each other in L2 / MALL.
+#ifndef DSQ_NONTEMPORAL
+#define DSQ_NONTEMPORAL 1
+#endif
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld4(const float* p) {
+#if DSQ_NONTEMPORAL
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+#else
+    const f32x4 v = *reinterpret_cast<const f32x4*>(p);
+#endif
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4(float* p, const float4& v) {
+    const f32x4 w = {v.x, v.y, v.z, v.w};
+#if DSQ_NONTEMPORAL
+    __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(p));
+#else
+    *reinterpret_cast<f32x4*>(p) = w;
+#endif
+}
+
 // ---- wave64 reductions; every lane ends with the result ---------------------------------------
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -91,10 +114,10 @@ struct Tile {
         const float* gr = a.g + (uint64_t)i * a.g_ld + col0 + 4 * lane;
 #pragma unroll
         for (int s = 0; s < SW; ++s) {
-            xv[s] = *reinterpret_cast<const float4*>(xr + s * kSweep);
-            dv[s] = *reinterpret_cast<const float4*>(dr + s * kSweep);
+            xv[s] = ld4(xr + s * kSweep);
+            dv[s] = ld4(dr + s * kSweep);
             if (FULL) {
-                gv[s] = *reinterpret_cast<const float4*>(gr + s * kSweep);
+                gv[s] = ld4(gr + s * kSweep);
             } else {
                 const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
                 gv[s].x = (j + 0 < a.N) ? gr[s * kSweep + 0] : 0.f;
@@ -161,7 +184,7 @@ struct Tile {
                         codes |= (uint32_t)q << (BITS * c);
                         set_comp(dnew, c, vc - cv);                  // line 6: delta = v - C[v]
                     }
-                    *reinterpret_cast<float4*>(dout + s * kSweep) = dnew;
+                    st4(dout + s * kSweep, dnew);
                     using lane_t = typename CT::lane_t;
                     reinterpret_cast<lane_t*>(lds_row)[s * kWave + lane] = (lane_t)codes;
                     const int in_blk = (s - b * SPB) * kWave + lane;  // lane-slot inside the block
@@ -200,7 +223,7 @@ struct Tile {
                         nib |= neg << c;
                         set_comp(dnew, c, vc - cv);
                     }
-                    *reinterpret_cast<float4*>(dout + s * kSweep) = dnew;
+                    st4(dout + s * kSweep, dnew);
                     uint32_t word = nib << (4 * (lane & 7));          // 8 lanes share one 32-bit word
                     word |= __shfl_xor(word, 1);
                     word |= __shfl_xor(word, 2);
@@ -217,7 +240,7 @@ struct Tile {
                     const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
                     float4 dnew;
                     dnew.x = v[s].x - v[s].x; dnew.y = v[s].y - v[s].y; dnew.z = v[s].z - v[s].z; dnew.w = v[s].w - v[s].w;
-                    *reinterpret_cast<float4*>(dout + s * kSweep) = dnew;
+                    st4(dout + s * kSweep, dnew);
                     reinterpret_cast<float4*>(lds_row)[s * kWave + lane] = v[s];
                     float* mrow = reinterpret_cast<float*>(msg_row);
 #pragma unroll
@@ -273,7 +296,7 @@ struct Tile {
                 if (!(j + 2 < a.N)) xn.z = 0.f;
                 if (!(j + 3 < a.N)) xn.w = 0.f;
             }
-            *reinterpret_cast<float4*>(xout + s * kSweep) = xn;
+            st4(xout + s * kSweep, xn);
         }
     }
 
@@ -284,10 +307,10 @@ struct Tile {
         const float* gr = a.g + (uint64_t)i * a.g_ld + col0 + 4 * lane;
 #pragma unroll
         for (int s = 0; s < SW; ++s) {
-            const float4 xv = *reinterpret_cast<const float4*>(xr + s * kSweep);
+            const float4 xv = ld4(xr + s * kSweep);
             float4 gv;
             if (FULL) {
-                gv = *reinterpret_cast<const float4*>(gr + s * kSweep);
+                gv = ld4(gr + s * kSweep);
             } else {
                 const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
                 gv.x = (j + 0 < a.N) ? gr[s * kSweep + 0] : 0.f;
@@ -374,30 +397,40 @@ TilePlan make_plan(const char* name) {
 constexpr size_t kMaxLds = 160 * 1024;
 
 // Variant table for one (KIND, BITS, B): picks waves per workgroup and rows per wave from n.
+// Measured on MI355X: 8-wave workgroups whose waves each own several rows beat 16-wave ones,
+// because two or more workgroups then share a CU and one's gossip phase overlaps the other's
+// loads.  A wave keeps xh for all its rows in registers, so rows-per-wave * sweeps is capped.
+template <int KIND, int BITS, int B, int SW, int NW, int RPW>
+bool try_plan(int n, const char* name, TilePlan& plan) {
+    if constexpr (RPW * SW > (NW > 8 ? 8 : 16)) {
+        return false;                                          // would spill: xh alone needs 4*RPW*SW VGPRs
+    } else {
+        if (n > NW * RPW) return false;
+        plan = make_plan<KIND, BITS, B, SW, NW, RPW>(name);
+        return true;
+    }
+}
+
 template <int KIND, int BITS, int B>
 bool pick_for_block(int n, TilePlan& plan, std::string& err) {
-    constexpr int SW = (B / kSweep) < 1 ? 1 : (B / kSweep);    // one scale block per tile
+    constexpr int SW = (B <= kSweep) ? 2 : (B / kSweep);       // 256-column blocks: two blocks per tile
     using T8 = Tile<KIND, BITS, B, SW, 8>;
     if (T8::lds_bytes(n) > kMaxLds) {
         err = "n is too large for the fused tile kernel: the codes of all n rows of one tile must fit in 160 KB of LDS";
         return false;
     }
+    if (try_plan<KIND, BITS, B, SW, 8, 1>(n, "tile/8w/1row", plan)) return true;
+    if (try_plan<KIND, BITS, B, SW, 8, 2>(n, "tile/8w/2rows", plan)) return true;
+    if (try_plan<KIND, BITS, B, SW, 8, 4>(n, "tile/8w/4rows", plan)) return true;
+    if (try_plan<KIND, BITS, B, SW, 8, 8>(n, "tile/8w/8rows", plan)) return true;
+    if (try_plan<KIND, BITS, B, SW, 16, 2>(n, "tile/16w/2rows", plan)) return true;
+    if (try_plan<KIND, BITS, B, SW, 16, 4>(n, "tile/16w/4rows", plan)) return true;
     if constexpr (SW >= 8) {
-        // a 2048-column block needs 32+ registers per lane for v alone: 8-wave workgroups only
-        if (n <= 8) plan = make_plan<KIND, BITS, B, SW, 8, 1>("tile/8w/1row");
-        else {
-            plan = make_plan<KIND, BITS, B, SW, 8, 0>("tile/8w/looped");
-            plan.rows_per_wave = (n + 7) / 8;
-        }
+        plan = make_plan<KIND, BITS, B, SW, 8, 0>("tile/8w/looped");
+        plan.rows_per_wave = (n + 7) / 8;
     } else {
-        if (n <= 8)       plan = make_plan<KIND, BITS, B, SW, 8, 1>("tile/8w/1row");
-        else if (n <= 16) plan = make_plan<KIND, BITS, B, SW, 16, 1>("tile/16w/1row");
-        else if (n <= 32 && SW <= 4) plan = make_plan<KIND, BITS, B, SW, 16, 2>("tile/16w/2rows");
-        else if (n <= 64 && SW <= 2) plan = make_plan<KIND, BITS, B, SW, 16, 4>("tile/16w/4rows");
-        else {
-            plan = make_plan<KIND, BITS, B, SW, 16, 0>("tile/16w/looped");
-            plan.rows_per_wave = (n + 15) / 16;
-        }
+        plan = make_plan<KIND, BITS, B, SW, 16, 0>("tile/16w/looped");
+        plan.rows_per_wave = (n + 15) / 16;
     }
     return true;
 }
@@ -425,7 +458,7 @@ bool choose_tile_plan(const ds_config& cfg, int /*max_degree*/, TilePlan& plan, 
         case DS_COMP_SIGN_MEANABS:
             return pick_for_kind<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, cfg.n, plan, err);
         case DS_COMP_IDENTITY:
-            return pick_for_block<DS_COMP_IDENTITY, 32, 256>(cfg.n, plan, err);
+            return pick_for_block<DS_COMP_IDENTITY, 32, 512>(cfg.n, plan, err);
         default:
             err = "no tile kernel for this compressor";
             return false;
