@@ -44,7 +44,7 @@ def cpu_baseline(w, budget_s=12.0):
     import oracle
     from paper_1907_07346_amd import workloads as wl
     blk = w.block if w.block else 1024
-    Ns = min(w.N, max(blk, (2_000_000 // w.n) // blk * blk))
+    Ns = min(w.N, max(blk, (16_000_000 // w.n) // blk * blk))
     ws = w.scaled(Ns)
     W = oracle.ring_matrix(ws.n) if ws.topo == wl.TOPO_RING else oracle.torus_matrix(*ws.torus)
     st = oracle.OracleState(n=ws.n, N=ws.N, W=W, kind=ws.kind, gamma=ws.gamma, eta=ws.eta, bits=ws.bits,
@@ -57,7 +57,7 @@ def cpu_baseline(w, budget_s=12.0):
         oracle.step(st, gs[steps % 2], want_cv=False, want_msg=True)
         steps += 1
         el = time.perf_counter() - t0
-        if el > budget_s or steps >= 50:
+        if el > budget_s or steps >= 20:
             break
     return {"value": ws.n * ws.N * steps / el, "unit": "worker-param updates/s", "cores": 1, "kind": "oracle",
             "sample": f"first {Ns} of {w.N} columns, all {w.n} workers, {steps} steps in {el:.1f} s "
