@@ -136,11 +136,21 @@ ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_h
 ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t* bytes);
 
 /* Borrows the device arrays: row i of x starts at x_dev + i*ld.  Ownership stays with the
- * handle; columns >= N of each row are padding the caller must leave zero. */
+ * handle; columns >= N of each row are padding the caller must leave zero.  The contents are
+ * complete once the work enqueued so far on the stream of the last ds_step has finished (with
+ * DS_COMP_TOPK this call itself enqueues the last sparse update of x on that stream); call it
+ * again after later steps before reading x. */
 ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t* ld);
 
 /* Borrows the device message buffer (ds_message_bytes bytes, layout as above). */
 ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes);
+
+/* Diagnostics for DS_COMP_TOPK: the number of workers whose last ds_step found its top-k among the
+ * candidates collected while forming v (the fast path) instead of re-reading v (the exact fallback
+ * taken on the first step and whenever the threshold guess of the previous step was too high or a
+ * candidate slot overflowed).  Results are identical either way.  Synchronises; 0 for other
+ * compressors; DS_ESTATE before the first step. */
+ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count);
 
 /* Step counter t (number of ds_step calls since init or the value set by ds_write_state). */
 uint64_t ds_step_count(const ds_handle* h);

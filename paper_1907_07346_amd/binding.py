@@ -24,7 +24,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
-           "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy"]
+           "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
+           "ds_topk_candidate_rows"]
 
 
 class ds_comp(ctypes.Structure):
@@ -70,6 +71,7 @@ def lib() -> ctypes.CDLL:
         L.ds_state_ptrs.argtypes, L.ds_state_ptrs.restype = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), u64p], i32
         L.ds_message_ptr.argtypes, L.ds_message_ptr.restype = [vp, ctypes.POINTER(vp), u64p], i32
         L.ds_step_count.argtypes, L.ds_step_count.restype = [vp], u64
+        L.ds_topk_candidate_rows.argtypes, L.ds_topk_candidate_rows.restype = [vp, ctypes.POINTER(ctypes.c_uint32)], i32
         L.ds_plan_name.argtypes, L.ds_plan_name.restype = [vp], ctypes.c_char_p
         L.ds_last_error.argtypes, L.ds_last_error.restype = [vp], ctypes.c_char_p
         L.ds_destroy.argtypes, L.ds_destroy.restype = [vp], None
@@ -203,6 +205,11 @@ class DeepSqueeze:
         p, b = ctypes.c_void_p(), ctypes.c_uint64()
         self._check(lib().ds_message_ptr(self._h, ctypes.byref(p), ctypes.byref(b)), "ds_message_ptr")
         return p.value, b.value
+
+    def ds_topk_candidate_rows(self) -> int:
+        c = ctypes.c_uint32(0)
+        self._check(lib().ds_topk_candidate_rows(self._h, ctypes.byref(c)), "ds_topk_candidate_rows")
+        return int(c.value)
 
     def ds_step_count(self) -> int:
         return int(lib().ds_step_count(self._h))

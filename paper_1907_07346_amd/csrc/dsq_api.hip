@@ -1,5 +1,6 @@
 // C ABI of libdsq: handle life cycle, state transfer and the ds_step dispatcher.
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -21,6 +22,7 @@ struct ds_handle {
     int32_t* d_col = nullptr;
     float* d_coef = nullptr;
     dsq::TilePlan tile;
+    std::vector<dsq::TilePlan> tile_candidates;
     dsq::TopkState* topk = nullptr;
     std::string err;
     std::string plan_name;
@@ -49,10 +51,75 @@ void release(ds_handle* h) {
     if (h->x) (void)hipFree(h->x);
     if (h->delta) (void)hipFree(h->delta);
     if (h->msg) (void)hipFree(h->msg);
-    if (h->d_rowptr) (void)hipFree(h->d_rowptr);
-    if (h->d_col) (void)hipFree(h->d_col);
-    if (h->d_coef) (void)hipFree(h->d_coef);
+    if (h->d_rowptr) (void)hipFree(h->d_rowptr);   // d_col and d_coef point into the same allocation
     delete h;
+}
+
+dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
+    dsq::TileArgs a{};
+    a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
+    a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
+    a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes;
+    a.n = h->cfg.n; a.nnz = (int)h->graph.col.size();
+    a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
+    a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32); a.t_lo = (uint32_t)h->t;
+    return a;
+}
+
+// Row pitch candidates (floats added to N rounded up to kPitchAlign).  A tile kernel has all n rows
+// of a column window in flight at once, so how the row pitch falls on the HBM channel hash decides
+// up to 12 % of the achieved bandwidth, and the best pitch differs between shapes and GPUs.  ds_init
+// times the real kernel on the (still all-zero) state for each candidate and keeps the fastest.
+const uint64_t kPitchCandidates[] = {0, 2560, 4096, 6656, 8192, 12288};
+constexpr uint64_t kMaxPitchSkew = 12288;
+
+// Times `plan` at the current h->ld on the all-zero state (3 launches after a warm-up); < 0 on failure.
+float time_plan(ds_handle* h, const dsq::TilePlan& plan, const float* g, hipEvent_t e0, hipEvent_t e1) {
+    const dsq::TileArgs a = tile_args(h, g, h->ld);
+    plan.launch(a, plan.rows_per_wave, nullptr);
+    (void)hipEventRecord(e0, nullptr);
+    for (int r = 0; r < 3; ++r) plan.launch(a, plan.rows_per_wave, nullptr);
+    (void)hipEventRecord(e1, nullptr);
+    float ms = 0.f;
+    if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.f;
+    return ms;
+}
+
+// Picks the launch shape (at the default pitch) and then the row pitch for it by timing the real
+// kernel.  Returns the chosen skew and sets h->tile; leaves x, delta and the messages zeroed.
+uint64_t autotune(ds_handle* h, uint64_t base_ld, size_t state_bytes, size_t msg_bytes) {
+    float* g = nullptr;
+    if (hipMalloc(&g, state_bytes) != hipSuccess) { (void)hipGetLastError(); return dsq::kPitchSkew; }
+    hipEvent_t e0, e1;
+    bool ok = hipMemset(g, 0, state_bytes) == hipSuccess && hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+    uint64_t best_skew = dsq::kPitchSkew;
+    if (ok) {
+        float best_ms = 1e30f;
+        h->ld = base_ld + dsq::kPitchSkew;
+        for (const dsq::TilePlan& plan : h->tile_candidates) {
+            const float ms = time_plan(h, plan, g, e0, e1);
+            if (ms < 0.f) { ok = false; break; }
+            if (ms < best_ms) { best_ms = ms; h->tile = plan; }
+        }
+        for (uint64_t skew : kPitchCandidates) {
+            if (!ok) break;
+            if (skew == dsq::kPitchSkew) continue;             // timed above
+            h->ld = base_ld + skew;
+            const float ms = time_plan(h, h->tile, g, e0, e1);
+            if (ms < 0.f) { ok = false; break; }
+            if (ms < best_ms) { best_ms = ms; best_skew = skew; }
+        }
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+    }
+    (void)hipDeviceSynchronize();
+    (void)hipFree(g);
+    (void)hipMemset(h->x, 0, state_bytes);
+    (void)hipMemset(h->delta, 0, state_bytes);
+    (void)hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4);
+    (void)hipDeviceSynchronize();
+    if (!ok) h->tile = h->tile_candidates.front();
+    return ok ? best_skew : dsq::kPitchSkew;
 }
 
 // Plain streaming copy, one 16-byte non-temporal load and store per lane, one-shot grid: the
@@ -91,17 +158,18 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     h->cfg = *cfg;
     if (dsq::build_graph(cfg, h->graph, err) != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(DS_EINVAL); }
     h->cfg.W_rowptr = nullptr; h->cfg.W_col = nullptr; h->cfg.W_val = nullptr;   // the copy lives in graph
-    h->ld = (cfg->N + dsq::kPitchAlign - 1) / dsq::kPitchAlign * dsq::kPitchAlign;
+    const uint64_t base_ld = (cfg->N + dsq::kPitchAlign - 1) / dsq::kPitchAlign * dsq::kPitchAlign;
+    h->ld = base_ld + kMaxPitchSkew;                       // allocation pitch; the working pitch is fixed below
     h->msg_row_bytes = dsq::message_row_bytes(cfg);
 
     if (cfg->comp.kind == DS_COMP_TOPK) {
         h->plan_name = "topk/radix-select";
     } else {
-        if (!dsq::choose_tile_plan(h->cfg, h->graph.max_degree, h->tile, err)) {
+        if (!dsq::choose_tile_plans(h->cfg, (int)h->graph.col.size(), h->tile_candidates, err)) {
             std::fprintf(stderr, "ds_init: %s\n", err.c_str());
             return bail(DS_EINVAL);
         }
-        h->plan_name = h->tile.name;
+        h->tile = h->tile_candidates.front();
     }
 
     hipError_t e = hipGetDevice(&h->device);
@@ -109,12 +177,14 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     const size_t state_bytes = (size_t)cfg->n * h->ld * sizeof(float);
     const size_t nnz = h->graph.col.size();
     const size_t msg_bytes = (size_t)cfg->n * h->msg_row_bytes;
-    hipError_t errs[6] = {
+    // rowptr | col | coef as one contiguous array of 32-bit words
+    hipError_t errs[4] = {
         hipMalloc(&h->x, state_bytes), hipMalloc(&h->delta, state_bytes), hipMalloc(&h->msg, msg_bytes ? msg_bytes : 4),
-        hipMalloc(&h->d_rowptr, (cfg->n + 1) * sizeof(int32_t)), hipMalloc(&h->d_col, nnz * sizeof(int32_t)),
-        hipMalloc(&h->d_coef, nnz * sizeof(float))};
+        hipMalloc(&h->d_rowptr, (cfg->n + 1 + 2 * nnz) * sizeof(int32_t))};
     for (hipError_t ee : errs)
         if (ee != hipSuccess) { std::fprintf(stderr, "ds_init: hipMalloc: %s\n", hipGetErrorString(ee)); return bail(ee == hipErrorOutOfMemory ? DS_ENOMEM : DS_EHIP); }
+    h->d_col = h->d_rowptr + cfg->n + 1;
+    h->d_coef = reinterpret_cast<float*>(h->d_col + nnz);
     bool ok = hipMemset(h->x, 0, state_bytes) == hipSuccess && hipMemset(h->delta, 0, state_bytes) == hipSuccess &&
               hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4) == hipSuccess &&
               hipMemcpy(h->d_rowptr, h->graph.rowptr.data(), (cfg->n + 1) * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
@@ -122,6 +192,21 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
               hipMemcpy(h->d_coef, h->graph.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice) == hipSuccess &&
               hipDeviceSynchronize() == hipSuccess;
     if (!ok) { std::fprintf(stderr, "ds_init: device initialisation failed\n"); return bail(DS_EHIP); }
+
+    // working row pitch: DSQ_PITCH_SKEW=<floats, multiple of 4, <= 12288> pins it; otherwise large tile-kernel
+    // problems are timed per candidate, everything else takes the default
+    uint64_t skew = dsq::kPitchSkew;
+    const char* pin = std::getenv("DSQ_PITCH_SKEW");
+    if (pin && *pin) {
+        const unsigned long long v = std::strtoull(pin, nullptr, 10);
+        if (v <= kMaxPitchSkew && (v & 3) == 0) skew = v;
+    } else if (cfg->comp.kind != DS_COMP_TOPK && (uint64_t)cfg->n * cfg->N >= (32ull << 20)) {
+        skew = autotune(h, base_ld, state_bytes, msg_bytes);
+    }
+    h->ld = base_ld + skew;
+    if (cfg->comp.kind != DS_COMP_TOPK)
+        h->plan_name = std::string(h->tile.name) + "/" + std::to_string(h->tile.sweeps) + "sweeps";
+    h->plan_name += "/pitch+" + std::to_string(skew);
 
     if (cfg->comp.kind == DS_COMP_TOPK) {
         const ds_status st = dsq::topk_create(h->cfg, h->ld, &h->topk, err);
@@ -148,12 +233,7 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
         const ds_status st = dsq::topk_step(h->topk, a, h->graph, stream, h->err);
         if (st != DS_OK) return st;
     } else {
-        dsq::TileArgs a{};
-        a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
-        a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
-        a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes; a.n = h->cfg.n;
-        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
-        a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32); a.t_lo = (uint32_t)h->t;
+        const dsq::TileArgs a = tile_args(h, g_dev, g_ld);
         h->tile.launch(a, h->tile.rows_per_wave, stream);
     }
     DSQ_HIP(h, hipGetLastError());
@@ -166,6 +246,7 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
 ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host) {
     if (!h) return DS_EINVAL;
     if (!x_host && !delta_host) return fail(h, DS_EINVAL, "nothing to read");
+    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
     if (x_host) DSQ_HIP(h, hipMemcpy2D(x_host, row, h->x, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
@@ -175,6 +256,7 @@ ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host) {
 
 ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_host, uint64_t t) {
     if (!h) return DS_EINVAL;
+    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
     if (x_host) DSQ_HIP(h, hipMemcpy2D(h->x, pitch, x_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
@@ -197,6 +279,8 @@ ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t*
 
 ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t* ld) {
     if (!h) return DS_EINVAL;
+    // top-k keeps the sparse part of the last gossip update pending; complete x before lending it
+    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
     if (x_dev) *x_dev = h->x;
     if (delta_dev) *delta_dev = h->delta;
     if (ld) *ld = h->ld;
@@ -208,6 +292,14 @@ ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes) {
     if (msg_dev) *msg_dev = h->msg;
     if (bytes) *bytes = h->msg_row_bytes * (uint64_t)h->cfg.n;
     return DS_OK;
+}
+
+ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count) {
+    if (!h || !count) return DS_EINVAL;
+    *count = 0;
+    if (!h->topk) return DS_OK;
+    if (!h->stepped) return fail(h, DS_ESTATE, "no step has been taken yet");
+    return dsq::topk_candidate_rows(h->topk, h->last_stream, count);
 }
 
 uint64_t ds_step_count(const ds_handle* h) { return h ? h->t : 0; }

@@ -14,7 +14,10 @@ namespace dsq {
 
 constexpr int kWave = 64;                 // gfx950 wavefront
 constexpr int kSweep = 4 * kWave;         // columns one wave covers with one float4 per lane
-constexpr uint64_t kPitchAlign = 4096;    // x / delta row pitch is a multiple of this many floats
+constexpr uint64_t kPitchAlign = 4096;    // x / delta row pitch: N rounded up to this many floats ...
+constexpr uint64_t kPitchSkew = 2560;     // ... plus 10 KB, so that rows do not sit a power of two apart: with all rows
+                                          // of a column tile in flight at once, HBM channel hashing made a 16 MiB pitch
+                                          // 12 % slower than this one on MI355X (measured, 64 rows x 4 Mi columns)
 constexpr int kMinBlock = 256, kMaxBlock = 2048;
 
 // Host-side description of W - I in CSR form (diagonal always present, columns ascending).
@@ -36,11 +39,11 @@ struct TileArgs {
     float* delta;              // n x ld
     const float* g;            // n x g_ld
     uint8_t* msg;              // n x msg_row_bytes
-    const int32_t* rowptr;     // device CSR of W - I
-    const int32_t* col;
+    const int32_t* rowptr;     // device CSR of W - I: rowptr (n+1), col (nnz) and coef (nnz, fp32 bits)
+    const int32_t* col;        // are ONE contiguous array in that order (the tile kernel copies it whole)
     const float* coef;
     uint64_t ld, g_ld, N, msg_row_bytes;
-    int n;
+    int n, nnz;                // workers; stored entries of W - I
     float gamma, eta;
     uint32_t seed_lo, seed_hi, t_lo;
 };
@@ -52,10 +55,11 @@ struct TilePlan {
     int tile_cols = 0;         // columns per workgroup
     int waves = 0;             // waves per workgroup
     int rows_per_wave = 0;     // rows each wave owns (held in registers when the variant says so)
+    int sweeps = 0;            // 256-column sweeps per tile
 };
 
-// Picks the variant for (n, compressor); returns false with `err` set if no variant fits.
-bool choose_tile_plan(const ds_config& cfg, int max_degree, TilePlan& plan, std::string& err);
+// Lists the variants that fit (n, compressor), best guess first; returns false with `err` set if none does.
+bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plans, std::string& err);
 
 // ---- top-k path ---------------------------------------------------------------------------------
 struct TopkArgs {
@@ -75,5 +79,10 @@ struct TopkState;              // device scratch of the radix select (histograms
 ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::string& err);
 void topk_destroy(TopkState* s);
 ds_status topk_step(TopkState* s, const TopkArgs& a, const Graph& graph, hipStream_t stream, std::string& err);
+// topk_step leaves the sparse part of the gossip update of x to the next step's first pass;
+// topk_flush applies it now (no-op if nothing is pending).  Call before x is read or replaced.
+ds_status topk_flush(TopkState* s, hipStream_t stream);
+// Number of rows whose last step selected from the candidate slots (the fast path).
+ds_status topk_candidate_rows(TopkState* s, hipStream_t stream, uint32_t* count);
 
 }  // namespace dsq

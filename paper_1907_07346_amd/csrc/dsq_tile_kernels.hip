@@ -66,18 +66,32 @@ __device__ __forceinline__ void st4(float* p, const float4& v) {
 #endif
 }
 
-// ---- wave64 reductions; every lane ends with the result ---------------------------------------
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+// ---- wave64 reductions on the DPP cross-lane path (no LDS traffic); the result is wave-uniform ----
+// row_shr:1,2,4,8 fold each row of 16 lanes into its lane 15, row_bcast15 folds row r into row r+1
+// (rows 1 and 3), row_bcast31 folds lane 31 into lane 63.  Lanes without a source keep `old`.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float old, float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
 }
-// Pairwise tree in lane order: level k adds the sums of adjacent groups of 2^k lanes.  Both
-// partners of an exchange compute a+b (commutative), so all lanes hold identical bits.
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_move<0x111, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x112, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x114, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x118, 0xF>(v, v));
+    v = fmaxf(v, dpp_move<0x142, 0xA>(v, v));
+    v = fmaxf(v, dpp_move<0x143, 0xC>(v, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// Pairwise tree in lane order: level k adds the sums of adjacent groups of 2^k lanes (the order of the
+// two operands of an addition does not matter), which is the balanced tree the scale definition asks for.
 __device__ __forceinline__ float wave_sum_tree(float v) {
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) v = v + __shfl_xor(v, o);
-    return v;
+    v = v + dpp_move<0x111, 0xF>(0.f, v);
+    v = v + dpp_move<0x112, 0xF>(0.f, v);
+    v = v + dpp_move<0x114, 0xF>(0.f, v);
+    v = v + dpp_move<0x118, 0xF>(0.f, v);
+    v = v + dpp_move<0x142, 0xA>(0.f, v);
+    v = v + dpp_move<0x143, 0xC>(0.f, v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 template <int KIND, int BITS> struct CodeTraits;
@@ -100,8 +114,9 @@ struct Tile {
     static constexpr int MSG_BLOCK_BYTES = 4 + B * (BITS & 15) / 8;   // [scale][codes] of a full block
     static_assert(B % kSweep == 0 && SW % SPB == 0, "tile must hold whole blocks");
 
-    static __host__ __device__ constexpr size_t lds_bytes(int n) {
-        return (size_t)n * ROW_CODE_BYTES + (size_t)n * BPT * sizeof(float);
+    // LDS: [codes of all rows][decode units of all rows][rowptr n+1][col nnz][coef nnz]
+    static __host__ __device__ constexpr size_t lds_bytes(int n, int nnz) {
+        return (size_t)n * ROW_CODE_BYTES + (size_t)n * BPT * sizeof(float) + (size_t)(n + 1 + 2 * nnz) * 4;
     }
 
     // ---- phase 1 for one row: returns xh (x - gamma g) in registers ---------------------------
@@ -252,43 +267,81 @@ struct Tile {
     }
 
     // ---- phase 2 for one row: gossip on the decoded neighbours (Algorithm 1, line 9) ----------
+    // acc[s][c] accumulates one neighbour after the other (CSR order), all sweeps at once, so the LDS
+    // reads of one neighbour are in flight together.
+    static __device__ __forceinline__ void gossip_accumulate(int nb, float w, int lane, const uint8_t* lds_codes,
+                                                             const float* lds_units, float (&acc)[SW][4]) {
+        const uint8_t* nrow = lds_codes + (size_t)nb * ROW_CODE_BYTES;
+        if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
+            using lane_t = typename CT::lane_t;
+            uint32_t codes[SW];
+            float unit[BPT];
+#pragma unroll
+            for (int s = 0; s < SW; ++s) codes[s] = reinterpret_cast<const lane_t*>(nrow)[s * kWave + lane];
+#pragma unroll
+            for (int b = 0; b < BPT; ++b) unit[b] = lds_units[nb * BPT + b];
+#pragma unroll
+            for (int s = 0; s < SW; ++s)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int q = (int)((codes[s] >> (BITS * c)) & (uint32_t)L);
+                    acc[s][c] = fmaf(w, (float)(2 * q - L) * unit[s / SPB], acc[s][c]);
+                }
+        } else if constexpr (KIND == DS_COMP_SIGN_MEANABS) {
+            uint32_t word[SW];
+            float scale[BPT];
+#pragma unroll
+            for (int s = 0; s < SW; ++s) word[s] = reinterpret_cast<const uint32_t*>(nrow)[s * 8 + (lane >> 3)];
+#pragma unroll
+            for (int b = 0; b < BPT; ++b) scale[b] = lds_units[nb * BPT + b];
+#pragma unroll
+            for (int s = 0; s < SW; ++s) {
+                const uint32_t nib = word[s] >> (4 * (lane & 7));
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    acc[s][c] = fmaf(w, ((nib >> c) & 1u) ? -scale[s / SPB] : scale[s / SPB], acc[s][c]);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < SW; ++s) {
+                const float4 cv = reinterpret_cast<const float4*>(nrow)[s * kWave + lane];
+                acc[s][0] = fmaf(w, cv.x, acc[s][0]); acc[s][1] = fmaf(w, cv.y, acc[s][1]);
+                acc[s][2] = fmaf(w, cv.z, acc[s][2]); acc[s][3] = fmaf(w, cv.w, acc[s][3]);
+            }
+        }
+    }
+
     template <bool FULL>
     static __device__ __forceinline__ void gossip_row(const TileArgs& a, int i, uint64_t col0, int lane,
                                                       const uint8_t* lds_codes, const float* lds_units,
-                                                      const float4 (&xh)[SW]) {
-        const int e0 = a.rowptr[i], e1 = a.rowptr[i + 1];
+                                                      const int32_t* lds_graph, const float4 (&xh)[SW]) {
+        // the graph sits in LDS (copied at kernel start); row i is the same for the whole wave
+        const int32_t* g_col = lds_graph + a.n + 1;
+        const float* g_coef = reinterpret_cast<const float*>(g_col + a.nnz);
+        const int e0 = __builtin_amdgcn_readfirstlane(lds_graph[i]);
+        const int e1 = __builtin_amdgcn_readfirstlane(lds_graph[i + 1]);
+        float acc[SW][4];
+#pragma unroll
+        for (int s = 0; s < SW; ++s) acc[s][0] = acc[s][1] = acc[s][2] = acc[s][3] = 0.f;
+        auto edge = [&](int e) {
+            const int nb = __builtin_amdgcn_readfirstlane(g_col[e]);
+            const float w = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(g_coef[e])));
+            gossip_accumulate(nb, w, lane, lds_codes, lds_units, acc);
+        };
+        const int deg = e1 - e0;
+        if (deg == 3) {                                   // ring
+            edge(e0); edge(e0 + 1); edge(e0 + 2);
+        } else if (deg == 5) {                            // 2-D torus
+            edge(e0); edge(e0 + 1); edge(e0 + 2); edge(e0 + 3); edge(e0 + 4);
+        } else {
+            for (int e = e0; e < e1; ++e) edge(e);
+        }
         float* xout = a.x + (uint64_t)i * a.ld + col0 + 4 * lane;
 #pragma unroll
         for (int s = 0; s < SW; ++s) {
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int e = e0; e < e1; ++e) {
-                const int nb = a.col[e];
-                const float w = a.coef[e];
-                const uint8_t* nrow = lds_codes + (size_t)nb * ROW_CODE_BYTES;
-                if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
-                    using lane_t = typename CT::lane_t;
-                    const uint32_t codes = reinterpret_cast<const lane_t*>(nrow)[s * kWave + lane];
-                    const float unit = lds_units[nb * BPT + s / SPB];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const int q = (int)((codes >> (BITS * c)) & (uint32_t)L);
-                        acc[c] = fmaf(w, (float)(2 * q - L) * unit, acc[c]);
-                    }
-                } else if constexpr (KIND == DS_COMP_SIGN_MEANABS) {
-                    const uint32_t word = reinterpret_cast<const uint32_t*>(nrow)[s * 8 + (lane >> 3)];
-                    const uint32_t nib = word >> (4 * (lane & 7));
-                    const float scale = lds_units[nb * BPT + s / SPB];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) acc[c] = fmaf(w, ((nib >> c) & 1u) ? -scale : scale, acc[c]);
-                } else {
-                    const float4 cv = reinterpret_cast<const float4*>(nrow)[s * kWave + lane];
-                    acc[0] = fmaf(w, cv.x, acc[0]); acc[1] = fmaf(w, cv.y, acc[1]);
-                    acc[2] = fmaf(w, cv.z, acc[2]); acc[3] = fmaf(w, cv.w, acc[3]);
-                }
-            }
             float4 xn;
-            xn.x = fmaf(a.eta, acc[0], xh[s].x); xn.y = fmaf(a.eta, acc[1], xh[s].y);
-            xn.z = fmaf(a.eta, acc[2], xh[s].z); xn.w = fmaf(a.eta, acc[3], xh[s].w);
+            xn.x = fmaf(a.eta, acc[s][0], xh[s].x); xn.y = fmaf(a.eta, acc[s][1], xh[s].y);
+            xn.z = fmaf(a.eta, acc[s][2], xh[s].z); xn.w = fmaf(a.eta, acc[s][3], xh[s].w);
             if (!FULL) {                                             // keep the pitch padding at zero
                 const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
                 if (!(j + 0 < a.N)) xn.x = 0.f;
@@ -329,6 +382,26 @@ struct Tile {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         uint8_t* lds_codes = lds;
         float* lds_units = reinterpret_cast<float*>(lds + (size_t)a.n * ROW_CODE_BYTES);
+        int32_t* lds_graph = reinterpret_cast<int32_t*>(lds_units + (size_t)a.n * BPT);
+        // W - I in CSR form (rowptr | col | coef, contiguous in device memory) -> LDS.  The loads are
+        // issued first and parked in registers; the LDS writes come after phase 1, so their latency
+        // hides behind the row streams.  Read only after the barrier.
+        constexpr int GPRE = 2;
+        const int gtotal = a.n + 1 + 2 * a.nnz;
+        int32_t gpre[GPRE];
+#pragma unroll
+        for (int k = 0; k < GPRE; ++k) {
+            const int q = threadIdx.x + k * NW * kWave;
+            gpre[k] = (q < gtotal) ? a.rowptr[q] : 0;
+        }
+        auto park_graph = [&]() {
+#pragma unroll
+            for (int k = 0; k < GPRE; ++k) {
+                const int q = threadIdx.x + k * NW * kWave;
+                if (q < gtotal) lds_graph[q] = gpre[k];
+            }
+            for (int q = threadIdx.x + GPRE * NW * kWave; q < gtotal; q += NW * kWave) lds_graph[q] = a.rowptr[q];
+        };
         if constexpr (RPW > 0) {
             float4 xh[RPW][SW];
 #pragma unroll
@@ -336,11 +409,12 @@ struct Tile {
                 const int i = wave + r * NW;
                 if (i < a.n) compress_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh[r]);
             }
+            park_graph();
             __syncthreads();
 #pragma unroll
             for (int r = 0; r < RPW; ++r) {
                 const int i = wave + r * NW;
-                if (i < a.n) gossip_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh[r]);
+                if (i < a.n) gossip_row<FULL>(a, i, col0, lane, lds_codes, lds_units, lds_graph, xh[r]);
             }
         } else {
             float4 xh[SW];
@@ -348,12 +422,13 @@ struct Tile {
                 const int i = wave + r * NW;
                 if (i < a.n) compress_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh);
             }
+            park_graph();
             __syncthreads();
             for (int r = 0; r < rpw_runtime; ++r) {
                 const int i = wave + r * NW;
                 if (i < a.n) {
                     reload_xh<FULL>(a, i, col0, lane, xh);
-                    gossip_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh);
+                    gossip_row<FULL>(a, i, col0, lane, lds_codes, lds_units, lds_graph, xh);
                 }
             }
         }
@@ -373,7 +448,7 @@ template <int KIND, int BITS, int B, int SW, int NW, int RPW>
 void launch_tile(const TileArgs& a, int rpw_runtime, hipStream_t stream) {
     using T = Tile<KIND, BITS, B, SW, NW>;
     const unsigned tiles = (unsigned)((a.N + T::TC - 1) / T::TC);
-    const size_t lds = T::lds_bytes(a.n);
+    const size_t lds = T::lds_bytes(a.n, a.nnz);
     auto kern = fused_tile_kernel<KIND, BITS, B, SW, NW, RPW>;
     static bool attr_set = false;
     if (lds > 48 * 1024 && !attr_set) {
@@ -391,74 +466,92 @@ TilePlan make_plan(const char* name) {
     p.tile_cols = SW * kSweep;
     p.waves = NW;
     p.rows_per_wave = RPW;
+    p.sweeps = SW;
     return p;
 }
 
 constexpr size_t kMaxLds = 160 * 1024;
 
-// Variant table for one (KIND, BITS, B): picks waves per workgroup and rows per wave from n.
-// Measured on MI355X: 8-wave workgroups whose waves each own several rows beat 16-wave ones,
-// because two or more workgroups then share a CU and one's gossip phase overlaps the other's
-// loads.  A wave keeps xh for all its rows in registers, so rows-per-wave * sweeps is capped.
+// Variant table for one (KIND, BITS, B): every launch shape that fits n, best guess first.
+// Measured on MI355X: 8-wave workgroups whose waves each own several rows usually beat 16-wave
+// ones (two or more workgroups then share a CU and one's gossip phase overlaps the other's loads),
+// but the order changes with the shape and from GPU to GPU, so ds_init times the candidates.
+// A wave keeps xh for all its rows in registers, so rows-per-wave * sweeps is capped.
 template <int KIND, int BITS, int B, int SW, int NW, int RPW>
-bool try_plan(int n, const char* name, TilePlan& plan) {
-    if constexpr (RPW * SW > (NW > 8 ? 8 : 16)) {
-        return false;                                          // would spill: xh alone needs 4*RPW*SW VGPRs
-    } else {
-        if (n > NW * RPW) return false;
-        plan = make_plan<KIND, BITS, B, SW, NW, RPW>(name);
-        return true;
+void add_plan(int n, const char* name, std::vector<TilePlan>& plans) {
+    if constexpr (RPW * SW <= (NW > 8 ? 8 : 16) && (NW <= 8 || SW <= 4)) {   // else the 128-VGPR cap of a 16-wave group spills
+        if (n > NW * RPW) return;
+        if (RPW > 1 && n <= NW * (RPW / 2)) return;            // a smaller RPW already covers n
+        plans.push_back(make_plan<KIND, BITS, B, SW, NW, RPW>(name));
     }
 }
 
+template <int KIND, int BITS, int B, int SW>
+void add_plans_for_sweeps(int n, std::vector<TilePlan>& plans) {
+    add_plan<KIND, BITS, B, SW, 8, 1>(n, "tile/8w/1row", plans);
+    add_plan<KIND, BITS, B, SW, 8, 2>(n, "tile/8w/2rows", plans);
+    add_plan<KIND, BITS, B, SW, 8, 4>(n, "tile/8w/4rows", plans);
+    add_plan<KIND, BITS, B, SW, 8, 8>(n, "tile/8w/8rows", plans);
+    add_plan<KIND, BITS, B, SW, 16, 1>(n, "tile/16w/1row", plans);
+    add_plan<KIND, BITS, B, SW, 16, 2>(n, "tile/16w/2rows", plans);
+    add_plan<KIND, BITS, B, SW, 16, 4>(n, "tile/16w/4rows", plans);
+    add_plan<KIND, BITS, B, SW, 4, 2>(n, "tile/4w/2rows", plans);
+    add_plan<KIND, BITS, B, SW, 4, 4>(n, "tile/4w/4rows", plans);
+}
+
 template <int KIND, int BITS, int B>
-bool pick_for_block(int n, TilePlan& plan, std::string& err) {
-    constexpr int SW = (B <= kSweep) ? 2 : (B / kSweep);       // 256-column blocks: two blocks per tile
-    using T8 = Tile<KIND, BITS, B, SW, 8>;
-    if (T8::lds_bytes(n) > kMaxLds) {
+bool pick_for_block(int n, int nnz, std::vector<TilePlan>& plans, std::string& err) {
+    constexpr int SW = (B <= kSweep) ? 1 : (B / kSweep);
+    using T8 = Tile<KIND, BITS, B, (B <= kSweep) ? 2 : SW, 8>;
+    if (T8::lds_bytes(n, nnz) > kMaxLds) {
         err = "n is too large for the fused tile kernel: the codes of all n rows of one tile must fit in 160 KB of LDS";
         return false;
     }
-    if (try_plan<KIND, BITS, B, SW, 8, 1>(n, "tile/8w/1row", plan)) return true;
-    if (try_plan<KIND, BITS, B, SW, 8, 2>(n, "tile/8w/2rows", plan)) return true;
-    if (try_plan<KIND, BITS, B, SW, 8, 4>(n, "tile/8w/4rows", plan)) return true;
-    if (try_plan<KIND, BITS, B, SW, 8, 8>(n, "tile/8w/8rows", plan)) return true;
-    if (try_plan<KIND, BITS, B, SW, 16, 2>(n, "tile/16w/2rows", plan)) return true;
-    if (try_plan<KIND, BITS, B, SW, 16, 4>(n, "tile/16w/4rows", plan)) return true;
-    if constexpr (SW >= 8) {
-        plan = make_plan<KIND, BITS, B, SW, 8, 0>("tile/8w/looped");
-        plan.rows_per_wave = (n + 7) / 8;
-    } else {
-        plan = make_plan<KIND, BITS, B, SW, 16, 0>("tile/16w/looped");
-        plan.rows_per_wave = (n + 15) / 16;
+    add_plans_for_sweeps<KIND, BITS, B, SW>(n, plans);
+    if constexpr (B <= kSweep) {
+        // 256-column blocks: also try two blocks per tile
+        std::vector<TilePlan> two;
+        add_plans_for_sweeps<KIND, BITS, B, 2>(n, two);
+        for (TilePlan& p : two) plans.push_back(p);
+    }
+    if (plans.empty()) {
+        TilePlan plan;
+        if constexpr (SW >= 8) {
+            plan = make_plan<KIND, BITS, B, SW, 8, 0>("tile/8w/looped");
+            plan.rows_per_wave = (n + 7) / 8;
+        } else {
+            plan = make_plan<KIND, BITS, B, SW, 16, 0>("tile/16w/looped");
+            plan.rows_per_wave = (n + 15) / 16;
+        }
+        plans.push_back(plan);
     }
     return true;
 }
 
 template <int KIND, int BITS>
-bool pick_for_kind(int block, int n, TilePlan& plan, std::string& err) {
+bool pick_for_kind(int block, int n, int nnz, std::vector<TilePlan>& plan, std::string& err) {
     switch (block) {
-        case 256:  return pick_for_block<KIND, BITS, 256>(n, plan, err);
-        case 512:  return pick_for_block<KIND, BITS, 512>(n, plan, err);
-        case 1024: return pick_for_block<KIND, BITS, 1024>(n, plan, err);
-        case 2048: return pick_for_block<KIND, BITS, 2048>(n, plan, err);
+        case 256:  return pick_for_block<KIND, BITS, 256>(n, nnz, plan, err);
+        case 512:  return pick_for_block<KIND, BITS, 512>(n, nnz, plan, err);
+        case 1024: return pick_for_block<KIND, BITS, 1024>(n, nnz, plan, err);
+        case 2048: return pick_for_block<KIND, BITS, 2048>(n, nnz, plan, err);
         default: err = "block must be a power of two between 256 and 2048"; return false;
     }
 }
 
 }  // namespace
 
-bool choose_tile_plan(const ds_config& cfg, int /*max_degree*/, TilePlan& plan, std::string& err) {
+bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plan, std::string& err) {
     switch (cfg.comp.kind) {
         case DS_COMP_QUANT_MAXABS:
-            if (cfg.comp.bits == 4) return pick_for_kind<DS_COMP_QUANT_MAXABS, 4>(cfg.comp.block, cfg.n, plan, err);
-            if (cfg.comp.bits == 2) return pick_for_kind<DS_COMP_QUANT_MAXABS, 2>(cfg.comp.block, cfg.n, plan, err);
+            if (cfg.comp.bits == 4) return pick_for_kind<DS_COMP_QUANT_MAXABS, 4>(cfg.comp.block, cfg.n, nnz, plan, err);
+            if (cfg.comp.bits == 2) return pick_for_kind<DS_COMP_QUANT_MAXABS, 2>(cfg.comp.block, cfg.n, nnz, plan, err);
             err = "bits must be 2 or 4";
             return false;
         case DS_COMP_SIGN_MEANABS:
-            return pick_for_kind<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, cfg.n, plan, err);
+            return pick_for_kind<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, cfg.n, nnz, plan, err);
         case DS_COMP_IDENTITY:
-            return pick_for_block<DS_COMP_IDENTITY, 32, 512>(cfg.n, plan, err);
+            return pick_for_block<DS_COMP_IDENTITY, 32, 512>(cfg.n, nnz, plan, err);
         default:
             err = "no tile kernel for this compressor";
             return false;

@@ -7,11 +7,27 @@
 // sparse vectors into x.
 //
 // The select is an MSB-first radix select on key = bits(v) & 0x7fffffff (order preserving for
-// finite |v|): 11 + 11 + 9 bits with workgroup histograms in LDS.  The first histogram is fused
-// into the pass that forms v; the exact threshold key tau and the number r_tie of elements equal
-// to tau that still belong to the set come out of three tiny per-row select kernels.  Ordered
-// output (ascending index, needed for the tie rule and for a canonical message) comes from
-// per-chunk counts, a per-row scan over chunks and an in-chunk ordered compaction.
+// finite |v|): 11 + 11 + 9 bits, workgroup histograms in LDS, three tiny per-row select kernels
+// that end with the exact threshold key tau and the number r_tie of elements equal to tau that
+// still belong to the set.  Ordered output (ascending index: the tie rule and a canonical
+// message need it) comes from per-chunk counts, a per-row scan over chunks and an ordered
+// compaction inside each chunk.
+//
+// Two sources feed the select, chosen per row on the device with no host round trip:
+//   * candidate mode (the fast path): the pass that forms v also appends every element whose key
+//     reaches a per-row guess `tlo` (a level-1 bin edge taken from the previous step, aimed at
+//     about 2.5 k elements) to a small per-chunk slot.  If at least k candidates were collected
+//     and no slot overflowed, the whole select runs on the slots (a few % of N) and v is never
+//     read again.
+//   * full mode (always exact, used on the first step and whenever the guess fails): the same
+//     select with histogram passes over v itself.
+// Both end in the same tau, r_tie, per-chunk counts and message, so results never depend on the
+// guess; only speed does.
+//
+// Line 9 is deferred: the first pass writes x = (x - gamma g) + 0, which already is the final
+// value of every column no neighbour sent; the sparse remainder eta * sum_j a_ij C[v_j] is
+// folded into the NEXT step's first pass (which streams x anyway), or applied by topk_flush
+// before anyone else looks at x.
 
 #include "dsq_internal.h"
 
@@ -22,7 +38,9 @@ namespace {
 constexpr int TK_THREADS = 256;
 constexpr int TK_VEC = 4 * TK_THREADS;       // elements per workgroup iteration
 constexpr int TK_ITERS = 8;
-constexpr int TK_CHUNK = TK_VEC * TK_ITERS;  // columns per chunk (one workgroup)
+constexpr int TK_CHUNK = TK_VEC * TK_ITERS;  // columns per chunk (one workgroup of the streaming passes)
+constexpr int TK_CAP = 1024;                 // candidate slots per chunk (12.5 % of the chunk)
+constexpr int TK_CPW = 8;                    // chunks per workgroup in the candidate-mode kernels
 constexpr int BINS1 = 2048, SHIFT1 = 20;     // key bits 30..20
 constexpr int BINS2 = 2048, SHIFT2 = 9;      // key bits 19..9
 constexpr int BINS3 = 512;                   // key bits 8..0
@@ -33,8 +51,22 @@ struct TopkRow {
     uint32_t prefix2, need2;   // 22-bit prefix of the threshold key; how many to take among its matches
     uint32_t tau, r_tie;       // threshold key; number of elements with key == tau to take (lowest indices)
     uint32_t total;            // number of selected elements found by the scan (must equal k)
+    uint32_t tlo;              // candidate threshold key for the next first pass (0xffffffff: collect nothing)
+    uint32_t cand_mode;        // 1: this step's select runs on the candidate slots
+    uint32_t overflow;         // a slot overflowed in this step's first pass
+    uint32_t cand_total;       // candidates collected in this step
     uint32_t pad;
 };
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld4_stream(const float* p) {
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st4_stream(float* p, const float4& v) {
+    const f32x4 w = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(p));
+}
 
 __device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7FFFFFFFu; }
 
@@ -67,65 +99,157 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_sums) {
     return tot;
 }
 
-// ---- pass 1: Algorithm 1 line 5 (x <- x - gamma g, delta <- v) + level-1 histogram ------------
-__global__ void __launch_bounds__(TK_THREADS) topk_form_hist1(TopkArgs a, uint32_t* __restrict__ hist) {
-    __shared__ uint32_t h[HIST_BINS];
+struct Scratch {               // device pointers of the select's scratch (all owned by TopkState)
+    uint32_t* hist;            // n x 2048
+    TopkRow* rows;             // n
+    uint32_t* cnt_gt;          // n x nchunks: keys above the threshold (prefix) in the chunk
+    uint32_t* cnt_eq;          // n x nchunks: keys equal to the threshold (prefix) in the chunk
+    uint32_t* eq_before;       // n x nchunks: ties in earlier chunks of the row
+    uint32_t* out_off;         // n x (nchunks+1): message offset of each chunk
+    uint32_t* cand_cnt;        // n x nchunks: candidates stored in the chunk's slot
+    uint2* slots;              // n x nchunks x TK_CAP candidate (index, value bits) pairs, unordered inside a slot
+    uint32_t nchunks;
+};
+
+// ---- pass 1: pending gossip of the previous step, Algorithm 1 line 5, candidate collection ------
+template <bool PENDING>
+__global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scratch s) {
+    __shared__ float acc[PENDING ? TK_CHUNK : 1];
+    __shared__ uint32_t h[HIST_BINS];                          // level-1 digits of the candidates
+    __shared__ uint32_t cand_count;
     const int row = blockIdx.y;
-    const uint64_t c0 = (uint64_t)blockIdx.x * TK_CHUNK;
+    const uint32_t chunk = blockIdx.x;
+    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+    if (threadIdx.x == 0) cand_count = 0;
     for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS) h[b] = 0;
+    bool patch = false;
+    if (PENDING) {
+        // eta * sum_j a_ij C[v_j] of the previous step for this chunk: the neighbours' pairs that fall
+        // into the chunk are contiguous in their messages; accumulate neighbour after neighbour.
+        const int e0 = a.rowptr[row], e1 = a.rowptr[row + 1];
+        for (int e = e0; e < e1; ++e) {
+            const uint32_t* off = s.out_off + (size_t)a.col[e] * (s.nchunks + 1) + chunk;
+            patch |= (off[0] != off[1]);
+        }
+        if (patch) {                                           // uniform
+            for (int q = threadIdx.x; q < TK_CHUNK; q += TK_THREADS) acc[q] = 0.f;
+            __syncthreads();
+            for (int e = e0; e < e1; ++e) {
+                const int nb = a.col[e];
+                const float w = a.coef[e];
+                const uint32_t* off = s.out_off + (size_t)nb * (s.nchunks + 1) + chunk;
+                const uint2* in = reinterpret_cast<const uint2*>(a.msg + (uint64_t)nb * a.k * 8);
+                for (uint32_t p = off[0] + threadIdx.x; p < off[1]; p += TK_THREADS) {
+                    const uint2 pr = in[p];
+                    const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
+                    if (q < (uint32_t)TK_CHUNK) acc[q] = fmaf(w, __uint_as_float(pr.y), acc[q]);
+                }
+                __syncthreads();
+            }
+        }
+    }
     __syncthreads();
+    const uint32_t tlo = s.rows[row].tlo;
+    uint2* slot = s.slots + ((size_t)row * s.nchunks + chunk) * TK_CAP;
     float* xr = a.x + (uint64_t)row * a.ld;
     float* dr = a.delta + (uint64_t)row * a.ld;
     const float* gr = a.g + (uint64_t)row * a.g_ld;
 #pragma unroll 2
     for (int it = 0; it < TK_ITERS; ++it) {
-        const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
+        const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
+        const uint64_t j = c0 + q0;
         if (j >= a.ld) break;
-        const float4 xv = *reinterpret_cast<const float4*>(xr + j);
-        const float4 dv = *reinterpret_cast<const float4*>(dr + j);
+        float4 xv = ld4_stream(xr + j);
+        const float4 dv = ld4_stream(dr + j);
         float4 gv;
         if (j + 3 < a.N) {
-            gv = *reinterpret_cast<const float4*>(gr + j);
+            gv = ld4_stream(gr + j);
         } else {
             gv.x = (j + 0 < a.N) ? gr[j + 0] : 0.f;
             gv.y = (j + 1 < a.N) ? gr[j + 1] : 0.f;
             gv.z = (j + 2 < a.N) ? gr[j + 2] : 0.f;
             gv.w = (j + 3 < a.N) ? gr[j + 3] : 0.f;
         }
+        if (PENDING && patch) {                                // line 9 of the previous step
+            xv.x = fmaf(a.eta, acc[q0 + 0], xv.x); xv.y = fmaf(a.eta, acc[q0 + 1], xv.y);
+            xv.z = fmaf(a.eta, acc[q0 + 2], xv.z); xv.w = fmaf(a.eta, acc[q0 + 3], xv.w);
+        }
         float4 xh, v;
         xh.x = fmaf(-a.gamma, gv.x, xv.x); v.x = xh.x + dv.x;
         xh.y = fmaf(-a.gamma, gv.y, xv.y); v.y = xh.y + dv.y;
         xh.z = fmaf(-a.gamma, gv.z, xv.z); v.z = xh.z + dv.z;
         xh.w = fmaf(-a.gamma, gv.w, xv.w); v.w = xh.w + dv.w;
-        // x holds xh + eta*0 until the gossip kernel patches the columns some neighbour sent
+        // x holds xh + eta*0 until the sparse part of line 9 is applied
         xh.x += 0.f; xh.y += 0.f; xh.z += 0.f; xh.w += 0.f;
-        *reinterpret_cast<float4*>(xr + j) = xh;
-        *reinterpret_cast<float4*>(dr + j) = v;
-        if (j + 0 < a.N) atomicAdd(&h[key_of(v.x) >> SHIFT1], 1u);
-        if (j + 1 < a.N) atomicAdd(&h[key_of(v.y) >> SHIFT1], 1u);
-        if (j + 2 < a.N) atomicAdd(&h[key_of(v.z) >> SHIFT1], 1u);
-        if (j + 3 < a.N) atomicAdd(&h[key_of(v.w) >> SHIFT1], 1u);
+        st4_stream(xr + j, xh);
+        st4_stream(dr + j, v);
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (j + c < a.N && key_of(vv[c]) >= tlo) {
+                const uint32_t idx = atomicAdd(&cand_count, 1u);
+                if (idx < (uint32_t)TK_CAP) slot[idx] = make_uint2((uint32_t)(j + c), __float_as_uint(vv[c]));
+                atomicAdd(&h[key_of(vv[c]) >> SHIFT1], 1u);
+            }
     }
     __syncthreads();
-    uint32_t* hrow = hist + (size_t)row * HIST_BINS;
-    for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS)
+    // only bins from tlo's upward can be non-empty; the row histogram is used if the row ends up in
+    // candidate mode and wiped by topk_decide otherwise
+    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
+    for (int b = (int)(tlo >> SHIFT1 < (uint32_t)HIST_BINS ? tlo >> SHIFT1 : (uint32_t)HIST_BINS) + threadIdx.x; b < HIST_BINS; b += TK_THREADS)
         if (h[b]) atomicAdd(&hrow[b], h[b]);
+    if (threadIdx.x == 0) {
+        const uint32_t c = cand_count;
+        s.cand_cnt[(size_t)row * s.nchunks + chunk] = c < (uint32_t)TK_CAP ? c : (uint32_t)TK_CAP;
+        if (c > (uint32_t)TK_CAP) atomicOr(&s.rows[row].overflow, 1u);
+    }
 }
 
-// ---- passes 2 and 3: histogram of the next digit among keys matching the prefix so far ---------
+// ---- per row: did the guess work?  (candidates >= k and no slot overflow) ----------------------
+__global__ void __launch_bounds__(TK_THREADS) topk_decide(Scratch s, uint32_t k) {
+    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    const int row = blockIdx.x;
+    uint32_t sum = 0;
+    for (uint32_t c = threadIdx.x; c < s.nchunks; c += TK_THREADS) sum += s.cand_cnt[(size_t)row * s.nchunks + c];
+    const uint32_t total = block_sum(sum, wave_sums);
+    const bool cand = total >= k && s.rows[row].overflow == 0;
+    if (!cand)                                             // full mode builds its own level-1 histogram
+        for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS) s.hist[(size_t)row * HIST_BINS + b] = 0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        TopkRow& r = s.rows[row];
+        r.cand_total = total;
+        r.cand_mode = cand ? 1u : 0u;
+        r.overflow = 0;
+    }
+}
+
+// ---- digit histograms.  LEVEL 1: all keys; 2: keys matching prefix1; 3: keys matching prefix2,
+//      plus per-chunk counts of keys above / inside the 22-bit prefix. -------------------------------
 template <int LEVEL>
-__global__ void __launch_bounds__(TK_THREADS) topk_hist_level(const float* __restrict__ delta, uint64_t ld, uint64_t N,
-                                                              const TopkRow* __restrict__ rows, uint32_t* __restrict__ hist,
-                                                              uint32_t* __restrict__ cnt_gt, uint32_t* __restrict__ cnt_eq,
-                                                              uint32_t nchunks) {
+__device__ __forceinline__ void hist_key(uint32_t key, uint32_t prefix, uint32_t* h, uint32_t& gt, uint32_t& eq) {
+    if (LEVEL == 1) {
+        atomicAdd(&h[key >> SHIFT1], 1u);
+    } else if (LEVEL == 2) {
+        if ((key >> SHIFT1) == prefix) atomicAdd(&h[(key >> SHIFT2) & (BINS2 - 1)], 1u);
+    } else {
+        const uint32_t hi = key >> SHIFT2;
+        if (hi == prefix) { atomicAdd(&h[key & (BINS3 - 1)], 1u); ++eq; }
+        else if (hi > prefix) ++gt;
+    }
+}
+
+template <int LEVEL>
+__global__ void __launch_bounds__(TK_THREADS) topk_hist_full(const float* __restrict__ delta, uint64_t ld, uint64_t N, Scratch s) {
     __shared__ uint32_t h[HIST_BINS];
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
+    if (s.rows[row].cand_mode) return;                         // uniform
     const uint64_t c0 = (uint64_t)blockIdx.x * TK_CHUNK;
-    constexpr int BINS = (LEVEL == 2) ? BINS2 : BINS3;
+    constexpr int BINS = (LEVEL == 3) ? BINS3 : HIST_BINS;
     for (int b = threadIdx.x; b < BINS; b += TK_THREADS) h[b] = 0;
     __syncthreads();
-    const uint32_t prefix = (LEVEL == 2) ? rows[row].prefix1 : rows[row].prefix2;
+    const uint32_t prefix = (LEVEL == 2) ? s.rows[row].prefix1 : (LEVEL == 3) ? s.rows[row].prefix2 : 0u;
     const float* dr = delta + (uint64_t)row * ld;
     uint32_t gt = 0, eq = 0;
 #pragma unroll 2
@@ -135,43 +259,83 @@ __global__ void __launch_bounds__(TK_THREADS) topk_hist_level(const float* __res
         const float4 v = *reinterpret_cast<const float4*>(dr + j);
         const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (j + c < N) {
-                const uint32_t key = key_of(vv[c]);
-                if (LEVEL == 2) {
-                    if ((key >> SHIFT1) == prefix) atomicAdd(&h[(key >> SHIFT2) & (BINS2 - 1)], 1u);
-                } else {
-                    const uint32_t hi = key >> SHIFT2;
-                    if (hi == prefix) { atomicAdd(&h[key & (BINS3 - 1)], 1u); ++eq; }
-                    else if (hi > prefix) ++gt;
-                }
-            }
-        }
+        for (int c = 0; c < 4; ++c)
+            if (j + c < N) hist_key<LEVEL>(key_of(vv[c]), prefix, h, gt, eq);
     }
     __syncthreads();
-    uint32_t* hrow = hist + (size_t)row * HIST_BINS;
+    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
     for (int b = threadIdx.x; b < BINS; b += TK_THREADS)
         if (h[b]) atomicAdd(&hrow[b], h[b]);
     if (LEVEL == 3) {
         const uint32_t gts = block_sum(gt, wave_sums);
         const uint32_t eqs = block_sum(eq, wave_sums);
         if (threadIdx.x == 0) {
-            cnt_gt[(size_t)row * nchunks + blockIdx.x] = gts;
-            cnt_eq[(size_t)row * nchunks + blockIdx.x] = eqs;
+            s.cnt_gt[(size_t)row * s.nchunks + blockIdx.x] = gts;
+            s.cnt_eq[(size_t)row * s.nchunks + blockIdx.x] = eqs;
         }
     }
 }
 
-// ---- per-row digit select: the bin where the count from the top crosses `need` -----------------
 template <int LEVEL>
-__global__ void __launch_bounds__(TK_THREADS) topk_select(uint32_t* __restrict__ hist, TopkRow* __restrict__ rows, uint32_t k) {
+__global__ void __launch_bounds__(TK_THREADS) topk_hist_cand(Scratch s) {
+    __shared__ uint32_t h[HIST_BINS];
+    __shared__ uint32_t c_gt[TK_CPW], c_eq[TK_CPW];
+    const int row = blockIdx.y;
+    if (!s.rows[row].cand_mode) return;                        // uniform
+    constexpr int BINS = (LEVEL == 3) ? BINS3 : HIST_BINS;
+    for (int b = threadIdx.x; b < BINS; b += TK_THREADS) h[b] = 0;
+    if (threadIdx.x < TK_CPW) { c_gt[threadIdx.x] = 0; c_eq[threadIdx.x] = 0; }
+    __syncthreads();
+    const uint32_t prefix = (LEVEL == 2) ? s.rows[row].prefix1 : s.rows[row].prefix2;
+    // 32 threads per chunk, TK_CPW chunks side by side
+    constexpr int TPC = TK_THREADS / TK_CPW;
+    const int ci = threadIdx.x / TPC, sub = threadIdx.x % TPC;
+    const uint32_t chunk = blockIdx.x * TK_CPW + ci;
+    uint32_t gt = 0, eq = 0;
+    if (chunk < s.nchunks) {
+        const size_t cidx = (size_t)row * s.nchunks + chunk;
+        const uint32_t cnt = s.cand_cnt[cidx];
+        const uint2* slot = s.slots + cidx * TK_CAP;
+        for (uint32_t p0 = sub; p0 < cnt; p0 += 4 * TPC) {
+            uint32_t key[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (key[u] != 0xFFFFFFFFu) hist_key<LEVEL>(key[u], prefix, h, gt, eq);
+        }
+    }
+    if (LEVEL == 3) {
+        if (gt) atomicAdd(&c_gt[ci], gt);
+        if (eq) atomicAdd(&c_eq[ci], eq);
+    }
+    __syncthreads();
+    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
+    for (int b = threadIdx.x; b < BINS; b += TK_THREADS)
+        if (h[b]) atomicAdd(&hrow[b], h[b]);
+    const uint32_t chunk0 = blockIdx.x * TK_CPW;
+    if (LEVEL == 3 && threadIdx.x < TK_CPW && chunk0 + threadIdx.x < s.nchunks) {
+        s.cnt_gt[(size_t)row * s.nchunks + chunk0 + threadIdx.x] = c_gt[threadIdx.x];
+        s.cnt_eq[(size_t)row * s.nchunks + chunk0 + threadIdx.x] = c_eq[threadIdx.x];
+    }
+}
+
+// ---- per-row digit select: the bin where the count from the top crosses `need` -----------------
+// Level 1 also fixes the candidate threshold of the next step: the lower edge of the bin where the
+// count from the top crosses about 2.5 k, or one bin further down if too few keys are in sight.
+template <int LEVEL>
+__global__ void __launch_bounds__(TK_THREADS) topk_select(Scratch s, uint32_t k) {
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.x;
     constexpr int BINS = (LEVEL == 1) ? BINS1 : (LEVEL == 2) ? BINS2 : BINS3;
     constexpr int PER = HIST_BINS / TK_THREADS;           // 8 consecutive bins per thread
-    uint32_t* hrow = hist + (size_t)row * HIST_BINS;
-    TopkRow& r = rows[row];
+    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
+    TopkRow& r = s.rows[row];
     const uint32_t need = (LEVEL == 1) ? k : (LEVEL == 2) ? r.need1 : r.need2;
+    const uint64_t want64 = (uint64_t)k * 5 / 2;
+    const uint32_t want = want64 > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)want64;
+    const uint32_t old_tlo = r.tlo;
+    const uint32_t was_cand = r.cand_mode;
     // thread t owns bins [top - 8t - 7, top - 8t], i.e. threads are ordered from the largest keys down
     uint32_t mine[PER];
     uint32_t sum = 0;
@@ -184,6 +348,15 @@ __global__ void __launch_bounds__(TK_THREADS) topk_select(uint32_t* __restrict__
     uint32_t total;
     uint32_t above = block_exclusive_scan(sum, wave_sums, &total);   // keys in strictly higher bins
     __syncthreads();
+    if (LEVEL == 1 && threadIdx.x == 0 && total < want) {
+        // not enough keys in sight to aim: look one level-1 bin further down next time
+        uint32_t nt = 0;
+        if (was_cand && old_tlo != 0xFFFFFFFFu) {
+            const uint32_t bin = old_tlo >> SHIFT1;
+            nt = bin > 0 ? (bin - 1) << SHIFT1 : 0u;
+        }
+        r.tlo = nt;
+    }
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         const int b = HIST_BINS - 1 - (threadIdx.x * PER + q);
@@ -193,20 +366,20 @@ __global__ void __launch_bounds__(TK_THREADS) topk_select(uint32_t* __restrict__
             else if (LEVEL == 2) { r.prefix2 = (r.prefix1 << (SHIFT1 - SHIFT2)) | (uint32_t)b; r.need2 = rem; }
             else                 { r.tau = (r.prefix2 << SHIFT2) | (uint32_t)b; r.r_tie = rem; }
         }
+        if (LEVEL == 1 && above < want && want <= above + mine[q]) r.tlo = (uint32_t)b << SHIFT1;
         above += mine[q];
-        if (b < HIST_BINS) hrow[b] = 0;                   // leave the histogram clean for the next pass
+        hrow[b] = 0;                                      // leave the histogram clean for the next pass
     }
 }
 
 // ---- exact per-chunk counts: only chunks that hold a key with the threshold's 22-bit prefix -----
-__global__ void __launch_bounds__(TK_THREADS) topk_fix_counts(const float* __restrict__ delta, uint64_t ld, uint64_t N,
-                                                              const TopkRow* __restrict__ rows, uint32_t* __restrict__ cnt_gt,
-                                                              uint32_t* __restrict__ cnt_eq, uint32_t nchunks) {
+__global__ void __launch_bounds__(TK_THREADS) topk_fix_full(const float* __restrict__ delta, uint64_t ld, uint64_t N, Scratch s) {
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
-    const size_t ci = (size_t)row * nchunks + blockIdx.x;
-    if (cnt_eq[ci] == 0) return;                          // uniform: nothing in this chunk can tie or straddle
-    const uint32_t tau = rows[row].tau;
+    if (s.rows[row].cand_mode) return;
+    const size_t ci = (size_t)row * s.nchunks + blockIdx.x;
+    if (s.cnt_eq[ci] == 0) return;                        // uniform: nothing in this chunk can tie or straddle
+    const uint32_t tau = s.rows[row].tau;
     const uint64_t c0 = (uint64_t)blockIdx.x * TK_CHUNK;
     const float* dr = delta + (uint64_t)row * ld;
     uint32_t gt = 0, eq = 0;
@@ -225,20 +398,52 @@ __global__ void __launch_bounds__(TK_THREADS) topk_fix_counts(const float* __res
     }
     const uint32_t gts = block_sum(gt, wave_sums);
     const uint32_t eqs = block_sum(eq, wave_sums);
-    if (threadIdx.x == 0) { cnt_gt[ci] = gts; cnt_eq[ci] = eqs; }
+    if (threadIdx.x == 0) { s.cnt_gt[ci] = gts; s.cnt_eq[ci] = eqs; }
+}
+
+__global__ void __launch_bounds__(TK_THREADS) topk_fix_cand(Scratch s) {
+    __shared__ uint32_t c_gt[TK_CPW], c_eq[TK_CPW];
+    const int row = blockIdx.y;
+    if (!s.rows[row].cand_mode) return;
+    if (threadIdx.x < TK_CPW) { c_gt[threadIdx.x] = 0; c_eq[threadIdx.x] = 0; }
+    __syncthreads();
+    const uint32_t tau = s.rows[row].tau;
+    constexpr int TPC = TK_THREADS / TK_CPW;
+    const int ci = threadIdx.x / TPC, sub = threadIdx.x % TPC;
+    const uint32_t chunk = blockIdx.x * TK_CPW + ci;
+    if (chunk < s.nchunks) {
+        const size_t cidx = (size_t)row * s.nchunks + chunk;
+        if (s.cnt_eq[cidx] != 0) {
+            const uint32_t cnt = s.cand_cnt[cidx];
+            const uint2* slot = s.slots + cidx * TK_CAP;
+            uint32_t gt = 0, eq = 0;
+            for (uint32_t p = sub; p < cnt; p += TPC) {
+                const uint32_t key = slot[p].y & 0x7FFFFFFFu;
+                gt += key > tau;
+                eq += key == tau;
+            }
+            if (gt) atomicAdd(&c_gt[ci], gt);
+            if (eq) atomicAdd(&c_eq[ci], eq);
+        }
+    }
+    __syncthreads();
+    const uint32_t chunk0 = blockIdx.x * TK_CPW;
+    if (threadIdx.x < TK_CPW && chunk0 + threadIdx.x < s.nchunks) {
+        const size_t cidx = (size_t)row * s.nchunks + chunk0 + threadIdx.x;
+        if (s.cnt_eq[cidx] != 0) { s.cnt_gt[cidx] = c_gt[threadIdx.x]; s.cnt_eq[cidx] = c_eq[threadIdx.x]; }
+    }
 }
 
 // ---- per-row scan over chunks: tie quota and output offset of every chunk -----------------------
-__global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(TopkRow* __restrict__ rows, const uint32_t* __restrict__ cnt_gt,
-                                                               const uint32_t* __restrict__ cnt_eq, uint32_t* __restrict__ eq_before,
-                                                               uint32_t* __restrict__ out_off, uint32_t nchunks) {
+__global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(Scratch s) {
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.x;
-    const uint32_t r_tie = rows[row].r_tie;
-    const uint32_t* gt = cnt_gt + (size_t)row * nchunks;
-    const uint32_t* eq = cnt_eq + (size_t)row * nchunks;
-    uint32_t* eqb = eq_before + (size_t)row * nchunks;
-    uint32_t* off = out_off + (size_t)row * (nchunks + 1);
+    const uint32_t nchunks = s.nchunks;
+    const uint32_t r_tie = s.rows[row].r_tie;
+    const uint32_t* gt = s.cnt_gt + (size_t)row * nchunks;
+    const uint32_t* eq = s.cnt_eq + (size_t)row * nchunks;
+    uint32_t* eqb = s.eq_before + (size_t)row * nchunks;
+    uint32_t* off = s.out_off + (size_t)row * (nchunks + 1);
     uint32_t run_eq = 0, run_out = 0;
     for (uint32_t base = 0; base < nchunks; base += TK_THREADS) {
         const uint32_t c = base + threadIdx.x;
@@ -253,23 +458,22 @@ __global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(TopkRow* __restri
         run_eq += tot_e;
         run_out += tot_o;
     }
-    if (threadIdx.x == 0) { off[nchunks] = run_out; rows[row].total = run_out; }
+    if (threadIdx.x == 0) { off[nchunks] = run_out; s.rows[row].total = run_out; }
 }
 
 // ---- ordered compaction: message pairs, delta <- 0 on the selected set (Algorithm 1, line 6) ----
-__global__ void __launch_bounds__(TK_THREADS) topk_write_selected(TopkArgs a, const TopkRow* __restrict__ rows,
-                                                                  const uint32_t* __restrict__ cnt_eq,
-                                                                  const uint32_t* __restrict__ eq_before,
-                                                                  const uint32_t* __restrict__ out_off, uint32_t nchunks) {
+__global__ void __launch_bounds__(TK_THREADS) topk_write_full(TopkArgs a, Scratch s) {
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
+    if (s.rows[row].cand_mode) return;
+    const uint32_t nchunks = s.nchunks;
     const size_t ci = (size_t)row * nchunks + blockIdx.x;
-    const uint32_t off0 = out_off[(size_t)row * (nchunks + 1) + blockIdx.x];
-    const uint32_t off1 = out_off[(size_t)row * (nchunks + 1) + blockIdx.x + 1];
+    const uint32_t off0 = s.out_off[(size_t)row * (nchunks + 1) + blockIdx.x];
+    const uint32_t off1 = s.out_off[(size_t)row * (nchunks + 1) + blockIdx.x + 1];
     if (off0 == off1) return;
-    const bool ties = cnt_eq[ci] != 0;
-    const uint32_t tau = rows[row].tau, r_tie = rows[row].r_tie;
-    uint32_t run_eq = eq_before[ci], run_out = off0;
+    const bool ties = s.cnt_eq[ci] != 0;
+    const uint32_t tau = s.rows[row].tau, r_tie = s.rows[row].r_tie;
+    uint32_t run_eq = s.eq_before[ci], run_out = off0;
     const uint64_t c0 = (uint64_t)blockIdx.x * TK_CHUNK;
     float* dr = a.delta + (uint64_t)row * a.ld;
     uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
@@ -314,20 +518,105 @@ __global__ void __launch_bounds__(TK_THREADS) topk_write_selected(TopkArgs a, co
     }
 }
 
-// ---- gossip on the sparse messages (Algorithm 1, line 9) ----------------------------------------
+// Candidate mode, one wave per chunk.  A slot is unordered, so order comes from two bitmaps over the
+// chunk's columns (selected, tied): the place of a pair in the message is the number of selected
+// columns below it, and the ties that belong to the set are the `quota` lowest tied columns.
+constexpr int TK_WORDS = TK_CHUNK / 32;                        // bitmap words per chunk
+__device__ __forceinline__ void bitmap_prefix(const uint32_t* bits, uint32_t* prefix, int lane) {
+    // prefix[w] = number of set bits in words [0, w); 4 consecutive words per lane
+    uint32_t c[TK_WORDS / 64], sum = 0;
+#pragma unroll
+    for (int q = 0; q < TK_WORDS / 64; ++q) { c[q] = __popc(bits[lane * (TK_WORDS / 64) + q]); sum += c[q]; }
+    uint32_t inc = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(inc, o);
+        if (lane >= o) inc += up;
+    }
+    uint32_t run = inc - sum;
+#pragma unroll
+    for (int q = 0; q < TK_WORDS / 64; ++q) { prefix[lane * (TK_WORDS / 64) + q] = run; run += c[q]; }
+}
+__device__ __forceinline__ uint32_t bitmap_rank(const uint32_t* bits, const uint32_t* prefix, uint32_t q) {
+    return prefix[q >> 5] + __popc(bits[q >> 5] & ((1u << (q & 31)) - 1u));
+}
+
+__global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
+    __shared__ uint32_t sel_bits[TK_WORDS], eq_bits[TK_WORDS], prefix[TK_WORDS];
+    const int row = blockIdx.y;
+    if (!s.rows[row].cand_mode) return;
+    const int lane = threadIdx.x;
+    const uint32_t nchunks = s.nchunks, chunk = blockIdx.x;
+    const size_t cidx = (size_t)row * nchunks + chunk;
+    const uint32_t off0 = s.out_off[(size_t)row * (nchunks + 1) + chunk];
+    const uint32_t off1 = s.out_off[(size_t)row * (nchunks + 1) + chunk + 1];
+    if (off0 == off1) return;                               // uniform
+    const uint32_t tau = s.rows[row].tau, r_tie = s.rows[row].r_tie;
+    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+    const uint32_t cnt = s.cand_cnt[cidx];
+    const uint2* slot = s.slots + cidx * TK_CAP;
+    const uint32_t eqb = s.eq_before[cidx];
+    const uint32_t quota = (eqb < r_tie) ? (r_tie - eqb) : 0u;   // ties of this chunk that belong to the set
+    const bool ties = s.cnt_eq[cidx] != 0 && quota != 0;
+    for (int w = lane; w < TK_WORDS; w += 64) { sel_bits[w] = 0; eq_bits[w] = 0; }
+    __syncthreads();
+    for (uint32_t p = lane; p < cnt; p += 64) {
+        const uint2 pr = slot[p];
+        const uint32_t key = pr.y & 0x7FFFFFFFu;
+        const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
+        if (q >= (uint32_t)TK_CHUNK) continue;
+        if (key > tau) atomicOr(&sel_bits[q >> 5], 1u << (q & 31));
+        else if (key == tau && ties) atomicOr(&eq_bits[q >> 5], 1u << (q & 31));
+    }
+    __syncthreads();
+    if (ties) {                                             // uniform
+        bitmap_prefix(eq_bits, prefix, lane);
+        __syncthreads();
+        for (int w = lane; w < TK_WORDS; w += 64) {
+            // keep the tied columns whose rank among the ties is below the quota
+            uint32_t word = eq_bits[w], keep = 0;
+            uint32_t rank = prefix[w];
+            while (word) {
+                const uint32_t bit = word & (0u - word);
+                if (rank < quota) keep |= bit;
+                ++rank;
+                word ^= bit;
+            }
+            sel_bits[w] |= keep;
+        }
+        __syncthreads();
+    }
+    bitmap_prefix(sel_bits, prefix, lane);
+    __syncthreads();
+    float* dr = a.delta + (uint64_t)row * a.ld;
+    uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
+    for (uint32_t p = lane; p < cnt; p += 64) {
+        const uint2 pr = slot[p];
+        const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
+        if (q >= (uint32_t)TK_CHUNK) continue;
+        if (sel_bits[q >> 5] & (1u << (q & 31))) {
+            const uint32_t pos = off0 + bitmap_rank(sel_bits, prefix, q);
+            if (pos < a.k && pos < off1) out[pos] = pr;
+            if (pr.x < a.N) dr[pr.x] = 0.f;                 // v - C[v] = v - v
+        }
+    }
+}
+
+// ---- the sparse part of line 9, applied in place (used when x must be complete right now) --------
 // One workgroup per (row, chunk): the neighbours' pairs that fall into the chunk are contiguous in
 // their messages (out_off), so they are accumulated in ascending neighbour order into an LDS copy
 // of the chunk and then applied once per touched column.
-__global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, const uint32_t* __restrict__ out_off, uint32_t nchunks) {
+__global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, Scratch s) {
     __shared__ float acc[TK_CHUNK];
     __shared__ uint32_t taken[TK_CHUNK / 32];
     const int row = blockIdx.y;
     const uint32_t c = blockIdx.x;
+    const uint32_t nchunks = s.nchunks;
     const uint64_t c0 = (uint64_t)c * TK_CHUNK;
     const int e0 = a.rowptr[row], e1 = a.rowptr[row + 1];
     bool any = false;
     for (int e = e0; e < e1; ++e) {
-        const uint32_t* off = out_off + (size_t)a.col[e] * (nchunks + 1) + c;
+        const uint32_t* off = s.out_off + (size_t)a.col[e] * (nchunks + 1) + c;
         any |= (off[0] != off[1]);
     }
     if (!any) return;                                       // uniform
@@ -337,7 +626,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, const uint
     for (int e = e0; e < e1; ++e) {
         const int nb = a.col[e];
         const float w = a.coef[e];
-        const uint32_t* off = out_off + (size_t)nb * (nchunks + 1) + c;
+        const uint32_t* off = s.out_off + (size_t)nb * (nchunks + 1) + c;
         const uint2* in = reinterpret_cast<const uint2*>(a.msg + (uint64_t)nb * a.k * 8);
         for (uint32_t p = off[0] + threadIdx.x; p < off[1]; p += TK_THREADS) {
             const uint2 pr = in[p];
@@ -349,7 +638,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, const uint
     float* xr = a.x + (uint64_t)row * a.ld;
     for (int e = e0; e < e1; ++e) {
         const int nb = a.col[e];
-        const uint32_t* off = out_off + (size_t)nb * (nchunks + 1) + c;
+        const uint32_t* off = s.out_off + (size_t)nb * (nchunks + 1) + c;
         const uint2* in = reinterpret_cast<const uint2*>(a.msg + (uint64_t)nb * a.k * 8);
         for (uint32_t p = off[0] + threadIdx.x; p < off[1]; p += TK_THREADS) {
             const uint32_t jj = in[p].x;
@@ -362,62 +651,104 @@ __global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, const uint
     }
 }
 
+__global__ void topk_init_rows(TopkRow* rows, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        TopkRow r{};
+        r.tlo = 0xFFFFFFFFu;                                // no guess yet: the first step runs in full mode
+        rows[i] = r;
+    }
+}
+
 }  // namespace
 
 struct TopkState {
-    uint32_t nchunks = 0;
+    Scratch s{};
     int n = 0;
-    uint32_t* hist = nullptr;
-    TopkRow* rows = nullptr;
-    uint32_t* cnt_gt = nullptr;
-    uint32_t* cnt_eq = nullptr;
-    uint32_t* eq_before = nullptr;
-    uint32_t* out_off = nullptr;
+    bool pending = false;          // the sparse part of the last step's line 9 has not been applied to x yet
+    TopkArgs last{};               // arguments of the last step (what the pending update needs)
 };
 
-void topk_destroy(TopkState* s) {
-    if (!s) return;
-    void* ptrs[] = {s->hist, s->rows, s->cnt_gt, s->cnt_eq, s->eq_before, s->out_off};
+void topk_destroy(TopkState* st) {
+    if (!st) return;
+    void* ptrs[] = {st->s.hist, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slots};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
-    delete s;
+    delete st;
 }
 
 ds_status topk_create(const ds_config& cfg, uint64_t /*ld*/, TopkState** out, std::string& err) {
-    TopkState* s = new TopkState();
-    s->n = cfg.n;
-    s->nchunks = (uint32_t)((cfg.N + TK_CHUNK - 1) / TK_CHUNK);
-    const size_t n = (size_t)cfg.n, nc = s->nchunks;
-    bool ok = hipMalloc(&s->hist, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&s->rows, n * sizeof(TopkRow)) == hipSuccess &&
-              hipMalloc(&s->cnt_gt, n * nc * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&s->cnt_eq, n * nc * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&s->eq_before, n * nc * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&s->out_off, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess;
-    ok = ok && hipMemset(s->hist, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
-         hipMemset(s->rows, 0, n * sizeof(TopkRow)) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    TopkState* st = new TopkState();
+    st->n = cfg.n;
+    Scratch& s = st->s;
+    s.nchunks = (uint32_t)((cfg.N + TK_CHUNK - 1) / TK_CHUNK);
+    const size_t n = (size_t)cfg.n, nc = s.nchunks;
+    bool ok = hipMalloc(&s.hist, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.rows, n * sizeof(TopkRow)) == hipSuccess &&
+              hipMalloc(&s.cnt_gt, n * nc * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.cnt_eq, n * nc * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.eq_before, n * nc * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.out_off, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.cand_cnt, n * nc * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.slots, n * nc * TK_CAP * sizeof(uint2)) == hipSuccess;
+    ok = ok && hipMemset(s.hist, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+         hipMemset(s.out_off, 0, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
+         hipMemset(s.cand_cnt, 0, n * nc * sizeof(uint32_t)) == hipSuccess;
+    if (ok) {
+        hipLaunchKernelGGL(topk_init_rows, dim3((cfg.n + 63) / 64), dim3(64), 0, 0, s.rows, cfg.n);
+        ok = hipDeviceSynchronize() == hipSuccess;
+    }
     if (!ok) {
         err = "top-k scratch allocation failed";
-        topk_destroy(s);
+        topk_destroy(st);
         return DS_ENOMEM;
     }
-    *out = s;
+    *out = st;
     return DS_OK;
 }
 
-ds_status topk_step(TopkState* s, const TopkArgs& a, const Graph& /*graph*/, hipStream_t stream, std::string& /*err*/) {
-    const dim3 grid(s->nchunks, a.n), block(TK_THREADS);
+ds_status topk_candidate_rows(TopkState* st, hipStream_t stream, uint32_t* count) {
+    std::vector<TopkRow> rows(st->n);
+    if (hipStreamSynchronize(stream) != hipSuccess) return DS_EHIP;
+    if (hipMemcpy(rows.data(), st->s.rows, rows.size() * sizeof(TopkRow), hipMemcpyDeviceToHost) != hipSuccess) return DS_EHIP;
+    uint32_t c = 0;
+    for (const TopkRow& r : rows) c += r.cand_mode ? 1u : 0u;
+    *count = c;
+    return DS_OK;
+}
+
+ds_status topk_flush(TopkState* st, hipStream_t stream) {
+    if (!st || !st->pending) return DS_OK;
+    const dim3 grid(st->s.nchunks, st->last.n), block(TK_THREADS);
+    hipLaunchKernelGGL(topk_gossip, grid, block, 0, stream, st->last, st->s);
+    st->pending = false;
+    return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
+}
+
+ds_status topk_step(TopkState* st, const TopkArgs& a, const Graph& /*graph*/, hipStream_t stream, std::string& /*err*/) {
+    const Scratch& s = st->s;
+    const dim3 grid(s.nchunks, a.n), block(TK_THREADS);
+    const dim3 cgrid((s.nchunks + TK_CPW - 1) / TK_CPW, a.n);
     const dim3 rows(a.n);
-    hipLaunchKernelGGL(topk_form_hist1, grid, block, 0, stream, a, s->hist);
-    hipLaunchKernelGGL(topk_select<1>, rows, block, 0, stream, s->hist, s->rows, (uint32_t)a.k);
-    hipLaunchKernelGGL(topk_hist_level<2>, grid, block, 0, stream, a.delta, a.ld, a.N, s->rows, s->hist, s->cnt_gt, s->cnt_eq, s->nchunks);
-    hipLaunchKernelGGL(topk_select<2>, rows, block, 0, stream, s->hist, s->rows, (uint32_t)a.k);
-    hipLaunchKernelGGL(topk_hist_level<3>, grid, block, 0, stream, a.delta, a.ld, a.N, s->rows, s->hist, s->cnt_gt, s->cnt_eq, s->nchunks);
-    hipLaunchKernelGGL(topk_select<3>, rows, block, 0, stream, s->hist, s->rows, (uint32_t)a.k);
-    hipLaunchKernelGGL(topk_fix_counts, grid, block, 0, stream, a.delta, a.ld, a.N, s->rows, s->cnt_gt, s->cnt_eq, s->nchunks);
-    hipLaunchKernelGGL(topk_scan_chunks, rows, block, 0, stream, s->rows, s->cnt_gt, s->cnt_eq, s->eq_before, s->out_off, s->nchunks);
-    hipLaunchKernelGGL(topk_write_selected, grid, block, 0, stream, a, s->rows, s->cnt_eq, s->eq_before, s->out_off, s->nchunks);
-    hipLaunchKernelGGL(topk_gossip, grid, block, 0, stream, a, s->out_off, s->nchunks);
+    const uint32_t k = (uint32_t)a.k;
+    if (st->pending) hipLaunchKernelGGL(topk_form_collect<true>, grid, block, 0, stream, a, s);
+    else             hipLaunchKernelGGL(topk_form_collect<false>, grid, block, 0, stream, a, s);
+    hipLaunchKernelGGL(topk_decide, rows, block, 0, stream, s, k);
+    hipLaunchKernelGGL(topk_hist_full<1>, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_select<1>, rows, block, 0, stream, s, k);
+    hipLaunchKernelGGL(topk_hist_cand<2>, cgrid, block, 0, stream, s);
+    hipLaunchKernelGGL(topk_hist_full<2>, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_select<2>, rows, block, 0, stream, s, k);
+    hipLaunchKernelGGL(topk_hist_cand<3>, cgrid, block, 0, stream, s);
+    hipLaunchKernelGGL(topk_hist_full<3>, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_select<3>, rows, block, 0, stream, s, k);
+    hipLaunchKernelGGL(topk_fix_cand, cgrid, block, 0, stream, s);
+    hipLaunchKernelGGL(topk_fix_full, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_scan_chunks, rows, block, 0, stream, s);
+    hipLaunchKernelGGL(topk_write_cand, grid, dim3(64), 0, stream, a, s);
+    hipLaunchKernelGGL(topk_write_full, grid, block, 0, stream, a, s);
+    st->pending = true;
+    st->last = a;
     return DS_OK;
 }
 

@@ -106,6 +106,9 @@ def free_run(w: wl.Config, steps, W=None):
             g_gpu = g_cpu = wl.gradient(w, t)
         ds.ds_step(upload(g_gpu))
         oracle.step(st, g_cpu, want_cv=False, want_msg=False)
+    if w.kind == wl.KIND_TOPK and steps >= 10 and w.N >= 100_000:
+        # by now the per-row threshold guesses have settled: the select runs on the candidate slots
+        assert ds.ds_topk_candidate_rows() == w.n, f"only {ds.ds_topk_candidate_rows()} of {w.n} rows on the fast path"
     x, d = ds.ds_read_state()
     for name, got, want in (("x", x, st.x), ("delta", d, st.delta)):
         num = np.linalg.norm(got.astype(np.float64) - want.astype(np.float64))
