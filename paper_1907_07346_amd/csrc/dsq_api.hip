@@ -302,6 +302,10 @@ ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count) {
     return dsq::topk_candidate_rows(h->topk, h->last_stream, count);
 }
 
+#ifdef DSQ_DEBUG_EXPORTS
+void* dsq_debug_topk_state(ds_handle* h) { return h ? h->topk : nullptr; }
+#endif
+
 uint64_t ds_step_count(const ds_handle* h) { return h ? h->t : 0; }
 
 const char* ds_plan_name(const ds_handle* h) { return h ? h->plan_name.c_str() : ""; }

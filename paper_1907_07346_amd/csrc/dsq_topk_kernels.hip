@@ -15,8 +15,8 @@
 //
 // Two sources feed the select, chosen per row on the device with no host round trip:
 //   * candidate mode (the fast path): the pass that forms v also appends every element whose key
-//     reaches a per-row guess `tlo` (a level-1 bin edge taken from the previous step, aimed at
-//     about 2.5 k elements) to a small per-chunk slot.  If at least k candidates were collected
+//     reaches a per-row guess `tlo` (extrapolated from the previous steps' thresholds, aimed at
+//     about 3 k elements) to a small per-chunk slot.  If at least k candidates were collected
 //     and no slot overflowed, the whole select runs on the slots (a few % of N) and v is never
 //     read again.
 //   * full mode (always exact, used on the first step and whenever the guess fails): the same
@@ -24,10 +24,11 @@
 // Both end in the same tau, r_tie, per-chunk counts and message, so results never depend on the
 // guess; only speed does.
 //
-// Line 9 is deferred: the first pass writes x = (x - gamma g) + 0, which already is the final
-// value of every column no neighbour sent; the sparse remainder eta * sum_j a_ij C[v_j] is
-// folded into the NEXT step's first pass (which streams x anyway), or applied by topk_flush
-// before anyone else looks at x.
+// The sparse tail of a step is deferred: the first pass writes x = (x - gamma g) + 0 and
+// delta = v, which already are the final values of every column nobody sent; the remainder --
+// delta = 0 where this worker sent v (line 6) and eta * sum_j a_ij C[v_j] where a neighbour did
+// (line 9) -- is folded into the NEXT step's first pass (which streams x and delta anyway), or
+// applied by topk_flush before anyone else looks at the state.
 
 #include "dsq_internal.h"
 
@@ -37,10 +38,14 @@ namespace {
 
 constexpr int TK_THREADS = 256;
 constexpr int TK_VEC = 4 * TK_THREADS;       // elements per workgroup iteration
-constexpr int TK_ITERS = 8;
+constexpr int TK_ITERS = 4;
 constexpr int TK_CHUNK = TK_VEC * TK_ITERS;  // columns per chunk (one workgroup of the streaming passes)
-constexpr int TK_CAP = 1024;                 // candidate slots per chunk (12.5 % of the chunk)
-constexpr int TK_CPW = 8;                    // chunks per workgroup in the candidate-mode kernels
+constexpr int TK_CAP = 512;                  // candidate slots per chunk (12.5 % of the chunk)
+constexpr int TK_H1 = 256;                   // level-1 bins the first pass tracks, counted from tlo's bin upwards
+constexpr int TK_CPW = 8;                    // chunks per workgroup in topk_fix_cand
+constexpr int TK_FPW = 8;                    // chunks per workgroup in the full-mode kernels (few, cheap-to-skip workgroups)
+constexpr int TK_HWG = 16;                   // workgroups per row in the candidate-mode histogram passes
+constexpr int TK_HTHREADS = 1024;            // threads of those workgroups
 constexpr int BINS1 = 2048, SHIFT1 = 20;     // key bits 30..20
 constexpr int BINS2 = 2048, SHIFT2 = 9;      // key bits 19..9
 constexpr int BINS3 = 512;                   // key bits 8..0
@@ -55,6 +60,8 @@ struct TopkRow {
     uint32_t cand_mode;        // 1: this step's select runs on the candidate slots
     uint32_t overflow;         // a slot overflowed in this step's first pass
     uint32_t cand_total;       // candidates collected in this step
+    uint32_t tlo_used;         // the threshold this step's first pass collected with
+    uint32_t tau_prev;         // threshold key of the previous step (0xffffffff: none yet)
     uint32_t pad;
 };
 
@@ -115,13 +122,14 @@ struct Scratch {               // device pointers of the select's scratch (all o
 template <bool PENDING>
 __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scratch s) {
     __shared__ float acc[PENDING ? TK_CHUNK : 1];
-    __shared__ uint32_t h[HIST_BINS];                          // level-1 digits of the candidates
+    __shared__ uint32_t own[PENDING ? TK_CHUNK / 32 : 1];       // columns this worker itself sent in the previous step
+    __shared__ uint32_t h[TK_H1];                              // level-1 digits of the candidates, relative to tlo's
     __shared__ uint32_t cand_count;
     const int row = blockIdx.y;
     const uint32_t chunk = blockIdx.x;
     const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
     if (threadIdx.x == 0) cand_count = 0;
-    for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS) h[b] = 0;
+    for (int b = threadIdx.x; b < TK_H1; b += TK_THREADS) h[b] = 0;
     bool patch = false;
     if (PENDING) {
         // eta * sum_j a_ij C[v_j] of the previous step for this chunk: the neighbours' pairs that fall
@@ -133,6 +141,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
         }
         if (patch) {                                           // uniform
             for (int q = threadIdx.x; q < TK_CHUNK; q += TK_THREADS) acc[q] = 0.f;
+            for (int q = threadIdx.x; q < TK_CHUNK / 32; q += TK_THREADS) own[q] = 0u;
             __syncthreads();
             for (int e = e0; e < e1; ++e) {
                 const int nb = a.col[e];
@@ -142,7 +151,10 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
                 for (uint32_t p = off[0] + threadIdx.x; p < off[1]; p += TK_THREADS) {
                     const uint2 pr = in[p];
                     const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
-                    if (q < (uint32_t)TK_CHUNK) acc[q] = fmaf(w, __uint_as_float(pr.y), acc[q]);
+                    if (q < (uint32_t)TK_CHUNK) {
+                        acc[q] = fmaf(w, __uint_as_float(pr.y), acc[q]);
+                        if (nb == row) atomicOr(&own[q >> 5], 1u << (q & 31));
+                    }
                 }
                 __syncthreads();
             }
@@ -150,6 +162,8 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     }
     __syncthreads();
     const uint32_t tlo = s.rows[row].tlo;
+    const uint32_t bin0 = tlo >> SHIFT1;                       // (0xfff for "collect nothing")
+    bool far = false;                                          // a candidate beyond the tracked bins
     uint2* slot = s.slots + ((size_t)row * s.nchunks + chunk) * TK_CAP;
     float* xr = a.x + (uint64_t)row * a.ld;
     float* dr = a.delta + (uint64_t)row * a.ld;
@@ -160,7 +174,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
         const uint64_t j = c0 + q0;
         if (j >= a.ld) break;
         float4 xv = ld4_stream(xr + j);
-        const float4 dv = ld4_stream(dr + j);
+        float4 dv = ld4_stream(dr + j);
         float4 gv;
         if (j + 3 < a.N) {
             gv = ld4_stream(gr + j);
@@ -170,9 +184,14 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
             gv.z = (j + 2 < a.N) ? gr[j + 2] : 0.f;
             gv.w = (j + 3 < a.N) ? gr[j + 3] : 0.f;
         }
-        if (PENDING && patch) {                                // line 9 of the previous step
+        if (PENDING && patch) {                                // lines 6 and 9 of the previous step
             xv.x = fmaf(a.eta, acc[q0 + 0], xv.x); xv.y = fmaf(a.eta, acc[q0 + 1], xv.y);
             xv.z = fmaf(a.eta, acc[q0 + 2], xv.z); xv.w = fmaf(a.eta, acc[q0 + 3], xv.w);
+            const uint32_t sent = own[q0 >> 5] >> (q0 & 31);   // delta = v - C[v] = 0 where v was sent
+            if (sent & 1u) dv.x = 0.f;
+            if (sent & 2u) dv.y = 0.f;
+            if (sent & 4u) dv.z = 0.f;
+            if (sent & 8u) dv.w = 0.f;
         }
         float4 xh, v;
         xh.x = fmaf(-a.gamma, gv.x, xv.x); v.x = xh.x + dv.x;
@@ -189,15 +208,17 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
             if (j + c < a.N && key_of(vv[c]) >= tlo) {
                 const uint32_t idx = atomicAdd(&cand_count, 1u);
                 if (idx < (uint32_t)TK_CAP) slot[idx] = make_uint2((uint32_t)(j + c), __float_as_uint(vv[c]));
-                atomicAdd(&h[key_of(vv[c]) >> SHIFT1], 1u);
+                const uint32_t rel = (key_of(vv[c]) >> SHIFT1) - bin0;
+                if (rel < (uint32_t)TK_H1) atomicAdd(&h[rel], 1u); else far = true;
             }
     }
     __syncthreads();
-    // only bins from tlo's upward can be non-empty; the row histogram is used if the row ends up in
-    // candidate mode and wiped by topk_decide otherwise
+    // the row histogram is used if the row ends up in candidate mode and wiped by topk_decide otherwise;
+    // a candidate beyond the tracked bins (256 bins = 2^32 in magnitude above tlo) sends the row there too
     uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
-    for (int b = (int)(tlo >> SHIFT1 < (uint32_t)HIST_BINS ? tlo >> SHIFT1 : (uint32_t)HIST_BINS) + threadIdx.x; b < HIST_BINS; b += TK_THREADS)
-        if (h[b]) atomicAdd(&hrow[b], h[b]);
+    for (int b = threadIdx.x; b < TK_H1; b += TK_THREADS)
+        if (h[b]) atomicAdd(&hrow[bin0 + b], h[b]);
+    if (far) atomicOr(&s.rows[row].overflow, 1u);
     if (threadIdx.x == 0) {
         const uint32_t c = cand_count;
         s.cand_cnt[(size_t)row * s.nchunks + chunk] = c < (uint32_t)TK_CAP ? c : (uint32_t)TK_CAP;
@@ -221,6 +242,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_decide(Scratch s, uint32_t k)
         r.cand_total = total;
         r.cand_mode = cand ? 1u : 0u;
         r.overflow = 0;
+        r.tlo_used = r.tlo;
     }
 }
 
@@ -245,84 +267,108 @@ __global__ void __launch_bounds__(TK_THREADS) topk_hist_full(const float* __rest
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
     if (s.rows[row].cand_mode) return;                         // uniform
-    const uint64_t c0 = (uint64_t)blockIdx.x * TK_CHUNK;
     constexpr int BINS = (LEVEL == 3) ? BINS3 : HIST_BINS;
     for (int b = threadIdx.x; b < BINS; b += TK_THREADS) h[b] = 0;
     __syncthreads();
     const uint32_t prefix = (LEVEL == 2) ? s.rows[row].prefix1 : (LEVEL == 3) ? s.rows[row].prefix2 : 0u;
     const float* dr = delta + (uint64_t)row * ld;
-    uint32_t gt = 0, eq = 0;
+    for (uint32_t chunk = blockIdx.x * TK_FPW; chunk < (blockIdx.x + 1) * TK_FPW && chunk < s.nchunks; ++chunk) {
+        const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+        uint32_t gt = 0, eq = 0;
 #pragma unroll 2
-    for (int it = 0; it < TK_ITERS; ++it) {
-        const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
-        if (j >= ld) break;
-        const float4 v = *reinterpret_cast<const float4*>(dr + j);
-        const float vv[4] = {v.x, v.y, v.z, v.w};
+        for (int it = 0; it < TK_ITERS; ++it) {
+            const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
+            if (j >= ld) break;
+            const float4 v = *reinterpret_cast<const float4*>(dr + j);
+            const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (j + c < N) hist_key<LEVEL>(key_of(vv[c]), prefix, h, gt, eq);
+            for (int c = 0; c < 4; ++c)
+                if (j + c < N) hist_key<LEVEL>(key_of(vv[c]), prefix, h, gt, eq);
+        }
+        if (LEVEL == 3) {
+            const uint32_t gts = block_sum(gt, wave_sums);
+            const uint32_t eqs = block_sum(eq, wave_sums);
+            if (threadIdx.x == 0) {
+                s.cnt_gt[(size_t)row * s.nchunks + chunk] = gts;
+                s.cnt_eq[(size_t)row * s.nchunks + chunk] = eqs;
+            }
+        }
     }
     __syncthreads();
     uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
     for (int b = threadIdx.x; b < BINS; b += TK_THREADS)
         if (h[b]) atomicAdd(&hrow[b], h[b]);
-    if (LEVEL == 3) {
-        const uint32_t gts = block_sum(gt, wave_sums);
-        const uint32_t eqs = block_sum(eq, wave_sums);
-        if (threadIdx.x == 0) {
-            s.cnt_gt[(size_t)row * s.nchunks + blockIdx.x] = gts;
-            s.cnt_eq[(size_t)row * s.nchunks + blockIdx.x] = eqs;
-        }
-    }
 }
 
+// Candidate mode: TK_HWG workgroups of 1024 threads per row, each walking a contiguous range of chunks
+// with 32 lanes per chunk (32 chunks side by side) and 8 slot loads in flight per lane.  Few, large
+// workgroups keep the number of global histogram atomics down (one flush of <= 2048 bins each).
 template <int LEVEL>
-__global__ void __launch_bounds__(TK_THREADS) topk_hist_cand(Scratch s) {
+__global__ void __launch_bounds__(TK_HTHREADS) topk_hist_cand(Scratch s) {
     __shared__ uint32_t h[HIST_BINS];
-    __shared__ uint32_t c_gt[TK_CPW], c_eq[TK_CPW];
     const int row = blockIdx.y;
     if (!s.rows[row].cand_mode) return;                        // uniform
     constexpr int BINS = (LEVEL == 3) ? BINS3 : HIST_BINS;
-    for (int b = threadIdx.x; b < BINS; b += TK_THREADS) h[b] = 0;
-    if (threadIdx.x < TK_CPW) { c_gt[threadIdx.x] = 0; c_eq[threadIdx.x] = 0; }
+    for (int b = threadIdx.x; b < BINS; b += TK_HTHREADS) h[b] = 0;
     __syncthreads();
     const uint32_t prefix = (LEVEL == 2) ? s.rows[row].prefix1 : s.rows[row].prefix2;
-    // 32 threads per chunk, TK_CPW chunks side by side
-    constexpr int TPC = TK_THREADS / TK_CPW;
-    const int ci = threadIdx.x / TPC, sub = threadIdx.x % TPC;
-    const uint32_t chunk = blockIdx.x * TK_CPW + ci;
-    uint32_t gt = 0, eq = 0;
-    if (chunk < s.nchunks) {
+    constexpr int TPC = 32, SIDE = TK_HTHREADS / TPC;          // lanes per chunk, chunks side by side
+    const int sub = threadIdx.x % TPC;
+    const uint32_t per_wg = (s.nchunks + TK_HWG - 1) / TK_HWG;
+    const uint32_t first = blockIdx.x * per_wg;
+    const uint32_t last = (first + per_wg < s.nchunks) ? first + per_wg : s.nchunks;
+    for (uint32_t chunk = first + threadIdx.x / TPC; chunk < last; chunk += SIDE) {
         const size_t cidx = (size_t)row * s.nchunks + chunk;
         const uint32_t cnt = s.cand_cnt[cidx];
         const uint2* slot = s.slots + cidx * TK_CAP;
-        for (uint32_t p0 = sub; p0 < cnt; p0 += 4 * TPC) {
-            uint32_t key[4];
+        uint32_t gt = 0, eq = 0;
+        for (uint32_t p0 = sub; p0 < cnt; p0 += 8 * TPC) {
+            uint32_t key[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+            for (int u = 0; u < 8; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < 8; ++u)
                 if (key[u] != 0xFFFFFFFFu) hist_key<LEVEL>(key[u], prefix, h, gt, eq);
         }
-    }
-    if (LEVEL == 3) {
-        if (gt) atomicAdd(&c_gt[ci], gt);
-        if (eq) atomicAdd(&c_eq[ci], eq);
+        if (LEVEL == 3) {
+            // the 32 lanes of a chunk are half a wave: fold with shuffles inside the half
+#pragma unroll
+            for (int o = 1; o < TPC; o <<= 1) { gt += __shfl_xor(gt, o); eq += __shfl_xor(eq, o); }
+            if (sub == 0) { s.cnt_gt[cidx] = gt; s.cnt_eq[cidx] = eq; }
+        }
     }
     __syncthreads();
     uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
-    for (int b = threadIdx.x; b < BINS; b += TK_THREADS)
+    for (int b = threadIdx.x; b < BINS; b += TK_HTHREADS)
         if (h[b]) atomicAdd(&hrow[b], h[b]);
-    const uint32_t chunk0 = blockIdx.x * TK_CPW;
-    if (LEVEL == 3 && threadIdx.x < TK_CPW && chunk0 + threadIdx.x < s.nchunks) {
-        s.cnt_gt[(size_t)row * s.nchunks + chunk0 + threadIdx.x] = c_gt[threadIdx.x];
-        s.cnt_eq[(size_t)row * s.nchunks + chunk0 + threadIdx.x] = c_eq[threadIdx.x];
+}
+
+// ---- where to collect candidates in the next step ------------------------------------------------
+// Keys are (piecewise) logarithmic in |v|, and near the threshold the number of keys above a level
+// falls roughly exponentially with the level.  With d = tau - tlo the distance that caught
+// ratio * k candidates this step, the distance that would catch 3 k is d* = d ln 3 / ln ratio.  The
+// threshold itself moves from step to step (delta keeps growing early in a run), so the next level
+// is aimed at tau + drift - d*, but never closer to tau than d*/2 (at least ~1.7 k candidates if
+// the drift stops).  Without usable candidates (full mode) a fixed distance of two level-1 bins is
+// taken.  Only speed depends on this guess; a bad one sends the row through the exact full path.
+__device__ __forceinline__ uint32_t next_candidate_threshold(const TopkRow& r, uint32_t tau, uint32_t k) {
+    const float d0 = 2.f * (float)(1u << SHIFT1);
+    float dstar = d0;
+    if (r.cand_mode && r.cand_total > k && tau > r.tlo_used) {
+        const float ratio = (float)r.cand_total / (float)k;
+        const float d = (float)(tau - r.tlo_used);
+        dstar = d * (1.0986123f / logf(ratio));
+        dstar = fminf(fmaxf(dstar, 1024.f), 4.f * d0);
     }
+    float drift = 0.f;
+    if (r.tau_prev != 0xFFFFFFFFu && tau > r.tau_prev) drift = fminf((float)(tau - r.tau_prev), 8.f * d0);
+    const float down = fmaxf(dstar - drift, 0.5f * dstar);     // how far below tau to collect
+    const float t = (float)tau - down;
+    return t > 0.f ? (uint32_t)t : 0u;
 }
 
 // ---- per-row digit select: the bin where the count from the top crosses `need` -----------------
-// Level 1 also fixes the candidate threshold of the next step: the lower edge of the bin where the
-// count from the top crosses about 2.5 k, or one bin further down if too few keys are in sight.
+// Level 3 ends with the threshold key and also aims the candidate collection of the next step.
 template <int LEVEL>
 __global__ void __launch_bounds__(TK_THREADS) topk_select(Scratch s, uint32_t k) {
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
@@ -332,10 +378,6 @@ __global__ void __launch_bounds__(TK_THREADS) topk_select(Scratch s, uint32_t k)
     uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
     TopkRow& r = s.rows[row];
     const uint32_t need = (LEVEL == 1) ? k : (LEVEL == 2) ? r.need1 : r.need2;
-    const uint64_t want64 = (uint64_t)k * 5 / 2;
-    const uint32_t want = want64 > 0xFFFFFFFFull ? 0xFFFFFFFFu : (uint32_t)want64;
-    const uint32_t old_tlo = r.tlo;
-    const uint32_t was_cand = r.cand_mode;
     // thread t owns bins [top - 8t - 7, top - 8t], i.e. threads are ordered from the largest keys down
     uint32_t mine[PER];
     uint32_t sum = 0;
@@ -348,15 +390,6 @@ __global__ void __launch_bounds__(TK_THREADS) topk_select(Scratch s, uint32_t k)
     uint32_t total;
     uint32_t above = block_exclusive_scan(sum, wave_sums, &total);   // keys in strictly higher bins
     __syncthreads();
-    if (LEVEL == 1 && threadIdx.x == 0 && total < want) {
-        // not enough keys in sight to aim: look one level-1 bin further down next time
-        uint32_t nt = 0;
-        if (was_cand && old_tlo != 0xFFFFFFFFu) {
-            const uint32_t bin = old_tlo >> SHIFT1;
-            nt = bin > 0 ? (bin - 1) << SHIFT1 : 0u;
-        }
-        r.tlo = nt;
-    }
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
         const int b = HIST_BINS - 1 - (threadIdx.x * PER + q);
@@ -364,9 +397,14 @@ __global__ void __launch_bounds__(TK_THREADS) topk_select(Scratch s, uint32_t k)
             const uint32_t rem = need - above;
             if (LEVEL == 1)      { r.prefix1 = (uint32_t)b; r.need1 = rem; }
             else if (LEVEL == 2) { r.prefix2 = (r.prefix1 << (SHIFT1 - SHIFT2)) | (uint32_t)b; r.need2 = rem; }
-            else                 { r.tau = (r.prefix2 << SHIFT2) | (uint32_t)b; r.r_tie = rem; }
+            else {
+                const uint32_t tau = (r.prefix2 << SHIFT2) | (uint32_t)b;
+                r.tlo = next_candidate_threshold(r, tau, k);
+                r.tau_prev = tau;
+                r.tau = tau;
+                r.r_tie = rem;
+            }
         }
-        if (LEVEL == 1 && above < want && want <= above + mine[q]) r.tlo = (uint32_t)b << SHIFT1;
         above += mine[q];
         hrow[b] = 0;                                      // leave the histogram clean for the next pass
     }
@@ -377,28 +415,30 @@ __global__ void __launch_bounds__(TK_THREADS) topk_fix_full(const float* __restr
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
     if (s.rows[row].cand_mode) return;
-    const size_t ci = (size_t)row * s.nchunks + blockIdx.x;
-    if (s.cnt_eq[ci] == 0) return;                        // uniform: nothing in this chunk can tie or straddle
     const uint32_t tau = s.rows[row].tau;
-    const uint64_t c0 = (uint64_t)blockIdx.x * TK_CHUNK;
     const float* dr = delta + (uint64_t)row * ld;
-    uint32_t gt = 0, eq = 0;
-    for (int it = 0; it < TK_ITERS; ++it) {
-        const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
-        if (j >= ld) break;
-        const float4 v = *reinterpret_cast<const float4*>(dr + j);
-        const float vv[4] = {v.x, v.y, v.z, v.w};
+    for (uint32_t chunk = blockIdx.x * TK_FPW; chunk < (blockIdx.x + 1) * TK_FPW && chunk < s.nchunks; ++chunk) {
+        const size_t ci = (size_t)row * s.nchunks + chunk;
+        if (s.cnt_eq[ci] == 0) continue;                  // uniform: nothing in this chunk can tie or straddle
+        const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+        uint32_t gt = 0, eq = 0;
+        for (int it = 0; it < TK_ITERS; ++it) {
+            const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
+            if (j >= ld) break;
+            const float4 v = *reinterpret_cast<const float4*>(dr + j);
+            const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (j + c < N) {
-                const uint32_t key = key_of(vv[c]);
-                gt += key > tau;
-                eq += key == tau;
-            }
+            for (int c = 0; c < 4; ++c)
+                if (j + c < N) {
+                    const uint32_t key = key_of(vv[c]);
+                    gt += key > tau;
+                    eq += key == tau;
+                }
+        }
+        const uint32_t gts = block_sum(gt, wave_sums);
+        const uint32_t eqs = block_sum(eq, wave_sums);
+        if (threadIdx.x == 0) { s.cnt_gt[ci] = gts; s.cnt_eq[ci] = eqs; }
     }
-    const uint32_t gts = block_sum(gt, wave_sums);
-    const uint32_t eqs = block_sum(eq, wave_sums);
-    if (threadIdx.x == 0) { s.cnt_gt[ci] = gts; s.cnt_eq[ci] = eqs; }
 }
 
 __global__ void __launch_bounds__(TK_THREADS) topk_fix_cand(Scratch s) {
@@ -462,20 +502,17 @@ __global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(Scratch s) {
 }
 
 // ---- ordered compaction: message pairs, delta <- 0 on the selected set (Algorithm 1, line 6) ----
-__global__ void __launch_bounds__(TK_THREADS) topk_write_full(TopkArgs a, Scratch s) {
-    __shared__ uint32_t wave_sums[TK_THREADS / 64];
-    const int row = blockIdx.y;
-    if (s.rows[row].cand_mode) return;
+__device__ __forceinline__ void write_full_chunk(const TopkArgs& a, const Scratch& s, int row, uint32_t chunk, uint32_t* wave_sums) {
     const uint32_t nchunks = s.nchunks;
-    const size_t ci = (size_t)row * nchunks + blockIdx.x;
-    const uint32_t off0 = s.out_off[(size_t)row * (nchunks + 1) + blockIdx.x];
-    const uint32_t off1 = s.out_off[(size_t)row * (nchunks + 1) + blockIdx.x + 1];
-    if (off0 == off1) return;
+    const size_t ci = (size_t)row * nchunks + chunk;
+    const uint32_t off0 = s.out_off[(size_t)row * (nchunks + 1) + chunk];
+    const uint32_t off1 = s.out_off[(size_t)row * (nchunks + 1) + chunk + 1];
+    if (off0 == off1) return;                               // uniform
     const bool ties = s.cnt_eq[ci] != 0;
     const uint32_t tau = s.rows[row].tau, r_tie = s.rows[row].r_tie;
     uint32_t run_eq = s.eq_before[ci], run_out = off0;
-    const uint64_t c0 = (uint64_t)blockIdx.x * TK_CHUNK;
-    float* dr = a.delta + (uint64_t)row * a.ld;
+    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+    const float* dr = a.delta + (uint64_t)row * a.ld;
     uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
     for (int it = 0; it < TK_ITERS; ++it) {
         const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
@@ -512,10 +549,17 @@ __global__ void __launch_bounds__(TK_THREADS) topk_write_full(TopkArgs a, Scratc
             if (sel[c]) {
                 if (pos < a.k) out[pos] = make_uint2((uint32_t)(j + c), __float_as_uint(vv[c]));
                 ++pos;
-                dr[j + c] = 0.f;                            // v - C[v] = v - v
             }
         run_out += tot;
     }
+}
+
+__global__ void __launch_bounds__(TK_THREADS) topk_write_full(TopkArgs a, Scratch s) {
+    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    const int row = blockIdx.y;
+    if (s.rows[row].cand_mode) return;
+    for (uint32_t chunk = blockIdx.x * TK_FPW; chunk < (blockIdx.x + 1) * TK_FPW && chunk < s.nchunks; ++chunk)
+        write_full_chunk(a, s, row, chunk, wave_sums);
 }
 
 // Candidate mode, one wave per chunk.  A slot is unordered, so order comes from two bitmaps over the
@@ -558,13 +602,21 @@ __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
     const uint32_t eqb = s.eq_before[cidx];
     const uint32_t quota = (eqb < r_tie) ? (r_tie - eqb) : 0u;   // ties of this chunk that belong to the set
     const bool ties = s.cnt_eq[cidx] != 0 && quota != 0;
+    // the whole slot goes into registers (16 pairs per lane, all loads in flight at once)
+    constexpr int EPL = TK_CAP / 64;
+    uint2 ent[EPL];
+#pragma unroll
+    for (int u = 0; u < EPL; ++u) {
+        const uint32_t p = (uint32_t)u * 64 + lane;
+        ent[u] = (p < cnt) ? slot[p] : make_uint2(0xFFFFFFFFu, 0u);
+    }
     for (int w = lane; w < TK_WORDS; w += 64) { sel_bits[w] = 0; eq_bits[w] = 0; }
     __syncthreads();
-    for (uint32_t p = lane; p < cnt; p += 64) {
-        const uint2 pr = slot[p];
-        const uint32_t key = pr.y & 0x7FFFFFFFu;
-        const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
-        if (q >= (uint32_t)TK_CHUNK) continue;
+#pragma unroll
+    for (int u = 0; u < EPL; ++u) {
+        const uint32_t key = ent[u].y & 0x7FFFFFFFu;
+        const uint32_t q = (uint32_t)((uint64_t)ent[u].x - c0);
+        if (q >= (uint32_t)TK_CHUNK) continue;              // also the padding pairs
         if (key > tau) atomicOr(&sel_bits[q >> 5], 1u << (q & 31));
         else if (key == tau && ties) atomicOr(&eq_bits[q >> 5], 1u << (q & 31));
     }
@@ -588,21 +640,20 @@ __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
     }
     bitmap_prefix(sel_bits, prefix, lane);
     __syncthreads();
-    float* dr = a.delta + (uint64_t)row * a.ld;
     uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
-    for (uint32_t p = lane; p < cnt; p += 64) {
-        const uint2 pr = slot[p];
+#pragma unroll
+    for (int u = 0; u < EPL; ++u) {
+        const uint2 pr = ent[u];
         const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
         if (q >= (uint32_t)TK_CHUNK) continue;
         if (sel_bits[q >> 5] & (1u << (q & 31))) {
             const uint32_t pos = off0 + bitmap_rank(sel_bits, prefix, q);
             if (pos < a.k && pos < off1) out[pos] = pr;
-            if (pr.x < a.N) dr[pr.x] = 0.f;                 // v - C[v] = v - v
         }
     }
 }
 
-// ---- the sparse part of line 9, applied in place (used when x must be complete right now) --------
+// ---- the deferred sparse tail of a step, applied in place (when the state must be complete now) --
 // One workgroup per (row, chunk): the neighbours' pairs that fall into the chunk are contiguous in
 // their messages (out_off), so they are accumulated in ascending neighbour order into an LDS copy
 // of the chunk and then applied once per touched column.
@@ -636,6 +687,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, Scratch s)
         __syncthreads();
     }
     float* xr = a.x + (uint64_t)row * a.ld;
+    float* dr = a.delta + (uint64_t)row * a.ld;
     for (int e = e0; e < e1; ++e) {
         const int nb = a.col[e];
         const uint32_t* off = s.out_off + (size_t)nb * (nchunks + 1) + c;
@@ -644,6 +696,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, Scratch s)
             const uint32_t jj = in[p].x;
             const uint32_t q = (uint32_t)((uint64_t)jj - c0);
             if (q >= (uint32_t)TK_CHUNK || jj >= a.N) continue;
+            if (nb == row) dr[jj] = 0.f;                    // line 6: delta = v - C[v] = 0 where v was sent
             const uint32_t bit = 1u << (q & 31);
             const uint32_t old = atomicOr(&taken[q >> 5], bit);
             if (!(old & bit)) xr[jj] = fmaf(a.eta, acc[q], xr[jj]);
@@ -656,6 +709,7 @@ __global__ void topk_init_rows(TopkRow* rows, int n) {
     if (i < n) {
         TopkRow r{};
         r.tlo = 0xFFFFFFFFu;                                // no guess yet: the first step runs in full mode
+        r.tau_prev = 0xFFFFFFFFu;
         rows[i] = r;
     }
 }
@@ -717,6 +771,13 @@ ds_status topk_candidate_rows(TopkState* st, hipStream_t stream, uint32_t* count
     return DS_OK;
 }
 
+#ifdef DSQ_DEBUG_EXPORTS
+extern "C" int dsq_debug_topk_rows(TopkState* st, uint32_t* out) {   // 12 words per row
+    (void)hipDeviceSynchronize();
+    return (int)hipMemcpy(out, st->s.rows, (size_t)st->n * sizeof(TopkRow), hipMemcpyDeviceToHost);
+}
+#endif
+
 ds_status topk_flush(TopkState* st, hipStream_t stream) {
     if (!st || !st->pending) return DS_OK;
     const dim3 grid(st->s.nchunks, st->last.n), block(TK_THREADS);
@@ -729,24 +790,26 @@ ds_status topk_step(TopkState* st, const TopkArgs& a, const Graph& /*graph*/, hi
     const Scratch& s = st->s;
     const dim3 grid(s.nchunks, a.n), block(TK_THREADS);
     const dim3 cgrid((s.nchunks + TK_CPW - 1) / TK_CPW, a.n);
+    const dim3 fgrid((s.nchunks + TK_FPW - 1) / TK_FPW, a.n);
+    const dim3 hgrid(TK_HWG, a.n), hblock(TK_HTHREADS);
     const dim3 rows(a.n);
     const uint32_t k = (uint32_t)a.k;
     if (st->pending) hipLaunchKernelGGL(topk_form_collect<true>, grid, block, 0, stream, a, s);
     else             hipLaunchKernelGGL(topk_form_collect<false>, grid, block, 0, stream, a, s);
     hipLaunchKernelGGL(topk_decide, rows, block, 0, stream, s, k);
-    hipLaunchKernelGGL(topk_hist_full<1>, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_hist_full<1>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
     hipLaunchKernelGGL(topk_select<1>, rows, block, 0, stream, s, k);
-    hipLaunchKernelGGL(topk_hist_cand<2>, cgrid, block, 0, stream, s);
-    hipLaunchKernelGGL(topk_hist_full<2>, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_hist_cand<2>, hgrid, hblock, 0, stream, s);
+    hipLaunchKernelGGL(topk_hist_full<2>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
     hipLaunchKernelGGL(topk_select<2>, rows, block, 0, stream, s, k);
-    hipLaunchKernelGGL(topk_hist_cand<3>, cgrid, block, 0, stream, s);
-    hipLaunchKernelGGL(topk_hist_full<3>, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_hist_cand<3>, hgrid, hblock, 0, stream, s);
+    hipLaunchKernelGGL(topk_hist_full<3>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
     hipLaunchKernelGGL(topk_select<3>, rows, block, 0, stream, s, k);
     hipLaunchKernelGGL(topk_fix_cand, cgrid, block, 0, stream, s);
-    hipLaunchKernelGGL(topk_fix_full, grid, block, 0, stream, a.delta, a.ld, a.N, s);
+    hipLaunchKernelGGL(topk_fix_full, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
     hipLaunchKernelGGL(topk_scan_chunks, rows, block, 0, stream, s);
     hipLaunchKernelGGL(topk_write_cand, grid, dim3(64), 0, stream, a, s);
-    hipLaunchKernelGGL(topk_write_full, grid, block, 0, stream, a, s);
+    hipLaunchKernelGGL(topk_write_full, fgrid, block, 0, stream, a, s);
     st->pending = true;
     st->last = a;
     return DS_OK;
