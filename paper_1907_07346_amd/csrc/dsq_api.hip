@@ -170,6 +170,15 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
             return bail(DS_EINVAL);
         }
         h->tile = h->tile_candidates.front();
+        // DSQ_TILE_PLAN=<i> pins the i-th candidate launch shape (tests walk through all of them)
+        const char* pinned = std::getenv("DSQ_TILE_PLAN");
+        if (pinned && *pinned) {
+            const size_t i = (size_t)std::strtoull(pinned, nullptr, 10);
+            if (i < h->tile_candidates.size()) {
+                h->tile = h->tile_candidates[i];
+                h->tile_candidates.assign(1, h->tile);
+            }
+        }
     }
 
     hipError_t e = hipGetDevice(&h->device);

@@ -164,6 +164,24 @@ def test_gradient_pitch_larger_than_N(w):
     lock_step(w, steps=2, pitch=((w.N + 3) // 4) * 4 + 64)
 
 
+@pytest.mark.parametrize("w", [SMALL[1], SMALL[4], SMALL[5], SMALL[9], SMALL[12]], ids=lambda w: w.name)
+def test_every_candidate_launch_shape(w, monkeypatch):
+    # ds_init picks the launch shape by timing; here each candidate is pinned in turn and checked
+    seen = []
+    for i in range(12):
+        monkeypatch.setenv("DSQ_TILE_PLAN", str(i))
+        ds = b.DeepSqueeze.from_workload(w)
+        name = ds.ds_plan_name()
+        ds.ds_destroy()
+        if name in seen:                                   # index past the end: the default came back
+            break
+        seen.append(name)
+        say("case", w.name, "plan", name)
+        lock_step(w, steps=2)
+    monkeypatch.delenv("DSQ_TILE_PLAN")
+    assert len(seen) >= 2, seen
+
+
 def test_general_graph_csr():
     # symmetric doubly stochastic W of an irregular graph (degrees 2..5), given in CSR form
     n = 10
