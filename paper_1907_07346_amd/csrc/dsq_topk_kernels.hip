@@ -348,9 +348,8 @@ __global__ void __launch_bounds__(TK_HTHREADS) topk_hist_cand(Scratch s) {
 // falls roughly exponentially with the level.  With d = tau - tlo the distance that caught
 // ratio * k candidates this step, the distance that would catch 3 k is d* = d ln 3 / ln ratio.  The
 // threshold itself moves from step to step (delta keeps growing early in a run), so the next level
-// is aimed at tau + drift - d*, but never closer to tau than d*/2 (at least ~1.7 k candidates if
-// the drift stops).  Without usable candidates (full mode) a fixed distance of two level-1 bins is
-// taken.  Only speed depends on this guess; a bad one sends the row through the exact full path.
+// is aimed at tau + 3/4 drift - d*.  Without usable candidates (full mode) a fixed distance of two
+// level-1 bins is taken.  Only speed depends on this guess; a bad one sends the row through the exact full path.
 __device__ __forceinline__ uint32_t next_candidate_threshold(const TopkRow& r, uint32_t tau, uint32_t k) {
     const float d0 = 2.f * (float)(1u << SHIFT1);
     float dstar = d0;
@@ -362,8 +361,8 @@ __device__ __forceinline__ uint32_t next_candidate_threshold(const TopkRow& r, u
     }
     float drift = 0.f;
     if (r.tau_prev != 0xFFFFFFFFu && tau > r.tau_prev) drift = fminf((float)(tau - r.tau_prev), 8.f * d0);
-    const float down = fmaxf(dstar - drift, 0.5f * dstar);     // how far below tau to collect
-    const float t = (float)tau - down;
+    // the drift decays as a run settles: three quarters of the last one is the forecast
+    const float t = (float)tau + 0.75f * drift - dstar;
     return t > 0.f ? (uint32_t)t : 0u;
 }
 

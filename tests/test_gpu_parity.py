@@ -268,6 +268,8 @@ def test_all_zero_and_denormal_blocks():
     x = np.zeros((4, w.N), np.float32)
     r = np.random.default_rng(2)
     x[:, 512:1024] = (r.standard_normal((4, 512)) * 1e-40).astype(np.float32)     # denormal scale
+    x[0, 600] = 0.0            # 7.5 / scale overflows to inf here, so this element's level is 0 * inf = NaN -> code 0
+    x[3, 700] = -0.0
     x[:, 1024:] = r.standard_normal((4, 512)).astype(np.float32)
     x[1, 1024:] = 0.0
     x[2, 1030] = -0.0
