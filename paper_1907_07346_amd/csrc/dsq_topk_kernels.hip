@@ -130,6 +130,29 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
     if (threadIdx.x == 0) cand_count = 0;
     for (int b = threadIdx.x; b < TK_H1; b += TK_THREADS) h[b] = 0;
+    // all dense loads of the chunk go out first (12 x 16 bytes per lane); the sparse tail of the previous
+    // step is gathered while they are in flight
+    float* xr = a.x + (uint64_t)row * a.ld;
+    float* dr = a.delta + (uint64_t)row * a.ld;
+    const float* gr = a.g + (uint64_t)row * a.g_ld;
+    float4 xin[TK_ITERS], din[TK_ITERS], gin[TK_ITERS];
+#pragma unroll
+    for (int it = 0; it < TK_ITERS; ++it) {
+        const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
+        xin[it] = din[it] = gin[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j < a.ld) {
+            xin[it] = ld4_stream(xr + j);
+            din[it] = ld4_stream(dr + j);
+            if (j + 3 < a.N) {
+                gin[it] = ld4_stream(gr + j);
+            } else {
+                gin[it].x = (j + 0 < a.N) ? gr[j + 0] : 0.f;
+                gin[it].y = (j + 1 < a.N) ? gr[j + 1] : 0.f;
+                gin[it].z = (j + 2 < a.N) ? gr[j + 2] : 0.f;
+                gin[it].w = (j + 3 < a.N) ? gr[j + 3] : 0.f;
+            }
+        }
+    }
     bool patch = false;
     if (PENDING) {
         // eta * sum_j a_ij C[v_j] of the previous step for this chunk: the neighbours' pairs that fall
@@ -165,25 +188,13 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     const uint32_t bin0 = tlo >> SHIFT1;                       // (0xfff for "collect nothing")
     bool far = false;                                          // a candidate beyond the tracked bins
     uint2* slot = s.slots + ((size_t)row * s.nchunks + chunk) * TK_CAP;
-    float* xr = a.x + (uint64_t)row * a.ld;
-    float* dr = a.delta + (uint64_t)row * a.ld;
-    const float* gr = a.g + (uint64_t)row * a.g_ld;
-#pragma unroll 2
+#pragma unroll
     for (int it = 0; it < TK_ITERS; ++it) {
         const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
         const uint64_t j = c0 + q0;
         if (j >= a.ld) break;
-        float4 xv = ld4_stream(xr + j);
-        float4 dv = ld4_stream(dr + j);
-        float4 gv;
-        if (j + 3 < a.N) {
-            gv = ld4_stream(gr + j);
-        } else {
-            gv.x = (j + 0 < a.N) ? gr[j + 0] : 0.f;
-            gv.y = (j + 1 < a.N) ? gr[j + 1] : 0.f;
-            gv.z = (j + 2 < a.N) ? gr[j + 2] : 0.f;
-            gv.w = (j + 3 < a.N) ? gr[j + 3] : 0.f;
-        }
+        float4 xv = xin[it], dv = din[it];
+        const float4 gv = gin[it];
         if (PENDING && patch) {                                // lines 6 and 9 of the previous step
             xv.x = fmaf(a.eta, acc[q0 + 0], xv.x); xv.y = fmaf(a.eta, acc[q0 + 1], xv.y);
             xv.z = fmaf(a.eta, acc[q0 + 2], xv.z); xv.w = fmaf(a.eta, acc[q0 + 3], xv.w);
