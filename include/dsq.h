@@ -121,6 +121,14 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out);
  * work has finished.  Advances the step counter t by 1. */
 ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_stream);
 
+/* Replaces the mixing matrix W for the following steps (time-varying communication graphs; the
+ * paper's Algorithm 1 holds for any symmetric doubly stochastic W, and its related-work section
+ * cites time-varying topologies).  CSR of W as for DS_TOPO_CSR (host pointers, copied): n rows, every
+ * row with its diagonal entry, columns strictly ascending; checked like in ds_init (W >= 0,
+ * symmetric, rows summing to 1 within 1e-6).  The step counter, x and delta are untouched.  The call
+ * synchronises with the stream of the last ds_step.  DS_EINVAL leaves the old W in place. */
+ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_col, const float* W_val);
+
 /* Copies the state to dense host arrays of n*N fp32 each (delta_host may be NULL).  Synchronises
  * with the stream of the last ds_step. */
 ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host);
@@ -144,6 +152,14 @@ ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t
 
 /* Borrows the device message buffer (ds_message_bytes bytes, layout as above). */
 ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes);
+
+/* The quantities the paper's analysis tracks, computed on the device in fp64 (off the hot path,
+ * synchronises):
+ *   out[0] = ||X (I - A_n)||_F^2 = sum_i |x_i - mean_i x_i|^2   (consensus distance, squared)
+ *   out[1] = ||Delta||_F^2                                       (compression error carried over)
+ *   out[2] = ||Delta (W_eff - I)||_F^2, W_eff - I = eta (W - I)  (the part of it that reaches x)
+ *   out[3] = bytes of one step's packed messages (= ds_message_bytes) */
+ds_status ds_diagnostics(ds_handle* h, double* out4);
 
 /* Diagnostics for DS_COMP_TOPK: the number of workers whose last ds_step found its top-k among the
  * candidates collected while forming v (the fast path) instead of re-reading v (the exact fallback

@@ -6,5 +6,5 @@ this package; the GPU library and its Python binding never do.
 from .ds_oracle import (  # noqa: F401
     KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK,
     OracleState, build_oracle, philox4x32_10, rounding_word, step,
-    ring_matrix, torus_matrix, dense_to_csr, message_bytes,
+    ring_matrix, torus_matrix, dense_to_csr, message_bytes, diagnostics,
 )

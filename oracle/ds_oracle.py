@@ -149,6 +149,30 @@ class OracleState:
             self.delta = np.zeros((self.n, self.N), dtype=self.dtype)
         self._csr = dense_to_csr(np.asarray(self.W, dtype=np.float64))
 
+    def set_W(self, W: np.ndarray):
+        """Use another mixing matrix from the next step on (time-varying graph)."""
+        self.W = W
+        self._csr = dense_to_csr(np.asarray(W, dtype=np.float64))
+
+
+def diagnostics(st: OracleState) -> dict:
+    """The quantities the paper's analysis tracks, from their definitions in float64 (rows = workers):
+    consensus_sq   = ||X (I - A_n)||_F^2 = sum_i |x_i - mean_i x_i|^2     (supplement, proof of Lemma 1)
+    delta_sq       = ||Delta||_F^2
+    delta_mixed_sq = ||Delta (W_eff - I)||_F^2, W_eff - I = eta (W - I)    (section "Why DeepSqueeze is better")
+    """
+    X = st.x.astype(np.float64)
+    D = st.delta.astype(np.float64)
+    if st.dtype == np.float32:      # the coefficients an fp32 run mixes with: W and W - I rounded to fp32
+        A = (np.asarray(st.W, dtype=np.float32) - np.eye(st.n, dtype=np.float32)).astype(np.float64)
+        eta = float(np.float32(st.eta))
+    else:
+        A = np.asarray(st.W, dtype=np.float64) - np.eye(st.n)
+        eta = float(st.eta)
+    mixed = eta * A @ D
+    return {"consensus_sq": float(((X - X.mean(0)) ** 2).sum()), "delta_sq": float((D ** 2).sum()),
+            "delta_mixed_sq": float((mixed ** 2).sum())}
+
 
 def step(st: OracleState, g: np.ndarray, want_cv: bool = True, want_msg: bool = True):
     """Advance `st` by one iteration with gradients g (n x N). Returns (C[v], message bytes)."""

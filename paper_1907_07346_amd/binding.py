@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
            "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
-           "ds_topk_candidate_rows"]
+           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics"]
 
 
 class ds_comp(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.ds_init.argtypes, L.ds_init.restype = [cfgp, ctypes.POINTER(vp)], i32
         L.ds_step.argtypes, L.ds_step.restype = [vp, vp, u64, vp], i32
         L.ds_read_state.argtypes, L.ds_read_state.restype = [vp, vp, vp], i32
+        L.ds_set_mixing.argtypes, L.ds_set_mixing.restype = [vp, vp, vp, vp], i32
+        L.ds_diagnostics.argtypes, L.ds_diagnostics.restype = [vp, ctypes.POINTER(ctypes.c_double)], i32
         L.ds_write_state.argtypes, L.ds_write_state.restype = [vp, vp, vp, u64], i32
         L.ds_read_messages.argtypes, L.ds_read_messages.restype = [vp, vp, u64, u64p], i32
         L.ds_state_ptrs.argtypes, L.ds_state_ptrs.restype = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), u64p], i32
@@ -172,6 +174,13 @@ class DeepSqueeze:
     def ds_step_raw(self, g_ptr: int, g_ld: int, stream_ptr: int = 0) -> int:
         return lib().ds_step(self._h, g_ptr, g_ld, stream_ptr)
 
+    def ds_set_mixing(self, W_csr):
+        """W_csr = (rowptr int32, col int32, val float32): the mixing matrix for the following steps."""
+        rp = np.ascontiguousarray(W_csr[0], dtype=np.int32)
+        co = np.ascontiguousarray(W_csr[1], dtype=np.int32)
+        va = np.ascontiguousarray(W_csr[2], dtype=np.float32)
+        self._check(lib().ds_set_mixing(self._h, rp.ctypes.data, co.ctypes.data, va.ctypes.data), "ds_set_mixing")
+
     def ds_read_state(self, want_delta: bool = True):
         x = np.empty((self.n, self.N), np.float32)
         d = np.empty((self.n, self.N), np.float32) if want_delta else None
@@ -205,6 +214,11 @@ class DeepSqueeze:
         p, b = ctypes.c_void_p(), ctypes.c_uint64()
         self._check(lib().ds_message_ptr(self._h, ctypes.byref(p), ctypes.byref(b)), "ds_message_ptr")
         return p.value, b.value
+
+    def ds_diagnostics(self) -> dict:
+        out = (ctypes.c_double * 4)()
+        self._check(lib().ds_diagnostics(self._h, out), "ds_diagnostics")
+        return {"consensus_sq": out[0], "delta_sq": out[1], "delta_mixed_sq": out[2], "message_bytes": int(out[3])}
 
     def ds_topk_candidate_rows(self) -> int:
         c = ctypes.c_uint32(0)

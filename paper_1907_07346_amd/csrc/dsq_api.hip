@@ -122,6 +122,49 @@ uint64_t autotune(ds_handle* h, uint64_t base_ld, size_t state_bytes, size_t msg
     return ok ? best_skew : dsq::kPitchSkew;
 }
 
+// Diagnostics (off the hot path): one thread per column walks all rows; fp64 accumulation.
+__global__ void __launch_bounds__(256) diagnostics_kernel(const float* __restrict__ x, const float* __restrict__ delta, uint64_t ld,
+                                                          uint64_t N, int n, const int32_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ col, const float* __restrict__ coef,
+                                                          float eta, double* __restrict__ out) {
+    __shared__ double part[3][4];
+    const uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    double cons = 0.0, dsq_ = 0.0, mixed = 0.0;
+    if (j < N) {
+        double sum = 0.0, sumsq = 0.0;
+        for (int i = 0; i < n; ++i) {
+            const double xv = x[(uint64_t)i * ld + j];
+            const double dv = delta[(uint64_t)i * ld + j];
+            sum += xv;
+            sumsq += xv * xv;
+            dsq_ += dv * dv;
+        }
+        const double mean = sum / n;
+        for (int i = 0; i < n; ++i) {                           // second pass: no cancellation
+            const double dev = (double)x[(uint64_t)i * ld + j] - mean;
+            cons += dev * dev;
+            double m = 0.0;
+            for (int e = rowptr[i]; e < rowptr[i + 1]; ++e) m += (double)coef[e] * (double)delta[(uint64_t)col[e] * ld + j];
+            m *= (double)eta;
+            mixed += m * m;
+        }
+        (void)sumsq;
+    }
+    double v[3] = {cons, dsq_, mixed};
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v[q] += __shfl_xor(v[q], o);
+        if (lane == 0) part[q][wave] = v[q];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        const double tot = part[threadIdx.x][0] + part[threadIdx.x][1] + part[threadIdx.x][2] + part[threadIdx.x][3];
+        atomicAdd(&out[threadIdx.x], tot);
+    }
+}
+
 // Plain streaming copy, one 16-byte non-temporal load and store per lane, one-shot grid: the
 // yardstick for the HBM bandwidth a trivial kernel reaches.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -252,6 +295,39 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
     return DS_OK;
 }
 
+ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_col, const float* W_val) {
+    if (!h) return DS_EINVAL;
+    ds_config probe = h->cfg;
+    probe.topo = DS_TOPO_CSR;
+    probe.W_rowptr = W_rowptr; probe.W_col = W_col; probe.W_val = W_val;
+    std::string err;
+    if (dsq::validate_config(&probe, err, nullptr) != DS_OK) return fail(h, DS_EINVAL, err);
+    dsq::Graph g;
+    if (dsq::build_graph(&probe, g, err) != DS_OK) return fail(h, DS_EINVAL, err);
+    const size_t nnz = g.col.size();
+    if (h->cfg.comp.kind != DS_COMP_TOPK) {
+        // the launch shape was chosen for the old graph; the new CSR only has to fit in LDS next to the codes
+        std::vector<dsq::TilePlan> plans;
+        if (!dsq::choose_tile_plans(h->cfg, (int)nnz, plans, err)) return fail(h, DS_EINVAL, err);
+    }
+    // the deferred tail of a top-k step belongs to the old W: apply it first
+    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
+    DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
+    int32_t* packed = nullptr;
+    DSQ_HIP(h, hipMalloc(&packed, (h->cfg.n + 1 + 2 * nnz) * sizeof(int32_t)));
+    hipError_t e = hipMemcpy(packed, g.rowptr.data(), (h->cfg.n + 1) * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(packed + h->cfg.n + 1, g.col.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(packed + h->cfg.n + 1 + nnz, g.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(packed); return hip_fail(h, e, "hipMemcpy(W)"); }
+    (void)hipFree(h->d_rowptr);
+    h->d_rowptr = packed;
+    h->d_col = packed + h->cfg.n + 1;
+    h->d_coef = reinterpret_cast<float*>(h->d_col + nnz);
+    h->graph = g;
+    h->cfg.topo = DS_TOPO_CSR;
+    return DS_OK;
+}
+
 ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host) {
     if (!h) return DS_EINVAL;
     if (!x_host && !delta_host) return fail(h, DS_EINVAL, "nothing to read");
@@ -300,6 +376,26 @@ ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes) {
     if (!h) return DS_EINVAL;
     if (msg_dev) *msg_dev = h->msg;
     if (bytes) *bytes = h->msg_row_bytes * (uint64_t)h->cfg.n;
+    return DS_OK;
+}
+
+ds_status ds_diagnostics(ds_handle* h, double* out4) {
+    if (!h || !out4) return DS_EINVAL;
+    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
+    DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
+    double* d_out = nullptr;
+    DSQ_HIP(h, hipMalloc(&d_out, 3 * sizeof(double)));
+    hipError_t e = hipMemset(d_out, 0, 3 * sizeof(double));
+    if (e == hipSuccess) {
+        const unsigned blocks = (unsigned)((h->cfg.N + 255) / 256);
+        hipLaunchKernelGGL(diagnostics_kernel, dim3(blocks), dim3(256), 0, nullptr, h->x, h->delta, h->ld, h->cfg.N, h->cfg.n,
+                           h->d_rowptr, h->d_col, h->d_coef, h->cfg.eta, d_out);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpy(out4, d_out, 3 * sizeof(double), hipMemcpyDeviceToHost);
+    (void)hipFree(d_out);
+    if (e != hipSuccess) return hip_fail(h, e, "ds_diagnostics");
+    out4[3] = (double)(h->msg_row_bytes * (uint64_t)h->cfg.n);
     return DS_OK;
 }
 

@@ -209,6 +209,73 @@ def test_general_graph_csr():
         lock_step(w, steps=2, W=W, csr=(rp, co, va.astype(np.float32)))
 
 
+def _random_graph(n, extra, seed):
+    r = np.random.default_rng(seed)
+    A = np.zeros((n, n), bool)
+    for i in range(n):
+        A[i, (i + 1) % n] = A[(i + 1) % n, i] = True
+    for _ in range(extra):
+        i, j = r.integers(0, n, 2)
+        if i != j:
+            A[i, j] = A[j, i] = True
+    deg = A.sum(1)
+    W = np.zeros((n, n))
+    for i in range(n):
+        for j in range(n):
+            if A[i, j]:
+                W[i, j] = 1.0 / (1 + max(deg[i], deg[j]))
+        W[i, i] = 1.0 - W[i].sum()
+    return W
+
+
+def test_time_varying_graph():
+    # W is swapped between steps (ds_set_mixing); top-k has a deferred tail that must use the old W
+    n = 12
+    for w in (small(wl.KIND_QUANT_MAXABS, n, 512 * 3 + 9, bits=4, block=512),
+              small(wl.KIND_SIGN_MEANABS, n, 777, block=256),
+              small(wl.KIND_TOPK, n, 12_345, k=77)):
+        say("case", w.name)
+        ds = b.DeepSqueeze.from_workload(w)
+        st = oracle_state(w)
+        for t in range(5):
+            if t > 0:
+                W = _random_graph(n, 2 * t, seed=40 + t) if t % 2 else oracle.ring_matrix(n)
+                rp, co, va = oracle.dense_to_csr(W)
+                ds.ds_set_mixing((rp, co, va.astype(np.float32)))
+                st.set_W(W)
+            g = wl.gradient(w, t)
+            ds.ds_step(upload(g))
+            _, msg = oracle.step(st, g, want_cv=False)
+            assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} step {t}: messages differ"
+        x, d = ds.ds_read_state()
+        assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+        bad = oracle.ring_matrix(n)
+        bad[0, 1] += 0.05
+        rp, co, va = oracle.dense_to_csr(bad)
+        va32 = va.astype(np.float32)
+        assert b.lib().ds_set_mixing(ds._h, rp.ctypes.data, co.ctypes.data, va32.ctypes.data) == b.DS_EINVAL
+        ds.ds_destroy()
+
+
+def test_diagnostics_match_their_definitions():
+    for w in (small(wl.KIND_QUANT_MAXABS, 8, 512 * 5 + 37, bits=4, block=512),
+              small(wl.KIND_TOPK, 16, 20_000, k=200, topo=wl.TOPO_TORUS2D, torus=(4, 4)),
+              small(wl.KIND_SIGN_MEANABS, 33, 512 * 3 + 1, block=512)):
+        ds = b.DeepSqueeze.from_workload(w)
+        st = oracle_state(w)
+        for t in range(3):
+            g = wl.gradient(w, t)
+            ds.ds_step(upload(g))
+            oracle.step(st, g, want_cv=False, want_msg=False)
+        got = ds.ds_diagnostics()
+        want = oracle.diagnostics(st)
+        say(w.name, "diagnostics", got)
+        for key in ("consensus_sq", "delta_sq", "delta_mixed_sq"):
+            assert abs(got[key] - want[key]) <= 1e-9 * abs(want[key]) + 1e-30, (key, got[key], want[key])
+        assert got["message_bytes"] == b.ds_message_bytes(ds.cfg)
+        ds.ds_destroy()
+
+
 # ------------------------------------------------------------------------------------ worked examples
 
 def test_hand_expanded_example_on_gpu(golden_dir):

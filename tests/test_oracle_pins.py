@@ -121,6 +121,33 @@ def test_identity_reduces_to_dpsgd_closed_form(n, eta):
     np.testing.assert_array_equal(st.delta, 0.0)
 
 
+def test_time_varying_graph_product_form():
+    # with a different symmetric doubly stochastic W_t at every step and no compression,
+    # X_T = -gamma sum_s W_eff,T-1 ... W_eff,s G_s  (the D-PSGD closed form with a product instead of a power)
+    n, N, T, gamma, eta = 6, 9, 4, 0.2, 0.4
+    r = np.random.default_rng(21)
+    Ws = [metropolis_matrix(n, 3 + t, seed=30 + t) for t in range(T)]
+    gs = [r.standard_normal((n, N)) for _ in range(T)]
+    st = OracleState(n=n, N=N, W=Ws[0], kind=KIND_IDENTITY, gamma=gamma, eta=eta, dtype=np.float64)
+    for t in range(T):
+        st.set_W(Ws[t])
+        oracle.step(st, gs[t], want_msg=False)
+    X = np.zeros((n, N))
+    for s_ in range(T):
+        term = gs[s_]
+        for t in range(s_, T):
+            term = ((1 - eta) * np.eye(n) + eta * Ws[t]) @ term
+        X += -gamma * term
+    np.testing.assert_allclose(st.x, X, rtol=0, atol=1e-13)
+    # and with compression the node average still moves by -gamma * mean gradient at every step
+    st = OracleState(n=n, N=N, W=Ws[0], gamma=gamma, eta=eta, dtype=np.float64, **COMPRESSORS[0])
+    for t in range(T):
+        before = st.x.mean(0).copy()
+        st.set_W(Ws[t])
+        oracle.step(st, gs[t], want_msg=False)
+        np.testing.assert_allclose(st.x.mean(0), before - gamma * gs[t].mean(0), rtol=0, atol=1e-14)
+
+
 # ----------------------------------------------------------------------------- P2/P3/P4: one-step identities
 
 COMPRESSORS = [
@@ -489,3 +516,24 @@ def test_ring_and_torus_matrices():
     np.testing.assert_allclose(np.sort(np.linalg.eigvalsh(W)), np.sort(ev.ravel()), atol=1e-12)
     # eta <= 1/2 keeps W_eff positive semi-definite (used by the paper's proof of Theorem 1)
     assert np.linalg.eigvalsh(0.5 * np.eye(64) + 0.5 * W).min() > -1e-12
+
+
+def test_diagnostics_definitions():
+    n, N = 5, 40
+    r = np.random.default_rng(22)
+    W = metropolis_matrix(n, 3, seed=2)
+    st = OracleState(n=n, N=N, W=W, gamma=0.1, eta=0.4, dtype=np.float64, x=r.standard_normal((n, N)),
+                     delta=r.standard_normal((n, N)), **COMPRESSORS[2])
+    d = oracle.diagnostics(st)
+    X, D = st.x, st.delta
+    # ||X(I - A_n)||_F^2 = ||X||_F^2 - n |mean|^2 ; ||Delta (W_eff - I)||_F^2 with W_eff = (1-eta) I + eta W
+    np.testing.assert_allclose(d["consensus_sq"], (X ** 2).sum() - n * (X.mean(0) ** 2).sum(), rtol=1e-12)
+    Weff = 0.6 * np.eye(n) + 0.4 * W
+    np.testing.assert_allclose(d["delta_mixed_sq"], np.linalg.norm((Weff - np.eye(n)) @ D, "fro") ** 2, rtol=1e-12)
+    np.testing.assert_allclose(d["delta_sq"], np.linalg.norm(D, "fro") ** 2, rtol=1e-12)
+    # complete-graph averaging with eta = 1 and no compression reaches consensus in one step, with nothing carried over
+    st = OracleState(n=n, N=N, W=np.full((n, n), 1.0 / n), kind=KIND_IDENTITY, gamma=0.0, eta=1.0, dtype=np.float64,
+                     x=r.standard_normal((n, N)))
+    oracle.step(st, np.zeros((n, N)), want_msg=False)
+    d = oracle.diagnostics(st)
+    assert d["consensus_sq"] < 1e-25 and d["delta_sq"] == 0.0 and d["delta_mixed_sq"] == 0.0
