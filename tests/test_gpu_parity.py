@@ -137,6 +137,7 @@ SMALL = [
     small(wl.KIND_QUANT_MAXABS, 70, 512 * 2 + 5, bits=2, block=512),              # looped rows (re-read x, g)
     small(wl.KIND_QUANT_MAXABS, 12, 2048 * 2 + 2000, bits=4, block=2048),         # 8-wave looped variant
     small(wl.KIND_QUANT_MAXABS, 15, 512 * 4 + 4, bits=2, block=512, topo=wl.TOPO_TORUS2D, torus=(3, 5)),
+    small(wl.KIND_QUANT_MAXABS, 300, 512 + 5, bits=4, block=512),                 # 87 KB of LDS (above the 64 KB default)
     small(wl.KIND_SIGN_MEANABS, 8, 256 * 7 + 40, block=256),
     small(wl.KIND_SIGN_MEANABS, 16, 1024 * 2 + 999, block=1024),
     small(wl.KIND_SIGN_MEANABS, 3, 2, block=256),
@@ -158,13 +159,13 @@ def test_lock_step_small_shapes(w):
     lock_step(w, steps=3)
 
 
-@pytest.mark.parametrize("w", [SMALL[0], SMALL[9], SMALL[16]], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [SMALL[0], SMALL[10], SMALL[17]], ids=lambda w: w.name)
 def test_gradient_pitch_larger_than_N(w):
     say("case", w.name)
     lock_step(w, steps=2, pitch=((w.N + 3) // 4) * 4 + 64)
 
 
-@pytest.mark.parametrize("w", [SMALL[1], SMALL[4], SMALL[5], SMALL[9], SMALL[12]], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [SMALL[1], SMALL[4], SMALL[5], SMALL[10], SMALL[13]], ids=lambda w: w.name)
 def test_every_candidate_launch_shape(w, monkeypatch):
     # ds_init picks the launch shape by timing; here each candidate is pinned in turn and checked
     seen = []
