@@ -118,7 +118,8 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out);
  * g_dev: caller-owned DEVICE pointer, n rows of fp32, row pitch g_ld >= N elements, g_ld a multiple
  * of 4, base 16-byte aligned; read-only.  Work is enqueued on hip_stream (a hipStream_t, NULL = the
  * default stream) and the call returns without synchronising; g_dev must stay valid until that
- * work has finished.  Advances the step counter t by 1. */
+ * work has finished.  Advances the step counter t by 1.  DS_ESTATE if the current HIP device is not
+ * the one ds_init ran on. */
 ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_stream);
 
 /* Replaces the mixing matrix W for the following steps (time-varying communication graphs; the

@@ -274,6 +274,9 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
     if (!g_dev) return fail(h, DS_EINVAL, "g_dev is NULL");
     if (g_ld < h->cfg.N || (g_ld & 3)) return fail(h, DS_EINVAL, "g_ld must be >= N and a multiple of 4");
     if (reinterpret_cast<uintptr_t>(g_dev) & 15) return fail(h, DS_EINVAL, "g_dev must be 16-byte aligned");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != h->device)
+        return fail(h, DS_ESTATE, "the current HIP device is not the one the handle was created on");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     if (h->cfg.comp.kind == DS_COMP_TOPK) {

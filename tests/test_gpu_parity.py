@@ -421,6 +421,24 @@ def test_api_errors_and_restart():
     assert "eta" in big_eta.ds_last_error()
 
 
+def test_two_handles_interleaved():
+    # handles are independent: different compressors and shapes stepped in turn
+    ws = [small(wl.KIND_QUANT_MAXABS, 16, 1024 * 3 + 74, bits=2, block=1024), small(wl.KIND_TOPK, 8, 30_011, k=300),
+          small(wl.KIND_SIGN_MEANABS, 33, 512 * 3 + 1, block=512)]
+    dss = [b.DeepSqueeze.from_workload(w) for w in ws]
+    sts = [oracle_state(w) for w in ws]
+    for t in range(4):
+        for w, ds, st in zip(ws, dss, sts):
+            g = wl.gradient(w, t)
+            ds.ds_step(upload(g))
+            _, msg = oracle.step(st, g, want_cv=False)
+            assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} step {t}"
+    for w, ds, st in zip(ws, dss, sts):
+        x, d = ds.ds_read_state()
+        assert assert_close(w.name + " x", x, st.x) + assert_close(w.name + " delta", d, st.delta) == 0
+        ds.ds_destroy()
+
+
 def test_step_on_a_side_stream_and_determinism():
     w = small(wl.KIND_TOPK, 8, 50_000, k=500)
     outs = []
