@@ -119,7 +119,13 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out);
  * of 4, base 16-byte aligned; read-only.  Work is enqueued on hip_stream (a hipStream_t, NULL = the
  * default stream) and the call returns without synchronising; g_dev must stay valid until that
  * work has finished.  Advances the step counter t by 1.  DS_ESTATE if the current HIP device is not
- * the one ds_init ran on. */
+ * the one ds_init ran on.
+ * The call only launches kernels: it makes no allocation, copy, memset or synchronisation, and the
+ * step counter that selects the random rounding words lives in device memory and is advanced by
+ * the enqueued work itself.  A stream capture of the call therefore gives a HIP graph whose every
+ * replay is the next iteration (the gradients are read from the captured g_dev at replay time).
+ * Such a graph stays valid until ds_destroy, or a ds_set_mixing that changes the number of stored
+ * entries of W. */
 ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_stream);
 
 /* Replaces the mixing matrix W for the following steps (time-varying communication graphs; the
@@ -127,7 +133,9 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
  * cites time-varying topologies).  CSR of W as for DS_TOPO_CSR (host pointers, copied): n rows, every
  * row with its diagonal entry, columns strictly ascending; checked like in ds_init (W >= 0,
  * symmetric, rows summing to 1 within 1e-6).  The step counter, x and delta are untouched.  The call
- * synchronises with the stream of the last ds_step.  DS_EINVAL leaves the old W in place. */
+ * synchronises with the stream of the last ds_step.  DS_EINVAL leaves the old W in place.  A W with
+ * as many stored entries as the current one is written over it in place (device addresses, and HIP
+ * graphs captured from ds_step, stay valid); any other W moves to a new allocation. */
 ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_col, const float* W_val);
 
 /* Copies the state to dense host arrays of n*N fp32 each (delta_host may be NULL).  Synchronises
@@ -169,7 +177,9 @@ ds_status ds_diagnostics(ds_handle* h, double* out4);
  * compressors; DS_ESTATE before the first step. */
 ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count);
 
-/* Step counter t (number of ds_step calls since init or the value set by ds_write_state). */
+/* Step counter t: the number of iterations executed since init (graph replays included), or since
+ * the value set by ds_write_state.  Read from the device; synchronises with the stream of the last
+ * ds_step call. */
 uint64_t ds_step_count(const ds_handle* h);
 
 /* Name of the kernel plan ds_step uses for this handle (static string, for reports). */

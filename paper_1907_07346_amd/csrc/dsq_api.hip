@@ -21,6 +21,7 @@ struct ds_handle {
     int32_t* d_rowptr = nullptr;
     int32_t* d_col = nullptr;
     float* d_coef = nullptr;
+    unsigned long long* d_t = nullptr;   // device copy of t: kernels read it, bump_step advances it
     dsq::TilePlan tile;
     std::vector<dsq::TilePlan> tile_candidates;
     dsq::TopkState* topk = nullptr;
@@ -52,8 +53,11 @@ void release(ds_handle* h) {
     if (h->delta) (void)hipFree(h->delta);
     if (h->msg) (void)hipFree(h->msg);
     if (h->d_rowptr) (void)hipFree(h->d_rowptr);   // d_col and d_coef point into the same allocation
+    if (h->d_t) (void)hipFree(h->d_t);
     delete h;
 }
+
+__global__ void bump_step(unsigned long long* t) { *t += 1ull; }
 
 dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     dsq::TileArgs a{};
@@ -62,7 +66,7 @@ dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes;
     a.n = h->cfg.n; a.nnz = (int)h->graph.col.size();
     a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
-    a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32); a.t_lo = (uint32_t)h->t;
+    a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32); a.t_ptr = h->d_t;
     return a;
 }
 
@@ -230,15 +234,16 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     const size_t nnz = h->graph.col.size();
     const size_t msg_bytes = (size_t)cfg->n * h->msg_row_bytes;
     // rowptr | col | coef as one contiguous array of 32-bit words
-    hipError_t errs[4] = {
+    hipError_t errs[5] = {
         hipMalloc(&h->x, state_bytes), hipMalloc(&h->delta, state_bytes), hipMalloc(&h->msg, msg_bytes ? msg_bytes : 4),
-        hipMalloc(&h->d_rowptr, (cfg->n + 1 + 2 * nnz) * sizeof(int32_t))};
+        hipMalloc(&h->d_rowptr, (cfg->n + 1 + 2 * nnz) * sizeof(int32_t)), hipMalloc(&h->d_t, sizeof(unsigned long long))};
     for (hipError_t ee : errs)
         if (ee != hipSuccess) { std::fprintf(stderr, "ds_init: hipMalloc: %s\n", hipGetErrorString(ee)); return bail(ee == hipErrorOutOfMemory ? DS_ENOMEM : DS_EHIP); }
     h->d_col = h->d_rowptr + cfg->n + 1;
     h->d_coef = reinterpret_cast<float*>(h->d_col + nnz);
     bool ok = hipMemset(h->x, 0, state_bytes) == hipSuccess && hipMemset(h->delta, 0, state_bytes) == hipSuccess &&
               hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4) == hipSuccess &&
+              hipMemset(h->d_t, 0, sizeof(unsigned long long)) == hipSuccess &&
               hipMemcpy(h->d_rowptr, h->graph.rowptr.data(), (cfg->n + 1) * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->d_col, h->graph.col.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->d_coef, h->graph.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice) == hipSuccess &&
@@ -291,6 +296,7 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
         const dsq::TileArgs a = tile_args(h, g_dev, g_ld);
         h->tile.launch(a, h->tile.rows_per_wave, stream);
     }
+    hipLaunchKernelGGL(bump_step, dim3(1), dim3(1), 0, stream, h->d_t);
     DSQ_HIP(h, hipGetLastError());
     h->t += 1;
     h->stepped = true;
@@ -316,13 +322,19 @@ ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_
     // the deferred tail of a top-k step belongs to the old W: apply it first
     if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
-    int32_t* packed = nullptr;
-    DSQ_HIP(h, hipMalloc(&packed, (h->cfg.n + 1 + 2 * nnz) * sizeof(int32_t)));
+    // same number of stored entries: overwrite in place, so that the device addresses (and a HIP graph captured
+    // from ds_step with them) stay valid
+    const bool in_place = nnz == h->graph.col.size();
+    int32_t* packed = h->d_rowptr;
+    if (!in_place) DSQ_HIP(h, hipMalloc(&packed, (h->cfg.n + 1 + 2 * nnz) * sizeof(int32_t)));
     hipError_t e = hipMemcpy(packed, g.rowptr.data(), (h->cfg.n + 1) * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(packed + h->cfg.n + 1, g.col.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(packed + h->cfg.n + 1 + nnz, g.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice);
-    if (e != hipSuccess) { (void)hipFree(packed); return hip_fail(h, e, "hipMemcpy(W)"); }
-    (void)hipFree(h->d_rowptr);
+    if (e != hipSuccess) {
+        if (!in_place) (void)hipFree(packed);
+        return hip_fail(h, e, "hipMemcpy(W)");
+    }
+    if (!in_place) (void)hipFree(h->d_rowptr);
     h->d_rowptr = packed;
     h->d_col = packed + h->cfg.n + 1;
     h->d_coef = reinterpret_cast<float*>(h->d_col + nnz);
@@ -349,6 +361,8 @@ ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_h
     const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
     if (x_host) DSQ_HIP(h, hipMemcpy2D(h->x, pitch, x_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
     if (delta_host) DSQ_HIP(h, hipMemcpy2D(h->delta, pitch, delta_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
+    const unsigned long long t64 = t;
+    DSQ_HIP(h, hipMemcpy(h->d_t, &t64, sizeof(t64), hipMemcpyHostToDevice));
     DSQ_HIP(h, hipDeviceSynchronize());
     h->t = t;
     return DS_OK;
@@ -414,7 +428,14 @@ ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count) {
 void* dsq_debug_topk_state(ds_handle* h) { return h ? h->topk : nullptr; }
 #endif
 
-uint64_t ds_step_count(const ds_handle* h) { return h ? h->t : 0; }
+uint64_t ds_step_count(const ds_handle* h) {
+    // the device counter is the authority: replays of a captured graph advance it without the host seeing them
+    if (!h) return 0;
+    unsigned long long t64 = h->t;
+    if (hipStreamSynchronize(h->last_stream) == hipSuccess)
+        (void)hipMemcpy(&t64, h->d_t, sizeof(t64), hipMemcpyDeviceToHost);
+    return t64;
+}
 
 const char* ds_plan_name(const ds_handle* h) { return h ? h->plan_name.c_str() : ""; }
 

@@ -45,7 +45,9 @@ struct TileArgs {
     uint64_t ld, g_ld, N, msg_row_bytes;
     int n, nnz;                // workers; stored entries of W - I
     float gamma, eta;
-    uint32_t seed_lo, seed_hi, t_lo;
+    uint32_t seed_lo, seed_hi;
+    const unsigned long long* t_ptr;   // step counter in device memory (read by the kernel, so that a captured
+                                       // HIP graph of ds_step keeps advancing the random stream on replay)
 };
 
 // A compiled variant of the fused tile kernel, chosen once at init.

@@ -163,6 +163,7 @@ struct Tile {
             uint8_t* msg_blk = msg_row + (bcol0 / B) * MSG_BLOCK_BYTES;
 
             if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
+                const uint32_t t_lo = (uint32_t)*a.t_ptr;            // step counter, low word (Philox counter word 2)
                 float mx = 0.f;
 #pragma unroll
                 for (int s = b * SPB; s < (b + 1) * SPB; ++s)
@@ -179,7 +180,7 @@ struct Tile {
                 for (int s = b * SPB; s < (b + 1) * SPB; ++s) {
                     const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
                     uint32_t rnd[4];
-                    philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, a.t_lo, kQuantStreamTag, a.seed_lo, a.seed_hi, rnd);
+                    philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, t_lo, kQuantStreamTag, a.seed_lo, a.seed_hi, rnd);
                     uint32_t codes = 0;
                     float4 dnew;
 #pragma unroll

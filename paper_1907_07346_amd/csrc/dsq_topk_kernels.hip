@@ -119,10 +119,9 @@ struct Scratch {               // device pointers of the select's scratch (all o
 };
 
 // ---- pass 1: pending gossip of the previous step, Algorithm 1 line 5, candidate collection ------
-template <bool PENDING>
 __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scratch s) {
-    __shared__ float acc[PENDING ? TK_CHUNK : 1];
-    __shared__ uint32_t own[PENDING ? TK_CHUNK / 32 : 1];       // columns this worker itself sent in the previous step
+    __shared__ float acc[TK_CHUNK];
+    __shared__ uint32_t own[TK_CHUNK / 32];       // columns this worker itself sent in the previous step
     __shared__ uint32_t h[TK_H1];                              // level-1 digits of the candidates, relative to tlo's
     __shared__ uint32_t cand_count;
     const int row = blockIdx.y;
@@ -154,7 +153,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
         }
     }
     bool patch = false;
-    if (PENDING) {
+    {
         // eta * sum_j a_ij C[v_j] of the previous step for this chunk: the neighbours' pairs that fall
         // into the chunk are contiguous in their messages; accumulate neighbour after neighbour.
         const int e0 = a.rowptr[row], e1 = a.rowptr[row + 1];
@@ -195,7 +194,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
         if (j >= a.ld) break;
         float4 xv = xin[it], dv = din[it];
         const float4 gv = gin[it];
-        if (PENDING && patch) {                                // lines 6 and 9 of the previous step
+        if (patch) {                                // lines 6 and 9 of the previous step
             xv.x = fmaf(a.eta, acc[q0 + 0], xv.x); xv.y = fmaf(a.eta, acc[q0 + 1], xv.y);
             xv.z = fmaf(a.eta, acc[q0 + 2], xv.z); xv.w = fmaf(a.eta, acc[q0 + 3], xv.w);
             const uint32_t sent = own[q0 >> 5] >> (q0 & 31);   // delta = v - C[v] = 0 where v was sent
@@ -729,7 +728,8 @@ __global__ void topk_init_rows(TopkRow* rows, int n) {
 struct TopkState {
     Scratch s{};
     int n = 0;
-    bool pending = false;          // the sparse part of the last step's line 9 has not been applied to x yet
+    bool pending = false;          // a step has been enqueued since the last flush (or may have been, by a
+                                   // replayed graph): its sparse tail may not have been applied yet
     TopkArgs last{};               // arguments of the last step (what the pending update needs)
 };
 
@@ -792,8 +792,11 @@ ds_status topk_flush(TopkState* st, hipStream_t stream) {
     if (!st || !st->pending) return DS_OK;
     const dim3 grid(st->s.nchunks, st->last.n), block(TK_THREADS);
     hipLaunchKernelGGL(topk_gossip, grid, block, 0, stream, st->last, st->s);
-    st->pending = false;
-    return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
+    // the tail is applied: no message offsets, nothing for the next first pass to apply again
+    const hipError_t e = hipMemsetAsync(st->s.out_off, 0, (size_t)st->n * (st->s.nchunks + 1) * sizeof(uint32_t), stream);
+    // `pending` stays set: a captured graph of ds_step may be replayed without this code noticing, and a flush
+    // with nothing to apply is a grid of workgroups that return at once
+    return (e == hipSuccess && hipGetLastError() == hipSuccess) ? DS_OK : DS_EHIP;
 }
 
 ds_status topk_step(TopkState* st, const TopkArgs& a, const Graph& /*graph*/, hipStream_t stream, std::string& /*err*/) {
@@ -804,8 +807,8 @@ ds_status topk_step(TopkState* st, const TopkArgs& a, const Graph& /*graph*/, hi
     const dim3 hgrid(TK_HWG, a.n), hblock(TK_HTHREADS);
     const dim3 rows(a.n);
     const uint32_t k = (uint32_t)a.k;
-    if (st->pending) hipLaunchKernelGGL(topk_form_collect<true>, grid, block, 0, stream, a, s);
-    else             hipLaunchKernelGGL(topk_form_collect<false>, grid, block, 0, stream, a, s);
+    // after a flush (and at the start) all message offsets are zero, so the first pass finds no tail to apply
+    hipLaunchKernelGGL(topk_form_collect, grid, block, 0, stream, a, s);
     hipLaunchKernelGGL(topk_decide, rows, block, 0, stream, s, k);
     hipLaunchKernelGGL(topk_hist_full<1>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
     hipLaunchKernelGGL(topk_select<1>, rows, block, 0, stream, s, k);

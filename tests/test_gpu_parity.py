@@ -439,6 +439,46 @@ def test_two_handles_interleaved():
         ds.ds_destroy()
 
 
+@pytest.mark.parametrize("w", [small(wl.KIND_QUANT_MAXABS, 8, 512 * 9 + 37, bits=4, block=512),
+                               small(wl.KIND_TOPK, 8, 30_011, k=300)], ids=lambda w: w.name)
+def test_hip_graph_replay(w):
+    """ds_step captured once into a HIP graph and replayed: the step counter lives on the device, so every
+    replay draws fresh rounding words; each replay is checked against the oracle, with eager work between."""
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w)
+    pitch = (w.N + 3) // 4 * 4
+    g_static = torch.zeros((w.n, pitch), dtype=torch.float32, device="cuda")
+
+    def feed(t):
+        g = wl.gradient(w, t)
+        g_static[:, :w.N].copy_(torch.from_numpy(g).cuda())
+        torch.cuda.synchronize()
+        return g
+
+    g = feed(0)                                            # one eager step first
+    ds.ds_step(g_static)
+    oracle.step(st, g, want_cv=False, want_msg=False)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        g = feed(1)
+        with torch.cuda.graph(graph, stream=side):
+            ds.ds_step(g_static, side)
+    # capture does not run anything: replay for step 1
+    for t in range(1, 6):
+        g = feed(t)
+        graph.replay()
+        torch.cuda.synchronize()
+        _, msg = oracle.step(st, g, want_cv=False)
+        assert ds.ds_step_count() == st.t
+        assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} replay {t}: messages differ"
+        x, d = ds.ds_read_state()                          # eager work (incl. the top-k flush) between replays
+        assert assert_close(f"replay {t} x", x, st.x) + assert_close(f"replay {t} delta", d, st.delta) == 0
+    ds.ds_destroy()
+
+
 def test_step_on_a_side_stream_and_determinism():
     w = small(wl.KIND_TOPK, 8, 50_000, k=500)
     outs = []
