@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="index into the benchmark configuration list")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--hip-graph", action="store_true",
+                    help="capture the K timed steps into one HIP graph and time its replay (for launch-bound sizes)")
     ap.add_argument("--copy-only", action="store_true", help="run only the plain copy kernel (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -125,10 +127,25 @@ def main():
         ds.ds_step(gs[t % nbuf])
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    graph = None
+    if args.hip_graph:
+        # the step counter lives on the device and the steps' kernels advance it, so the captured steps run as
+        # iterations W .. W+K-1 when the graph is replayed
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for t in range(K):
+                    ds.ds_step(gs[(Wm + t) % nbuf], side)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev0.record()                                            # same stream ds_step launches on
-    for t in range(K):
-        ds.ds_step(gs[(Wm + t) % nbuf])
+    if graph is not None:
+        graph.replay()
+    else:
+        for t in range(K):
+            ds.ds_step(gs[(Wm + t) % nbuf])
     ev1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -148,7 +165,7 @@ def main():
         "value": value, "unit": "worker-param updates/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "n": w.n, "N": w.N, "plan": ds.ds_plan_name(), "gradient_buffers": nbuf,
+        "config": {"workload": w.name, "n": w.n, "N": w.N, "plan": ds.ds_plan_name(), "gradient_buffers": nbuf, "launch": "hip-graph" if graph is not None else "eager",
                    "compressor": {1: f"quant{w.bits}b/B{w.block}", 2: f"sign/B{w.block}", 3: f"top-{w.k}", 0: "identity"}[w.kind]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

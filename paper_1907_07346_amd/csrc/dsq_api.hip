@@ -21,7 +21,8 @@ struct ds_handle {
     int32_t* d_rowptr = nullptr;
     int32_t* d_col = nullptr;
     float* d_coef = nullptr;
-    unsigned long long* d_t = nullptr;   // device copy of t: kernels read it, bump_step advances it
+    unsigned long long* d_t = nullptr;   // kStepCells cells; d_t[0]: the step counter t, read and advanced by the
+                                         // step's kernels; the rest: the tile kernel's finished-workgroup counters
     dsq::TilePlan tile;
     std::vector<dsq::TilePlan> tile_candidates;
     dsq::TopkState* topk = nullptr;
@@ -57,7 +58,6 @@ void release(ds_handle* h) {
     delete h;
 }
 
-__global__ void bump_step(unsigned long long* t) { *t += 1ull; }
 
 dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     dsq::TileArgs a{};
@@ -121,6 +121,7 @@ uint64_t autotune(ds_handle* h, uint64_t base_ld, size_t state_bytes, size_t msg
     (void)hipMemset(h->x, 0, state_bytes);
     (void)hipMemset(h->delta, 0, state_bytes);
     (void)hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4);
+    (void)hipMemset(h->d_t, 0, dsq::kStepCells * sizeof(unsigned long long));   // the timed launches advanced t
     (void)hipDeviceSynchronize();
     if (!ok) h->tile = h->tile_candidates.front();
     return ok ? best_skew : dsq::kPitchSkew;
@@ -236,14 +237,14 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     // rowptr | col | coef as one contiguous array of 32-bit words
     hipError_t errs[5] = {
         hipMalloc(&h->x, state_bytes), hipMalloc(&h->delta, state_bytes), hipMalloc(&h->msg, msg_bytes ? msg_bytes : 4),
-        hipMalloc(&h->d_rowptr, (cfg->n + 1 + 2 * nnz) * sizeof(int32_t)), hipMalloc(&h->d_t, sizeof(unsigned long long))};
+        hipMalloc(&h->d_rowptr, (cfg->n + 1 + 2 * nnz) * sizeof(int32_t)), hipMalloc(&h->d_t, dsq::kStepCells * sizeof(unsigned long long))};
     for (hipError_t ee : errs)
         if (ee != hipSuccess) { std::fprintf(stderr, "ds_init: hipMalloc: %s\n", hipGetErrorString(ee)); return bail(ee == hipErrorOutOfMemory ? DS_ENOMEM : DS_EHIP); }
     h->d_col = h->d_rowptr + cfg->n + 1;
     h->d_coef = reinterpret_cast<float*>(h->d_col + nnz);
     bool ok = hipMemset(h->x, 0, state_bytes) == hipSuccess && hipMemset(h->delta, 0, state_bytes) == hipSuccess &&
               hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4) == hipSuccess &&
-              hipMemset(h->d_t, 0, sizeof(unsigned long long)) == hipSuccess &&
+              hipMemset(h->d_t, 0, dsq::kStepCells * sizeof(unsigned long long)) == hipSuccess &&
               hipMemcpy(h->d_rowptr, h->graph.rowptr.data(), (cfg->n + 1) * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->d_col, h->graph.col.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->d_coef, h->graph.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice) == hipSuccess &&
@@ -289,14 +290,13 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
         a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
         a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
         a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.k = h->cfg.comp.k; a.n = h->cfg.n;
-        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
+        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
         const ds_status st = dsq::topk_step(h->topk, a, h->graph, stream, h->err);
         if (st != DS_OK) return st;
     } else {
         const dsq::TileArgs a = tile_args(h, g_dev, g_ld);
         h->tile.launch(a, h->tile.rows_per_wave, stream);
     }
-    hipLaunchKernelGGL(bump_step, dim3(1), dim3(1), 0, stream, h->d_t);
     DSQ_HIP(h, hipGetLastError());
     h->t += 1;
     h->stepped = true;

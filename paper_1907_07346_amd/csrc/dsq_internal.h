@@ -19,6 +19,7 @@ constexpr uint64_t kPitchSkew = 2560;     // ... plus 10 KB, so that rows do not
                                           // of a column tile in flight at once, HBM channel hashing made a 16 MiB pitch
                                           // 12 % slower than this one on MI355X (measured, 64 rows x 4 Mi columns)
 constexpr int kMinBlock = 256, kMaxBlock = 2048;
+constexpr size_t kStepCells = 32 * 65;    // 64-bit cells behind the step counter (see TileArgs::t_ptr)
 
 // Host-side description of W - I in CSR form (diagonal always present, columns ascending).
 struct Graph {
@@ -46,8 +47,11 @@ struct TileArgs {
     int n, nnz;                // workers; stored entries of W - I
     float gamma, eta;
     uint32_t seed_lo, seed_hi;
-    const unsigned long long* t_ptr;   // step counter in device memory (read by the kernel, so that a captured
-                                       // HIP graph of ds_step keeps advancing the random stream on replay)
+    unsigned long long* t_ptr;         // kStepCells 64-bit cells in device memory.  [0]: the step counter t, read by
+                                       // the kernel and advanced by its last workgroup to finish, so that a captured
+                                       // HIP graph of ds_step keeps moving along the random stream on replay.
+                                       // [1]: finished first-level cells; [32 (1+c)], c < 64: finished workgroups
+                                       // with blockIdx % 64 == c.  All but [0] are zero between launches.
 };
 
 // A compiled variant of the fused tile kernel, chosen once at init.
@@ -75,6 +79,7 @@ struct TopkArgs {
     uint64_t ld, g_ld, N, k;
     int n;
     float gamma, eta;
+    unsigned long long* t_ptr;  // step counter in device memory (advanced once per step; top-k draws no random numbers)
 };
 
 struct TopkState;              // device scratch of the radix select (histograms, per-chunk counts)

@@ -443,6 +443,28 @@ __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int r
     const uint64_t col0 = (uint64_t)blockIdx.x * T::TC;
     if (col0 + T::TC <= a.N) T::template run<RPW, true>(a, rpw_runtime, col0, lds);
     else                     T::template run<RPW, false>(a, rpw_runtime, col0, lds);
+    // Advance the step counter once per launch: the workgroup that finds all others finished does it.
+    // Thread 0 is past the barrier that follows phase 1, so every wave of its workgroup has read t (the
+    // value has been consumed, so the load has completed) before the workgroup counts itself finished.
+    // Two levels of counters, 64 cells a cache line or more apart and one on top, because returning
+    // atomics on a single address serialise: with ~10^5 workgroups one shared counter doubled the
+    // kernel time on MI355X, 64 cells cost < 0.5 %.  Relaxed atomics on purpose: a release fence
+    // would write back the XCD's L2 once per workgroup; the end of the kernel publishes the new t.
+    // All cells are zero again when the kernel ends.
+    if (threadIdx.x == 0) {
+        const unsigned cell = blockIdx.x & 63u;
+        const unsigned long long members = (gridDim.x >> 6) + (cell < (gridDim.x & 63u) ? 1u : 0u);
+        unsigned long long* cnt = a.t_ptr + 32ull * (1 + cell);
+        if (__hip_atomic_fetch_add(cnt, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == members - 1ull) {
+            __hip_atomic_store(cnt, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long cells = gridDim.x < 64u ? gridDim.x : 64u;
+            unsigned long long* done = a.t_ptr + 1;
+            if (__hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == cells - 1ull) {
+                __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(a.t_ptr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
 }
 
 template <int KIND, int BITS, int B, int SW, int NW, int RPW>

@@ -484,7 +484,8 @@ __global__ void __launch_bounds__(TK_THREADS) topk_fix_cand(Scratch s) {
 }
 
 // ---- per-row scan over chunks: tie quota and output offset of every chunk -----------------------
-__global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(Scratch s) {
+__global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(Scratch s, unsigned long long* t_ptr) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(t_ptr, 1ull);   // one step taken
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.x;
     const uint32_t nchunks = s.nchunks;
@@ -820,7 +821,7 @@ ds_status topk_step(TopkState* st, const TopkArgs& a, const Graph& /*graph*/, hi
     hipLaunchKernelGGL(topk_select<3>, rows, block, 0, stream, s, k);
     hipLaunchKernelGGL(topk_fix_cand, cgrid, block, 0, stream, s);
     hipLaunchKernelGGL(topk_fix_full, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
-    hipLaunchKernelGGL(topk_scan_chunks, rows, block, 0, stream, s);
+    hipLaunchKernelGGL(topk_scan_chunks, rows, block, 0, stream, s, a.t_ptr);
     hipLaunchKernelGGL(topk_write_cand, grid, dim3(64), 0, stream, a, s);
     hipLaunchKernelGGL(topk_write_full, fgrid, block, 0, stream, a, s);
     st->pending = true;
