@@ -19,7 +19,7 @@
 // its *compressed* value with coefficient W_ii - 1.
 //
 // The paper leaves C_omega generic (Assumption 1.6 only asks for a bounded
-// signal-to-noise factor).  The four operators implemented here, and the exact
+// signal-to-noise factor).  The five operators implemented here, and the exact
 // floating-point evaluation order used for `real = float`, are this
 // repository's readings; every one is stated next to the code that does it.
 //
@@ -75,7 +75,7 @@ uint32_t rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
     return out[j % 4];
 }
 
-enum Kind { IDENTITY = 0, QUANT_MAXABS = 1, SIGN_MEANABS = 2, TOPK = 3 };
+enum Kind { IDENTITY = 0, QUANT_MAXABS = 1, SIGN_MEANABS = 2, TOPK = 3, QUANT_L2NORM = 4 };
 
 template <typename real> real fma_(real a, real b, real c);
 template <> float  fma_<float>(float a, float b, float c)    { return std::fmaf(a, b, c); }
@@ -184,6 +184,73 @@ void compress_row_topk(const real* v, real* cv, uint64_t N, uint64_t k, Msg<real
 }
 
 // ---------------------------------------------------------------------------
+// Sum of squares of a vector by a balanced binary tree in double precision:
+// the vector is padded with zeros to a power of two, adjacent pairs are added
+// first, then adjacent results, and so on.  (A pinned order, so that the
+// result is one well-defined number; the square of a float is exact in double.)
+// ---------------------------------------------------------------------------
+template <typename real>
+double sum_squares_tree(const real* v, uint64_t N) {
+    uint64_t P = 1;
+    while (P < N) P *= 2;
+    std::vector<double> a(P, 0.0);
+    for (uint64_t j = 0; j < N; ++j) a[j] = (double)v[j] * (double)v[j];
+    for (uint64_t len = P; len > 1; len /= 2)
+        for (uint64_t p = 0; p < len / 2; ++p) a[p] = a[2 * p] + a[2 * p + 1];
+    return a[0];
+}
+
+// ---------------------------------------------------------------------------
+// C_omega, operator 4: the compression of the paper's experiments (Section
+// "Experimental Setup", paragraph "Compression"): every element of a worker's
+// tensor becomes a b-bit code, and one number, the Euclidean norm of the
+// original tensor, travels with the codes; the receiver scales the decoded
+// tensor so that its Euclidean norm equals that number.
+// The paper gives neither grid nor rounding.  Reading: the grid is that of
+// operator 1 with the whole vector as one block (2^b equally spaced levels
+// from -s to +s, s = max|v|, which is not sent); v is rounded to the NEAREST
+// level (ties: to the even code), because the paragraph names no randomness
+// and Assumption 1.6 needs a signal-to-noise factor alpha < 1, which unbiased
+// random rounding to 4 levels does not give.  The code q stands for the odd
+// integer y = 2q - L, and the receiver returns
+//     C[v] = y * (nrm / ||y||_2),   nrm = ||v||_2 as sent (fp32),
+// with ||y||_2^2 = sum y_j^2 an exact integer (>= N, so never zero).
+// nrm^2 is the tree sum above; the scalar arithmetic is done in double and
+// rounded once:  nrm = (real) sqrt(S2),  unit = (real)(nrm / sqrt(sum y^2)).
+// Message: [f32 nrm][ceil(N*b/32) u32 words], codes packed as in operator 1.
+// ---------------------------------------------------------------------------
+template <typename real>
+void compress_row_quant_l2norm(const real* v, real* cv, uint64_t N, int bits, Msg<real>& msg) {
+    const int L = (1 << bits) - 1;
+    real s = 0;
+    for (uint64_t j = 0; j < N; ++j) s = std::max(s, (real)std::fabs(v[j]));
+    const real nrm = (real)std::sqrt(sum_squares_tree<real>(v, N));
+    const uint64_t nwords = (N * bits + 31) / 32;
+    std::vector<uint32_t> words(nwords, 0u);
+    std::vector<int> y(N);
+    const real hl = (real)0.5 * (real)L;
+    const real inv = (s > 0) ? hl / s : (real)0;
+    uint64_t sum_y2 = 0;
+    for (uint64_t j = 0; j < N; ++j) {
+        int q = 0;
+        if (s > 0) {
+            real tt = fma_<real>(v[j], inv, hl);         // (v/s + 1) * L/2 in [0, L]
+            tt = (tt > (real)0) ? tt : (real)0;          // also sends NaN to 0
+            tt = (tt < (real)L) ? tt : (real)L;
+            q = (int)std::nearbyint(tt);                 // round to nearest, ties to even (default rounding mode)
+        }
+        y[j] = 2 * q - L;
+        sum_y2 += (uint64_t)(y[j] * y[j]);
+        const uint64_t bitpos = j * (uint64_t)bits;
+        words[bitpos / 32] |= (uint32_t)q << (bitpos % 32);
+    }
+    const real unit = (real)((double)nrm / std::sqrt((double)sum_y2));
+    for (uint64_t j = 0; j < N; ++j) cv[j] = (real)y[j] * unit;
+    msg.put_f32(nrm);
+    for (uint64_t w = 0; w < nwords; ++w) msg.put_u32(words[w]);
+}
+
+// ---------------------------------------------------------------------------
 // One iteration for all workers.  Dense n x N row-major arrays throughout.
 // W comes as CSR (rowptr, col, val) *including* the diagonal entry of every
 // row, columns ascending; the mixing coefficient of line 9 is
@@ -197,7 +264,7 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
          real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes) {
     if (n < 1 || N < 1 || !rowptr || !col || !wval || !x || !delta || !g) return 1;
     if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && (block < 1 || (block & (block - 1)))) return 1;
-    if (kind == QUANT_MAXABS && (bits < 1 || bits > 8 || 32 % bits)) return 1;
+    if ((kind == QUANT_MAXABS || kind == QUANT_L2NORM) && (bits < 1 || bits > 8 || 32 % bits)) return 1;
     if (kind == TOPK && (k < 1 || k > N)) return 1;
     for (int i = 0; i < n; ++i) {                         // CSR sanity: sorted, has diagonal
         bool diag = false;
@@ -240,6 +307,8 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
             }
         } else if (kind == TOPK) {
             compress_row_topk<real>(vi, ci, N, k, msg);
+        } else if (kind == QUANT_L2NORM) {
+            compress_row_quant_l2norm<real>(vi, ci, N, bits, msg);
         } else {
             return 1;
         }
@@ -277,6 +346,8 @@ void dso_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) 
 uint32_t dso_rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
     return rounding_word(seed, t, i, j);
 }
+
+double dso_sum_squares_tree_f32(const float* v, uint64_t N) { return sum_squares_tree<float>(v, N); }
 
 int dso_step_f32(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const float* wval,
                  int kind, int bits, uint64_t block, uint64_t k, float gamma, float eta,

@@ -18,6 +18,7 @@ KIND_IDENTITY = 0      # C[v] = v: DeepSqueeze reduces to D-PSGD (paper, "Consis
 KIND_QUANT_MAXABS = 1  # stochastic b-bit block quantisation, max-abs scale
 KIND_SIGN_MEANABS = 2  # sign bit + block mean-abs scale
 KIND_TOPK = 3          # k largest magnitudes of the whole vector
+KIND_QUANT_L2NORM = 4  # b-bit codes over the whole vector + its Euclidean norm (the paper's experiments)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ds_oracle.cpp")
@@ -51,6 +52,8 @@ def _load():
     lib.dso_philox4x32_10.argtypes = [vp, vp, vp]
     lib.dso_rounding_word.restype = u32
     lib.dso_rounding_word.argtypes = [u64, u64, u32, u64]
+    lib.dso_sum_squares_tree_f32.restype = ctypes.c_double
+    lib.dso_sum_squares_tree_f32.argtypes = [vp, u64]
     _lib = lib
     return lib
 
@@ -69,6 +72,12 @@ def philox4x32_10(counter, key):
 def rounding_word(seed: int, t: int, i: int, j: int) -> int:
     """The 32-bit word that decides the stochastic rounding of element (i, j) at step t."""
     return int(_load().dso_rounding_word(seed, t, i, j))
+
+
+def sum_squares_tree(v) -> float:
+    """Sum of squares of a float32 vector in float64, balanced adjacent-pairs tree over the zero-padded vector."""
+    a = np.ascontiguousarray(v, dtype=np.float32)
+    return float(_load().dso_sum_squares_tree_f32(a.ctypes.data, a.size))
 
 
 # --- dense helpers for the tests' matrix identities --------------------------------------------
@@ -116,6 +125,8 @@ def message_bytes(kind: int, n: int, N: int, bits: int = 0, block: int = 0, k: i
         return n * N * 4
     if kind == KIND_TOPK:
         return n * k * 8
+    if kind == KIND_QUANT_L2NORM:
+        return n * (4 + 4 * ((N * bits + 31) // 32))
     b = bits if kind == KIND_QUANT_MAXABS else 1
     full, tail = divmod(N, block)
     per_row = full * (4 + 4 * ((block * b + 31) // 32))

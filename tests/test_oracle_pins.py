@@ -17,7 +17,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, OracleState)
+from oracle import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, OracleState)
 
 
 # ----------------------------------------------------------------------------- helpers
@@ -155,6 +155,8 @@ COMPRESSORS = [
     dict(kind=KIND_QUANT_MAXABS, bits=2, block=32),
     dict(kind=KIND_SIGN_MEANABS, block=8),
     dict(kind=KIND_TOPK, k=5),
+    dict(kind=KIND_QUANT_L2NORM, bits=2),
+    dict(kind=KIND_QUANT_L2NORM, bits=4),
 ]
 
 
@@ -285,6 +287,133 @@ def test_hand_expanded_example_matches_rational_brute_force(golden_dir):
               for j in range(N)] for i in range(n)]
         np.testing.assert_allclose(np.array(X, dtype=float), rec["x"], atol=1e-15)
         np.testing.assert_allclose(np.array(D, dtype=float), rec["d"], atol=1e-15)
+
+
+# ----------------------------------------------------------------------------- the experiments' compressor
+
+def l2norm_state(v, bits, dtype=np.float32, n=1):
+    v = np.asarray(v, dtype=dtype).reshape(n, -1)
+    W = np.ones((1, 1)) if n == 1 else np.eye(n)
+    return OracleState(n=n, N=v.shape[1], W=W, kind=KIND_QUANT_L2NORM, bits=bits, gamma=0.0, eta=0.5,
+                       dtype=dtype, x=v.copy())
+
+
+def test_l2norm_worked_example(golden_dir):
+    rec = {l.split()[0]: l.split()[1:] for l in open(os.path.join(golden_dir, "l2norm_2bit_micro.txt"))
+           if l[0] != "#"}
+    v = np.array([float(t) for t in rec["v"]], dtype=np.float32)
+    y = np.array([int(t) for t in rec["y"]])
+    nrm = np.float32(np.sqrt(float(rec["sum_v2"][0])))
+    unit = np.float32(float(nrm) / np.sqrt(float(rec["sum_y2"][0])))
+    st = l2norm_state(v, 2)
+    cv, msg = oracle.step(st, np.zeros((1, 8), np.float32))
+    assert msg[:4].tobytes() == nrm.tobytes()
+    assert np.frombuffer(msg[4:8].tobytes(), np.uint32)[0] == int(rec["word"][0], 16) and len(msg) == 8
+    assert list(unpack_codes(np.frombuffer(msg[4:8].tobytes(), np.uint32), 2, 8)) == [int(t) for t in rec["q"]]
+    np.testing.assert_array_equal(cv[0], y.astype(np.float32) * unit)
+    np.testing.assert_array_equal(st.delta[0], v - y.astype(np.float32) * unit)
+    np.testing.assert_array_equal(st.x[0], v)                   # W = [1]: nothing is mixed in
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_l2norm_receiver_restores_the_euclidean_norm(bits, dtype):
+    # the property the paper states: the decoded tensor has the Euclidean norm of the original one
+    r = np.random.default_rng(21)
+    n, N, L = 3, 1000 + 37, (1 << bits) - 1
+    v = (r.standard_normal((n, N)) * np.array([[1e-3], [1.0], [50.0]])).astype(dtype)
+    st = l2norm_state(v, bits, dtype=dtype, n=n)
+    cv, msg = oracle.step(st, np.zeros_like(v), want_msg=(dtype == np.float32))
+    tol = 2e-7 if dtype == np.float32 else 1e-14
+    exact = np.sqrt((v.astype(np.float64) ** 2).sum(1))
+    np.testing.assert_allclose(np.sqrt((cv.astype(np.float64) ** 2).sum(1)), exact, rtol=tol)
+    # C[v] is a positive multiple of a vector of odd integers in [-L, L] ...
+    unit = np.abs(cv).min(1, keepdims=True)                     # |y| = 1 occurs in every row of this input
+    y = cv / unit
+    assert np.all(np.abs(y - np.rint(y)) < 1e-5) and np.all(np.rint(np.abs(y)) % 2 == 1) and np.abs(y).max() <= L + 1e-5
+    # ... namely the nearest odd integer to L v / max|v| (no randomness: two runs agree, and the seed is irrelevant)
+    target = L * v.astype(np.float64) / np.abs(v).max(1, keepdims=True)
+    assert np.all(np.abs(np.rint(y) - target) <= 1.0 + 1e-5)
+    st2 = l2norm_state(v, bits, dtype=dtype, n=n)
+    st2.seed = 1234
+    cv2, _ = oracle.step(st2, np.zeros_like(v), want_msg=False)
+    np.testing.assert_array_equal(cv, cv2)
+    if dtype == np.float32:
+        # the message alone gives back C[v]: the receiver knows only the codes and the norm
+        row = 4 + 4 * ((N * bits + 31) // 32)
+        assert len(msg) == n * row
+        for i in range(n):
+            m = msg[i * row:(i + 1) * row]
+            sent = np.frombuffer(m[:4].tobytes(), np.float32)[0]
+            assert abs(float(sent) - exact[i]) <= 1e-7 * exact[i]
+            q = unpack_codes(np.frombuffer(m[4:].tobytes(), np.uint32), bits, N)
+            yy = 2 * q - L
+            dec = yy.astype(np.float32) * np.float32(float(sent) / np.sqrt(float((yy * yy).sum())))
+            np.testing.assert_array_equal(dec, cv[i])
+            # padding bits of the last word are zero
+            last = int(np.frombuffer(m[-4:].tobytes(), np.uint32)[0])
+            used = (N * bits) % 32
+            assert used == 0 or last >> used == 0
+
+
+def test_l2norm_rounds_to_the_nearest_level_ties_to_even():
+    # brute force in exact rational arithmetic; with s = max|v| = L the map is t = v/2 + L/2, exact in
+    # floating point for multiples of 1/4, and every even integer v is a real tie (t = q + 1/2)
+    for bits in (2, 4):
+        L = (1 << bits) - 1
+        ks = np.arange(-4 * L, 4 * L + 1)
+        v = ks / 4.0
+        st = l2norm_state(v, bits, dtype=np.float64)
+        cv, _ = oracle.step(st, np.zeros((1, v.size)), want_msg=False)
+        unit = np.abs(cv).min()
+        got = np.rint(cv[0] / unit).astype(int)
+        ties = 0
+        for k, yk in zip(ks, got):
+            t = (Fraction(int(k), 4 * L) + 1) * Fraction(L, 2)  # (v/s + 1) L / 2
+            lo = t.numerator // t.denominator
+            fr = t - lo
+            ties += fr == Fraction(1, 2)
+            q = lo + (1 if fr > Fraction(1, 2) or (fr == Fraction(1, 2) and lo % 2 == 1) else 0)
+            assert yk == 2 * q - L, (bits, k, yk, q)
+        assert ties == L                                        # t = 1/2, 3/2, ..., L - 1/2
+
+
+@pytest.mark.parametrize("bits,bound", [(2, 0.5), (4, 0.05)])
+def test_l2norm_satisfies_the_signal_to_noise_assumption(bits, bound):
+    # Assumption 1.6: |C[v] - v|^2 <= alpha^2 |v|^2 with alpha < 1.  On Gaussian vectors the operator
+    # behaves like a scaled sign for 2 bits (alpha^2 = 2 (1 - sqrt(2/pi)) ~ 0.40) and like a fine grid for 4.
+    r = np.random.default_rng(22)
+    v = r.standard_normal((4, 1 << 14))
+    st = l2norm_state(v, bits, dtype=np.float64, n=4)
+    cv, _ = oracle.step(st, np.zeros_like(v), want_msg=False)
+    alpha2 = ((cv - v) ** 2).sum(1) / (v ** 2).sum(1)
+    assert np.all(alpha2 < bound), alpha2
+    if bits == 2:
+        assert np.all(alpha2 > 0.3)
+
+
+def test_l2norm_zero_vector_and_single_element():
+    st = l2norm_state(np.zeros(10), 4)
+    cv, msg = oracle.step(st, np.zeros((1, 10), np.float32))
+    assert np.all(cv == 0) and np.all(st.delta == 0) and np.all(msg == 0)
+    st = l2norm_state([-2.5], 2)                                 # one element: C[v] = v exactly
+    cv, msg = oracle.step(st, np.zeros((1, 1), np.float32))
+    assert cv[0, 0] == np.float32(-2.5) and st.delta[0, 0] == 0 and msg[4] == 0
+
+
+def test_sum_of_squares_is_the_adjacent_pairs_tree_in_double():
+    A = 2.0 ** 27                                               # A^2 = 2^54, where doubles are 4 apart
+    # tree: (A^2+1) -> A^2, (1+1) three times, A^2+2 -> tie -> A^2, 2+2, A^2+4 exact; left to right stays at A^2
+    assert oracle.sum_squares_tree([A, 1, 1, 1, 1, 1, 1, 1]) == 2.0 ** 54 + 4
+    # five elements are padded to eight: (A^2+1), (1+1), (1+0), (0+0) -> A^2+2 -> A^2, 1 -> A^2
+    assert oracle.sum_squares_tree([A, 1, 1, 1, 1]) == 2.0 ** 54
+    assert oracle.sum_squares_tree([1, 1, 1, 1, A]) == 2.0 ** 54 + 4
+    r = np.random.default_rng(23)
+    v = r.standard_normal(3001).astype(np.float32)
+    import math
+    exact = math.fsum(float(t) * float(t) for t in v)
+    assert abs(oracle.sum_squares_tree(v) - exact) <= 1e-13 * exact
+    assert oracle.sum_squares_tree(np.zeros(0, np.float32)) == 0.0
 
 
 # ----------------------------------------------------------------------------- P7: quantiser
