@@ -52,13 +52,21 @@ typedef enum {
     DS_COMP_QUANT_MAXABS = 1, /* stochastic `bits`-bit uniform quantisation per block of `block` */
                               /* elements, scale = max |v| of the block; bits in {2, 4}          */
     DS_COMP_SIGN_MEANABS = 2, /* sign bit per element, scale = mean |v| of the block            */
-    DS_COMP_TOPK = 3          /* the k largest |v| of each worker's whole vector, ties to the   */
+    DS_COMP_TOPK = 3,         /* the k largest |v| of each worker's whole vector, ties to the   */
                               /* lower index; message = k (u32 index, f32 value) pairs          */
+    DS_COMP_QUANT_L2NORM = 4  /* the compression of the paper's experiments (section             */
+                              /* "Experimental Setup", paragraph "Compression"): a `bits`-bit     */
+                              /* code per element of the worker's whole vector plus ONE number,   */
+                              /* its Euclidean norm, to which the receiver rescales what it       */
+                              /* decodes.  Grid: 2^bits levels from -max|v| to +max|v|, nearest   */
+                              /* level (ties to the even code); code q stands for y = 2q - L,     */
+                              /* C[v] = y * (norm / ||y||_2).  Message per worker:                */
+                              /* [f32 norm][ceil(N*bits/32) u32 words]; bits in {2, 4}            */
 } ds_comp_kind;
 
 typedef struct {
     int32_t  kind;    /* ds_comp_kind */
-    int32_t  bits;    /* QUANT_MAXABS: 2 or 4; otherwise ignored                                */
+    int32_t  bits;    /* QUANT_MAXABS, QUANT_L2NORM: 2 or 4; otherwise ignored                  */
     int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 256 <= block <= 2048          */
     int32_t  reserved;
     uint64_t k;       /* TOPK: 1 <= k <= N; otherwise ignored                                   */

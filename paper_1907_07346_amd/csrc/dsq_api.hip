@@ -26,6 +26,7 @@ struct ds_handle {
     dsq::TilePlan tile;
     std::vector<dsq::TilePlan> tile_candidates;
     dsq::TopkState* topk = nullptr;
+    dsq::L2State* l2q = nullptr;
     std::string err;
     std::string plan_name;
 };
@@ -50,6 +51,7 @@ ds_status hip_fail(ds_handle* h, hipError_t e, const char* what) {
 void release(ds_handle* h) {
     if (!h) return;
     if (h->topk) dsq::topk_destroy(h->topk);
+    if (h->l2q) dsq::l2q_destroy(h->l2q);
     if (h->x) (void)hipFree(h->x);
     if (h->delta) (void)hipFree(h->delta);
     if (h->msg) (void)hipFree(h->msg);
@@ -58,6 +60,14 @@ void release(ds_handle* h) {
     delete h;
 }
 
+
+// Two paths (top-k, norm-rescaled codes) leave the tail of a step to the next step's first pass;
+// this applies it now, on the stream of the last step.
+ds_status flush_deferred(ds_handle* h) {
+    if (h->topk) return dsq::topk_flush(h->topk, h->last_stream);
+    if (h->l2q) return dsq::l2q_flush(h->l2q, h->last_stream);
+    return DS_OK;
+}
 
 dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     dsq::TileArgs a{};
@@ -210,8 +220,11 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     h->ld = base_ld + kMaxPitchSkew;                       // allocation pitch; the working pitch is fixed below
     h->msg_row_bytes = dsq::message_row_bytes(cfg);
 
+    const bool tiled = cfg->comp.kind != DS_COMP_TOPK && cfg->comp.kind != DS_COMP_QUANT_L2NORM;
     if (cfg->comp.kind == DS_COMP_TOPK) {
         h->plan_name = "topk/radix-select";
+    } else if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {
+        h->plan_name = "l2norm/two-pass";
     } else {
         if (!dsq::choose_tile_plans(h->cfg, (int)h->graph.col.size(), h->tile_candidates, err)) {
             std::fprintf(stderr, "ds_init: %s\n", err.c_str());
@@ -258,16 +271,20 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     if (pin && *pin) {
         const unsigned long long v = std::strtoull(pin, nullptr, 10);
         if (v <= kMaxPitchSkew && (v & 3) == 0) skew = v;
-    } else if (cfg->comp.kind != DS_COMP_TOPK && (uint64_t)cfg->n * cfg->N >= (32ull << 20)) {
+    } else if (tiled && (uint64_t)cfg->n * cfg->N >= (32ull << 20)) {
         skew = autotune(h, base_ld, state_bytes, msg_bytes);
     }
     h->ld = base_ld + skew;
-    if (cfg->comp.kind != DS_COMP_TOPK)
+    if (tiled)
         h->plan_name = std::string(h->tile.name) + "/" + std::to_string(h->tile.sweeps) + "sweeps";
     h->plan_name += "/pitch+" + std::to_string(skew);
 
     if (cfg->comp.kind == DS_COMP_TOPK) {
         const ds_status st = dsq::topk_create(h->cfg, h->ld, &h->topk, err);
+        if (st != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(st); }
+    }
+    if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {
+        const ds_status st = dsq::l2q_create(h->cfg, h->ld, &h->l2q, err);
         if (st != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(st); }
     }
     h->err = warn;
@@ -293,6 +310,14 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
         a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
         const ds_status st = dsq::topk_step(h->topk, a, h->graph, stream, h->err);
         if (st != DS_OK) return st;
+    } else if (h->cfg.comp.kind == DS_COMP_QUANT_L2NORM) {
+        dsq::L2Args a{};
+        a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
+        a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
+        a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes; a.n = h->cfg.n;
+        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
+        const ds_status st = dsq::l2q_step(h->l2q, a, stream);
+        if (st != DS_OK) return fail(h, st, "launching the norm-rescaled step failed");
     } else {
         const dsq::TileArgs a = tile_args(h, g_dev, g_ld);
         h->tile.launch(a, h->tile.rows_per_wave, stream);
@@ -314,13 +339,13 @@ ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_
     dsq::Graph g;
     if (dsq::build_graph(&probe, g, err) != DS_OK) return fail(h, DS_EINVAL, err);
     const size_t nnz = g.col.size();
-    if (h->cfg.comp.kind != DS_COMP_TOPK) {
+    if (!h->topk && !h->l2q) {
         // the launch shape was chosen for the old graph; the new CSR only has to fit in LDS next to the codes
         std::vector<dsq::TilePlan> plans;
         if (!dsq::choose_tile_plans(h->cfg, (int)nnz, plans, err)) return fail(h, DS_EINVAL, err);
     }
-    // the deferred tail of a top-k step belongs to the old W: apply it first
-    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
+    // a deferred tail belongs to the old W: apply it first
+    if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     // same number of stored entries: overwrite in place, so that the device addresses (and a HIP graph captured
     // from ds_step with them) stay valid
@@ -346,7 +371,7 @@ ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_
 ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host) {
     if (!h) return DS_EINVAL;
     if (!x_host && !delta_host) return fail(h, DS_EINVAL, "nothing to read");
-    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
+    if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
     if (x_host) DSQ_HIP(h, hipMemcpy2D(x_host, row, h->x, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
@@ -356,7 +381,7 @@ ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host) {
 
 ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_host, uint64_t t) {
     if (!h) return DS_EINVAL;
-    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
+    if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
     if (x_host) DSQ_HIP(h, hipMemcpy2D(h->x, pitch, x_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
@@ -382,7 +407,7 @@ ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t*
 ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t* ld) {
     if (!h) return DS_EINVAL;
     // top-k keeps the sparse part of the last gossip update pending; complete x before lending it
-    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
+    if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
     if (x_dev) *x_dev = h->x;
     if (delta_dev) *delta_dev = h->delta;
     if (ld) *ld = h->ld;
@@ -398,7 +423,7 @@ ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes) {
 
 ds_status ds_diagnostics(ds_handle* h, double* out4) {
     if (!h || !out4) return DS_EINVAL;
-    if (h->topk && dsq::topk_flush(h->topk, h->last_stream) != DS_OK) return fail(h, DS_EHIP, "top-k flush failed");
+    if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     double* d_out = nullptr;
     DSQ_HIP(h, hipMalloc(&d_out, 3 * sizeof(double)));

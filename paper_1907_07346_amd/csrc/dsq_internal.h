@@ -92,4 +92,27 @@ ds_status topk_flush(TopkState* s, hipStream_t stream);
 // Number of rows whose last step selected from the candidate slots (the fast path).
 ds_status topk_candidate_rows(TopkState* s, hipStream_t stream, uint32_t* count);
 
+// ---- norm-rescaled b-bit path (DS_COMP_QUANT_L2NORM) ----------------------------------------------
+struct L2Args {
+    float* x;
+    float* delta;
+    const float* g;
+    uint8_t* msg;              // n rows of [f32 norm][code words]
+    const int32_t* rowptr;
+    const int32_t* col;
+    const float* coef;
+    uint64_t ld, g_ld, N, msg_row_bytes;
+    int n;
+    float gamma, eta;
+    unsigned long long* t_ptr;  // step counter in device memory (advanced once per step)
+};
+
+struct L2State;                // device scratch: per-row scales, per-chunk partial reductions
+ds_status l2q_create(const ds_config& cfg, uint64_t ld, L2State** out, std::string& err);
+void l2q_destroy(L2State* s);
+ds_status l2q_step(L2State* s, const L2Args& a, hipStream_t stream);
+// l2q_step leaves delta = v - C[v] and the gossip update of x to the next step's first pass;
+// l2q_flush applies them now (no-op if nothing is pending).  Call before the state is read or replaced.
+ds_status l2q_flush(L2State* s, hipStream_t stream);
+
 }  // namespace dsq

@@ -150,6 +150,12 @@ SMALL = [
     small(wl.KIND_TOPK, 3, 5, k=1),
     small(wl.KIND_TOPK, 4, 9000, k=9000),                                          # k = N: everything is sent
     small(wl.KIND_TOPK, 16, 20_000, k=200, topo=wl.TOPO_TORUS2D, torus=(4, 4)),
+    small(wl.KIND_QUANT_L2NORM, 8, 4096 * 2 + 37, bits=4),                         # chunks of 4096 columns + ragged tail
+    small(wl.KIND_QUANT_L2NORM, 16, 4096 * 3 + 2, bits=2),
+    small(wl.KIND_QUANT_L2NORM, 3, 5, bits=2),
+    small(wl.KIND_QUANT_L2NORM, 5, 4096, bits=4),
+    small(wl.KIND_QUANT_L2NORM, 9, 9001, bits=2, topo=wl.TOPO_TORUS2D, torus=(3, 3)),
+    small(wl.KIND_QUANT_L2NORM, 3, 4096 * 1030 + 3, bits=2),                       # > 1024 chunks: 2 tree leaves per thread
 ]
 
 
@@ -204,7 +210,8 @@ def test_general_graph_csr():
     rp, co, va = oracle.dense_to_csr(W)
     for w in (small(wl.KIND_QUANT_MAXABS, n, 512 * 3 + 9, bits=4, block=512),
               small(wl.KIND_SIGN_MEANABS, n, 777, block=256),
-              small(wl.KIND_TOPK, n, 12_345, k=77)):
+              small(wl.KIND_TOPK, n, 12_345, k=77),
+              small(wl.KIND_QUANT_L2NORM, n, 4096 + 77, bits=2)):
         say("case", w.name)
         # the oracle rounds W to fp32 exactly like the CSR handed to the library
         lock_step(w, steps=2, W=W, csr=(rp, co, va.astype(np.float32)))
@@ -234,7 +241,8 @@ def test_time_varying_graph():
     n = 12
     for w in (small(wl.KIND_QUANT_MAXABS, n, 512 * 3 + 9, bits=4, block=512),
               small(wl.KIND_SIGN_MEANABS, n, 777, block=256),
-              small(wl.KIND_TOPK, n, 12_345, k=77)):
+              small(wl.KIND_TOPK, n, 12_345, k=77),
+              small(wl.KIND_QUANT_L2NORM, n, 4096 * 2 + 77, bits=4)):
         say("case", w.name)
         ds = b.DeepSqueeze.from_workload(w)
         st = oracle_state(w)
@@ -440,7 +448,8 @@ def test_two_handles_interleaved():
 
 
 @pytest.mark.parametrize("w", [small(wl.KIND_QUANT_MAXABS, 8, 512 * 9 + 37, bits=4, block=512),
-                               small(wl.KIND_TOPK, 8, 30_011, k=300)], ids=lambda w: w.name)
+                               small(wl.KIND_TOPK, 8, 30_011, k=300),
+                               small(wl.KIND_QUANT_L2NORM, 8, 4096 * 5 + 11, bits=2)], ids=lambda w: w.name)
 def test_hip_graph_replay(w):
     """ds_step captured once into a HIP graph and replayed: the step counter lives on the device, so every
     replay draws fresh rounding words; each replay is checked against the oracle, with eager work between."""
@@ -476,6 +485,61 @@ def test_hip_graph_replay(w):
         assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} replay {t}: messages differ"
         x, d = ds.ds_read_state()                          # eager work (incl. the top-k flush) between replays
         assert assert_close(f"replay {t} x", x, st.x) + assert_close(f"replay {t} delta", d, st.delta) == 0
+    ds.ds_destroy()
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_l2norm_free_run_messages_every_step(bits):
+    # nothing reads the state between the steps, so every step's tail (delta = v - C[v] and the gossip
+    # update) is applied by the next step's first pass; the messages are compared after every step
+    w = small(wl.KIND_QUANT_L2NORM, 8, 4096 * 6 + 1001, bits=bits, grad="quadratic")
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w)
+    c = wl.centres(w)
+    for t in range(8):
+        g = wl.gradient(w, t, st.x, c)
+        ds.ds_step(upload(g))
+        _, msg = oracle.step(st, g, want_cv=False)
+        assert np.array_equal(ds.ds_read_messages(), msg), f"step {t}: messages differ"
+    x, d = ds.ds_read_state()
+    assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+    x2, d2 = ds.ds_read_state()                               # a second read finds nothing pending
+    assert np.array_equal(x, x2) and np.array_equal(d, d2)
+    ds.ds_destroy()
+
+
+def test_l2norm_worked_example_and_zero_rows_on_gpu(golden_dir):
+    rec = {l.split()[0]: l.split()[1:] for l in open(os.path.join(golden_dir, "l2norm_2bit_micro.txt"))
+           if l[0] != "#"}
+    v = np.array([float(t) for t in rec["v"]], dtype=np.float32)
+    y = np.array([int(t) for t in rec["y"]]).astype(np.float32)
+    nrm = np.float32(np.sqrt(float(rec["sum_v2"][0])))
+    unit = np.float32(float(nrm) / np.sqrt(float(rec["sum_y2"][0])))
+    # three workers on a ring: worker 0 holds the example, worker 1 is all zero, worker 2 holds -example
+    n = 3
+    x0 = np.stack([v, np.zeros_like(v), -v])
+    cfg, keep = b.make_config(n, 8, wl.TOPO_RING, wl.KIND_QUANT_L2NORM, 0.0, 0.5, bits=2)
+    ds = b.DeepSqueeze(cfg, keep)
+    ds.ds_write_state(x0, np.zeros_like(x0), 0)
+    ds.ds_step(torch.zeros((n, 8), device="cuda"))
+    msg = ds.ds_read_messages().reshape(n, 8)
+    assert msg[0, :4].tobytes() == nrm.tobytes() and msg[2, :4].tobytes() == nrm.tobytes()
+    assert np.frombuffer(msg[0, 4:].tobytes(), np.uint32)[0] == int(rec["word"][0], 16)
+    assert np.all(msg[1] == 0)                                # zero vector: norm 0, all codes 0
+    x, d = ds.ds_read_state()
+    y_neg = -y
+    y_neg[3] = 1.0                                            # v = 0 sits on a tie and takes the even code either way
+    C = np.stack([y * unit, np.zeros(8, np.float32), y_neg * unit])
+    np.testing.assert_array_equal(d, x0 - C)
+    W = oracle.ring_matrix(3).astype(np.float32)
+    A = W - np.eye(3, dtype=np.float32)
+    want = x0.copy()
+    for i in range(n):
+        acc = np.zeros(8, np.float32)
+        for j in range(n):
+            acc = (np.float64(A[i, j]) * C[j].astype(np.float64) + acc.astype(np.float64)).astype(np.float32)
+        want[i] = (np.float64(np.float32(0.5)) * acc.astype(np.float64) + x0[i].astype(np.float64)).astype(np.float32)
+    np.testing.assert_allclose(x, want, rtol=1e-6, atol=1e-7)
     ds.ds_destroy()
 
 
