@@ -33,7 +33,6 @@ namespace {
 
 constexpr int LQ_THREADS = 256;
 constexpr int LQ_ITERS = 4;
-constexpr int LQ_SWEEP = 4 * 64;                          // columns one wave covers per iteration
 constexpr int LQ_CHUNK = 4 * LQ_THREADS * LQ_ITERS;       // 4096 columns per workgroup
 constexpr int LQ_ROW_THREADS = 1024;                      // threads of the per-row kernels
 

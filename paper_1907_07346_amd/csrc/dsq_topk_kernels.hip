@@ -114,7 +114,9 @@ struct Scratch {               // device pointers of the select's scratch (all o
     uint32_t* eq_before;       // n x nchunks: ties in earlier chunks of the row
     uint32_t* out_off;         // n x (nchunks+1): message offset of each chunk
     uint32_t* cand_cnt;        // n x nchunks: candidates stored in the chunk's slot
-    uint2* slots;              // n x nchunks x TK_CAP candidate (index, value bits) pairs, unordered inside a slot
+    uint32_t* slot_val;        // n x nchunks x TK_CAP candidate values (fp32 bits), unordered inside a slot; the select
+                               // passes read only these
+    uint16_t* slot_idx;        // same shape: the candidates' columns, relative to the start of the chunk
     uint32_t nchunks;
 };
 
@@ -186,7 +188,8 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     const uint32_t tlo = s.rows[row].tlo;
     const uint32_t bin0 = tlo >> SHIFT1;                       // (0xfff for "collect nothing")
     bool far = false;                                          // a candidate beyond the tracked bins
-    uint2* slot = s.slots + ((size_t)row * s.nchunks + chunk) * TK_CAP;
+    uint32_t* slot_val = s.slot_val + ((size_t)row * s.nchunks + chunk) * TK_CAP;
+    uint16_t* slot_idx = s.slot_idx + ((size_t)row * s.nchunks + chunk) * TK_CAP;
 #pragma unroll
     for (int it = 0; it < TK_ITERS; ++it) {
         const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
@@ -217,7 +220,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
         for (int c = 0; c < 4; ++c)
             if (j + c < a.N && key_of(vv[c]) >= tlo) {
                 const uint32_t idx = atomicAdd(&cand_count, 1u);
-                if (idx < (uint32_t)TK_CAP) slot[idx] = make_uint2((uint32_t)(j + c), __float_as_uint(vv[c]));
+                if (idx < (uint32_t)TK_CAP) { slot_val[idx] = __float_as_uint(vv[c]); slot_idx[idx] = (uint16_t)(q0 + c); }
                 const uint32_t rel = (key_of(vv[c]) >> SHIFT1) - bin0;
                 if (rel < (uint32_t)TK_H1) atomicAdd(&h[rel], 1u); else far = true;
             }
@@ -330,12 +333,12 @@ __global__ void __launch_bounds__(TK_HTHREADS) topk_hist_cand(Scratch s) {
     for (uint32_t chunk = first + threadIdx.x / TPC; chunk < last; chunk += SIDE) {
         const size_t cidx = (size_t)row * s.nchunks + chunk;
         const uint32_t cnt = s.cand_cnt[cidx];
-        const uint2* slot = s.slots + cidx * TK_CAP;
+        const uint32_t* slot = s.slot_val + cidx * TK_CAP;
         uint32_t gt = 0, eq = 0;
         for (uint32_t p0 = sub; p0 < cnt; p0 += 8 * TPC) {
             uint32_t key[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC].y & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+            for (int u = 0; u < 8; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC] & 0x7FFFFFFFu) : 0xFFFFFFFFu;
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (key[u] != 0xFFFFFFFFu) hist_key<LEVEL>(key[u], prefix, h, gt, eq);
@@ -464,10 +467,10 @@ __global__ void __launch_bounds__(TK_THREADS) topk_fix_cand(Scratch s) {
         const size_t cidx = (size_t)row * s.nchunks + chunk;
         if (s.cnt_eq[cidx] != 0) {
             const uint32_t cnt = s.cand_cnt[cidx];
-            const uint2* slot = s.slots + cidx * TK_CAP;
+            const uint32_t* slot = s.slot_val + cidx * TK_CAP;
             uint32_t gt = 0, eq = 0;
             for (uint32_t p = sub; p < cnt; p += TPC) {
-                const uint32_t key = slot[p].y & 0x7FFFFFFFu;
+                const uint32_t key = slot[p] & 0x7FFFFFFFu;
                 gt += key > tau;
                 eq += key == tau;
             }
@@ -494,21 +497,32 @@ __global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(Scratch s, unsign
     const uint32_t* eq = s.cnt_eq + (size_t)row * nchunks;
     uint32_t* eqb = s.eq_before + (size_t)row * nchunks;
     uint32_t* off = s.out_off + (size_t)row * (nchunks + 1);
-    uint32_t run_eq = 0, run_out = 0;
-    for (uint32_t base = 0; base < nchunks; base += TK_THREADS) {
-        const uint32_t c = base + threadIdx.x;
-        const uint32_t e = (c < nchunks) ? eq[c] : 0u;
-        const uint32_t g = (c < nchunks) ? gt[c] : 0u;
-        uint32_t tot_e, tot_o;
-        const uint32_t before = run_eq + block_exclusive_scan(e, wave_sums, &tot_e);
+    // each thread owns a run of consecutive chunks, so that two workgroup scans serve the whole row
+    const uint32_t per = (nchunks + TK_THREADS - 1) / TK_THREADS;
+    const uint32_t lo = (threadIdx.x * per < nchunks) ? threadIdx.x * per : nchunks;
+    const uint32_t hi = (lo + per < nchunks) ? lo + per : nchunks;
+    uint32_t sum_e = 0;
+    for (uint32_t c = lo; c < hi; ++c) sum_e += eq[c];
+    uint32_t tot_e, tot_o;
+    const uint32_t before0 = block_exclusive_scan(sum_e, wave_sums, &tot_e);   // ties in earlier chunks of the row
+    uint32_t before = before0, sum_take = 0;
+    for (uint32_t c = lo; c < hi; ++c) {
+        const uint32_t e = eq[c];
         const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
-        const uint32_t take = g + (e < quota ? e : quota);
-        const uint32_t o = run_out + block_exclusive_scan(take, wave_sums, &tot_o);
-        if (c < nchunks) { eqb[c] = before; off[c] = o; }
-        run_eq += tot_e;
-        run_out += tot_o;
+        sum_take += gt[c] + (e < quota ? e : quota);
+        before += e;
     }
-    if (threadIdx.x == 0) { off[nchunks] = run_out; s.rows[row].total = run_out; }
+    uint32_t o = block_exclusive_scan(sum_take, wave_sums, &tot_o);
+    before = before0;
+    for (uint32_t c = lo; c < hi; ++c) {
+        const uint32_t e = eq[c];
+        const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
+        eqb[c] = before;
+        off[c] = o;
+        o += gt[c] + (e < quota ? e : quota);
+        before += e;
+    }
+    if (threadIdx.x == 0) { off[nchunks] = tot_o; s.rows[row].total = tot_o; }
 }
 
 // ---- ordered compaction: message pairs, delta <- 0 on the selected set (Algorithm 1, line 6) ----
@@ -598,35 +612,45 @@ __device__ __forceinline__ uint32_t bitmap_rank(const uint32_t* bits, const uint
 __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
     __shared__ uint32_t sel_bits[TK_WORDS], eq_bits[TK_WORDS], prefix[TK_WORDS];
     const int row = blockIdx.y;
-    if (!s.rows[row].cand_mode) return;
     const int lane = threadIdx.x;
     const uint32_t nchunks = s.nchunks, chunk = blockIdx.x;
     const size_t cidx = (size_t)row * nchunks + chunk;
+    const uint32_t* slot_val = s.slot_val + cidx * TK_CAP;
+    const uint16_t* slot_idx = s.slot_idx + cidx * TK_CAP;
+    // The slot goes into registers, 8 pairs per lane.  The first half is loaded before anything is known
+    // about the chunk (the slot's memory exists whatever its fill; what lies behind `cnt` is discarded
+    // below), so that these loads do not queue behind the chunk's counters.
+    constexpr int EPL = TK_CAP / 64, SPEC = EPL / 2;
+    uint2 ent[EPL];
+#pragma unroll
+    for (int u = 0; u < SPEC; ++u) {
+        const uint32_t p = (uint32_t)u * 64 + lane;
+        ent[u] = make_uint2(slot_idx[p], slot_val[p]);     // .x: column in the chunk
+    }
+    const uint32_t cand_mode = s.rows[row].cand_mode;
+    const uint32_t tau = s.rows[row].tau, r_tie = s.rows[row].r_tie;
     const uint32_t off0 = s.out_off[(size_t)row * (nchunks + 1) + chunk];
     const uint32_t off1 = s.out_off[(size_t)row * (nchunks + 1) + chunk + 1];
-    if (off0 == off1) return;                               // uniform
-    const uint32_t tau = s.rows[row].tau, r_tie = s.rows[row].r_tie;
-    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
     const uint32_t cnt = s.cand_cnt[cidx];
-    const uint2* slot = s.slots + cidx * TK_CAP;
     const uint32_t eqb = s.eq_before[cidx];
+    const uint32_t cnt_eq = s.cnt_eq[cidx];
+    if (!cand_mode || off0 == off1) return;                 // uniform
+    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
     const uint32_t quota = (eqb < r_tie) ? (r_tie - eqb) : 0u;   // ties of this chunk that belong to the set
-    const bool ties = s.cnt_eq[cidx] != 0 && quota != 0;
-    // the whole slot goes into registers (16 pairs per lane, all loads in flight at once)
-    constexpr int EPL = TK_CAP / 64;
-    uint2 ent[EPL];
+    const bool ties = cnt_eq != 0 && quota != 0;
 #pragma unroll
     for (int u = 0; u < EPL; ++u) {
         const uint32_t p = (uint32_t)u * 64 + lane;
-        ent[u] = (p < cnt) ? slot[p] : make_uint2(0xFFFFFFFFu, 0u);
+        if (u < SPEC) { if (p >= cnt) ent[u] = make_uint2(0xFFFFFFFFu, 0u); }
+        else ent[u] = (p < cnt) ? make_uint2(slot_idx[p], slot_val[p]) : make_uint2(0xFFFFFFFFu, 0u);
     }
     for (int w = lane; w < TK_WORDS; w += 64) { sel_bits[w] = 0; eq_bits[w] = 0; }
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < EPL; ++u) {
         const uint32_t key = ent[u].y & 0x7FFFFFFFu;
-        const uint32_t q = (uint32_t)((uint64_t)ent[u].x - c0);
-        if (q >= (uint32_t)TK_CHUNK) continue;              // also the padding pairs
+        const uint32_t q = ent[u].x;
+        if (q >= (uint32_t)TK_CHUNK) continue;              // the padding pairs
         if (key > tau) atomicOr(&sel_bits[q >> 5], 1u << (q & 31));
         else if (key == tau && ties) atomicOr(&eq_bits[q >> 5], 1u << (q & 31));
     }
@@ -653,12 +677,11 @@ __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
     uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
 #pragma unroll
     for (int u = 0; u < EPL; ++u) {
-        const uint2 pr = ent[u];
-        const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
+        const uint32_t q = ent[u].x;
         if (q >= (uint32_t)TK_CHUNK) continue;
         if (sel_bits[q >> 5] & (1u << (q & 31))) {
             const uint32_t pos = off0 + bitmap_rank(sel_bits, prefix, q);
-            if (pos < a.k && pos < off1) out[pos] = pr;
+            if (pos < a.k && pos < off1) out[pos] = make_uint2((uint32_t)(c0 + q), ent[u].y);
         }
     }
 }
@@ -736,7 +759,7 @@ struct TopkState {
 
 void topk_destroy(TopkState* st) {
     if (!st) return;
-    void* ptrs[] = {st->s.hist, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slots};
+    void* ptrs[] = {st->s.hist, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slot_val, st->s.slot_idx};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     delete st;
@@ -755,7 +778,8 @@ ds_status topk_create(const ds_config& cfg, uint64_t /*ld*/, TopkState** out, st
               hipMalloc(&s.eq_before, n * nc * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.out_off, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.cand_cnt, n * nc * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&s.slots, n * nc * TK_CAP * sizeof(uint2)) == hipSuccess;
+              hipMalloc(&s.slot_val, n * nc * TK_CAP * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.slot_idx, n * nc * TK_CAP * sizeof(uint16_t)) == hipSuccess;
     ok = ok && hipMemset(s.hist, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.out_off, 0, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.cand_cnt, 0, n * nc * sizeof(uint32_t)) == hipSuccess;

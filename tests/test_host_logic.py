@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_validate_accepts_the_five_benchmark_configs():
-    for w in wl.configs():
+    for w in wl.configs() + wl.extra_configs():
         cfg, _ = b.config_from_workload(w)
         st, msg = b.ds_validate_config(cfg)
         assert st == b.DS_OK, (w.name, msg)
@@ -44,6 +44,7 @@ def test_validate_accepts_the_five_benchmark_configs():
     (dict(block=8192), "power of two"), (dict(kind=wl.KIND_TOPK, k=0), "k must"),
     (dict(kind=wl.KIND_TOPK, k=10 ** 9), "k must"), (dict(gamma=float("nan")), "finite"),
     (dict(eta=float("inf")), "finite"), (dict(kind=9), "unknown compressor"), (dict(topo=7), "unknown topology"),
+    (dict(kind=wl.KIND_QUANT_L2NORM, bits=3, block=0), "bits"), (dict(kind=wl.KIND_QUANT_L2NORM, bits=8, block=0), "bits"),
 ])
 def test_validate_rejects(kw, needle):
     base = dict(n=8, N=4096, topo=wl.TOPO_RING, kind=wl.KIND_QUANT_MAXABS, gamma=0.1, eta=0.5, bits=4, block=512)
@@ -110,7 +111,8 @@ def test_torus_topology_matches_definition():
 
 
 def test_message_sizes():
-    for w in wl.configs() + [wl.configs()[1].scaled(1024 * 3 + 74), wl.configs()[2].scaled(40)]:
+    for w in wl.configs() + wl.extra_configs() + [wl.configs()[1].scaled(1024 * 3 + 74), wl.configs()[2].scaled(40),
+                                                  wl.extra_configs()[0].scaled(17), wl.extra_configs()[1].scaled(16)]:
         cfg, _ = b.config_from_workload(w)
         assert b.ds_message_bytes(cfg) == oracle.message_bytes(w.kind, w.n, w.N, w.bits, w.block, w.k)
     # the figures quoted for the benchmark: 260 B per 512 4-bit codes, 260 B per 1024 2-bit codes, 36 B per 256 signs
@@ -120,6 +122,11 @@ def test_message_sizes():
     assert b.ds_message_bytes(c) == 3 * 260
     c, _ = b.make_config(3, 256, wl.TOPO_RING, wl.KIND_SIGN_MEANABS, 0.1, 0.5, block=256)
     assert b.ds_message_bytes(c) == 3 * 36
+    # the experiments' compressor: one norm + N b-bit codes per worker (the paper's "4 bits: 7/8 saved" up to the norm)
+    c, _ = b.make_config(3, 1000, wl.TOPO_RING, wl.KIND_QUANT_L2NORM, 0.1, 0.5, bits=4)
+    assert b.ds_message_bytes(c) == 3 * (4 + 500)
+    c, _ = b.make_config(3, 17, wl.TOPO_RING, wl.KIND_QUANT_L2NORM, 0.1, 0.5, bits=2)
+    assert b.ds_message_bytes(c) == 3 * (4 + 8)
 
 
 def test_workload_generators_are_seeded_and_shaped():
