@@ -627,6 +627,34 @@ def test_block_configs_full_size_one_step(idx):
     assert nb == 0
 
 
+def test_l2norm_full_size_two_steps():
+    """The norm-rescaled compressor at the size bench.py --config 6 times (16 x 11.17 M, 2 bits): two steps in a
+    row, so the first step's tail goes through the second step's first pass; every output is compared."""
+    w = wl.extra_configs()[1]
+    x0, d0, g = _full_size_inputs(w, 6)
+    ds = b.DeepSqueeze.from_workload(w)
+    ds.ds_write_state(x0, d0, 3)
+    say("case", w.name, "gpu steps, plan", ds.ds_plan_name())
+    ds.ds_step(g)
+    m1 = ds.ds_read_messages()
+    ds.ds_step(g)
+    m2 = ds.ds_read_messages()
+    x, d = ds.ds_read_state()
+    ds.ds_destroy()
+    g_host = np.ascontiguousarray(g[:, :w.N].cpu().numpy())
+    del g
+    torch.cuda.empty_cache()
+    st = oracle_state(w, x=x0, delta=d0, t=3)
+    say("case", w.name, "oracle steps")
+    _, o1 = oracle.step(st, g_host, want_cv=False)
+    assert np.array_equal(m1, o1), f"step 1: {int((m1 != o1).sum())} message bytes differ"
+    _, o2 = oracle.step(st, g_host, want_cv=False)
+    assert np.array_equal(m2, o2), f"step 2: {int((m2 != o2).sum())} message bytes differ"
+    nb = assert_close("x", x, st.x) + assert_close("delta", d, st.delta)
+    say(w.name, "full size: state elements differing bitwise:", nb)
+    assert nb == 0
+
+
 def test_topk_config_full_size_sampled_rows():
     """Config 4 at full size.  The oracle needs about a minute for all 32 rows, so it is run on
     sampled rows: a worker and its two ring neighbours form a 3-row problem whose middle row has
