@@ -146,6 +146,13 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
  * graphs captured from ds_step, stay valid); any other W moves to a new allocation. */
 ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_col, const float* W_val);
 
+/* Replaces the step length gamma and the consensus step eta for the following steps (the paper's
+ * experiments decay the learning rate during a run, section "Convergence Efficiency"; Algorithm 1
+ * itself is stated for constants).  Both must be finite; eta > 1/2 is accepted with the note
+ * ds_init gives.  A deferred tail of the last step is applied first, with the old eta.  A HIP
+ * graph captured from ds_step keeps the values it was captured with.  Synchronises nothing. */
+ds_status ds_set_rates(ds_handle* h, float gamma, float eta);
+
 /* Copies the state to dense host arrays of n*N fp32 each (delta_host may be NULL).  Synchronises
  * with the stream of the last ds_step. */
 ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host);

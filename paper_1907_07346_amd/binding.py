@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
            "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
-           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics"]
+           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates"]
 
 
 class ds_comp(ctypes.Structure):
@@ -67,6 +67,7 @@ def lib() -> ctypes.CDLL:
         L.ds_step.argtypes, L.ds_step.restype = [vp, vp, u64, vp], i32
         L.ds_read_state.argtypes, L.ds_read_state.restype = [vp, vp, vp], i32
         L.ds_set_mixing.argtypes, L.ds_set_mixing.restype = [vp, vp, vp, vp], i32
+        L.ds_set_rates.argtypes, L.ds_set_rates.restype = [vp, ctypes.c_float, ctypes.c_float], i32
         L.ds_diagnostics.argtypes, L.ds_diagnostics.restype = [vp, ctypes.POINTER(ctypes.c_double)], i32
         L.ds_write_state.argtypes, L.ds_write_state.restype = [vp, vp, vp, u64], i32
         L.ds_read_messages.argtypes, L.ds_read_messages.restype = [vp, vp, u64, u64p], i32
@@ -180,6 +181,9 @@ class DeepSqueeze:
         co = np.ascontiguousarray(W_csr[1], dtype=np.int32)
         va = np.ascontiguousarray(W_csr[2], dtype=np.float32)
         self._check(lib().ds_set_mixing(self._h, rp.ctypes.data, co.ctypes.data, va.ctypes.data), "ds_set_mixing")
+
+    def ds_set_rates(self, gamma: float, eta: float):
+        self._check(lib().ds_set_rates(self._h, gamma, eta), "ds_set_rates")
 
     def ds_read_state(self, want_delta: bool = True):
         x = np.empty((self.n, self.N), np.float32)

@@ -1,4 +1,5 @@
 // C ABI of libdsq: handle life cycle, state transfer and the ds_step dispatcher.
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -365,6 +366,17 @@ ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_
     h->d_coef = reinterpret_cast<float*>(h->d_col + nnz);
     h->graph = g;
     h->cfg.topo = DS_TOPO_CSR;
+    return DS_OK;
+}
+
+ds_status ds_set_rates(ds_handle* h, float gamma, float eta) {
+    if (!h) return DS_EINVAL;
+    if (!std::isfinite(gamma) || !std::isfinite(eta)) return fail(h, DS_EINVAL, "gamma and eta must be finite");
+    // a deferred tail was computed for the old eta
+    if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
+    h->cfg.gamma = gamma;
+    h->cfg.eta = eta;
+    h->err = (eta > 0.5f) ? "warning: eta > 1/2, outside the range of the paper's Theorem 1 (W_eff may not be PSD)" : "";
     return DS_OK;
 }
 

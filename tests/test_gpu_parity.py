@@ -217,6 +217,29 @@ def test_general_graph_csr():
         lock_step(w, steps=2, W=W, csr=(rp, co, va.astype(np.float32)))
 
 
+def test_rates_change_between_steps():
+    # gamma decays during a run (the paper's experiments divide the learning rate by 5 every 60 epochs) and
+    # eta is retuned; top-k and the norm-rescaled codes carry a deferred tail that belongs to the old eta
+    for w in (small(wl.KIND_QUANT_MAXABS, 8, 512 * 3 + 9, bits=4, block=512),
+              small(wl.KIND_TOPK, 8, 12_345, k=77),
+              small(wl.KIND_QUANT_L2NORM, 8, 4096 + 77, bits=4)):
+        say("case", w.name)
+        ds = b.DeepSqueeze.from_workload(w)
+        st = oracle_state(w)
+        for t in range(6):
+            if t in (2, 4):
+                st.gamma, st.eta = st.gamma / 5, st.eta * 0.75
+                ds.ds_set_rates(st.gamma, st.eta)
+            g = wl.gradient(w, t)
+            ds.ds_step(upload(g))
+            _, msg = oracle.step(st, g, want_cv=False)
+            assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} step {t}: messages differ"
+        x, d = ds.ds_read_state()
+        assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+        assert b.lib().ds_set_rates(ds._h, float("nan"), 0.1) == b.DS_EINVAL
+        ds.ds_destroy()
+
+
 def _random_graph(n, extra, seed):
     r = np.random.default_rng(seed)
     A = np.zeros((n, n), bool)
