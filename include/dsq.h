@@ -206,7 +206,7 @@ const char* ds_last_error(const ds_handle* h);
 /* Measurement aid, not part of the method: a plain streaming copy of `bytes` (a multiple of 16,
  * both pointers 16-byte aligned, device memory) enqueued on hip_stream.  Benchmarks use it to
  * report the HBM bandwidth a trivial kernel reaches on the same GPU, and profiles use it to
- * calibrate the hardware traffic counters against a known byte count. */
+ * calibrate the hardware traffic counters against a known byte count.  DS_EINVAL for bytes >= 64 GiB. */
 ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream);
 
 /* Frees everything the handle owns (synchronises first).  NULL is a no-op. */

@@ -261,7 +261,7 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
          int kind, int bits, uint64_t block, uint64_t k,
          real gamma, real eta, uint64_t seed, uint64_t t,
          real* x, real* delta, const real* g,
-         real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes) {
+         real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes, uint64_t col0 = 0) {
     if (n < 1 || N < 1 || !rowptr || !col || !wval || !x || !delta || !g) return 1;
     if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && (block < 1 || (block & (block - 1)))) return 1;
     if ((kind == QUANT_MAXABS || kind == QUANT_L2NORM) && (bits < 1 || bits > 8 || 32 % bits)) return 1;
@@ -301,7 +301,7 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
             for (uint64_t j0 = 0; j0 < N; j0 += block) {
                 const uint64_t m = std::min<uint64_t>(block, N - j0);
                 if (kind == QUANT_MAXABS)
-                    compress_block_quant<real>(vi + j0, ci + j0, m, bits, seed, t, (uint32_t)i, j0, msg);
+                    compress_block_quant<real>(vi + j0, ci + j0, m, bits, seed, t, (uint32_t)i, col0 + j0, msg);
                 else
                     compress_block_sign<real>(vi + j0, ci + j0, m, block, msg);
             }
@@ -355,6 +355,19 @@ int dso_step_f32(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, c
                  float* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
     return step<float>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t,
                        x, delta, g, cv, msg, msg_cap, msg_bytes);
+}
+
+// The same step on a window of columns [col0, col0 + N) of a wider problem: only the addresses of
+// the random rounding words know about col0.  For the per-block operators (col0 a multiple of the
+// block size) and the identity the result equals the corresponding columns of the wide problem's.
+int dso_step_window_f32(int n, uint64_t N, uint64_t col0, const int32_t* rowptr, const int32_t* col, const float* wval,
+                        int kind, int bits, uint64_t block, float gamma, float eta,
+                        uint64_t seed, uint64_t t, float* x, float* delta, const float* g,
+                        uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
+    if (kind == TOPK || kind == QUANT_L2NORM) return 1;            // whole-vector operators have no windows
+    if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && block && col0 % block) return 1;
+    return step<float>(n, N, rowptr, col, wval, kind, bits, block, 0, gamma, eta, seed, t,
+                       x, delta, g, nullptr, msg, msg_cap, msg_bytes, col0);
 }
 
 int dso_step_f64(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const double* wval,

@@ -48,6 +48,9 @@ def _load():
         fn.restype = ctypes.c_int
         fn.argtypes = [i32, u64, vp, vp, vp, i32, i32, u64, u64, real, real, u64, u64,
                        vp, vp, vp, vp, vp, u64, ctypes.POINTER(u64)]
+    lib.dso_step_window_f32.restype = ctypes.c_int
+    lib.dso_step_window_f32.argtypes = [i32, u64, u64, vp, vp, vp, i32, i32, u64, ctypes.c_float, ctypes.c_float,
+                                        u64, u64, vp, vp, vp, vp, u64, ctypes.POINTER(u64)]
     lib.dso_philox4x32_10.restype = None
     lib.dso_philox4x32_10.argtypes = [vp, vp, vp]
     lib.dso_rounding_word.restype = u32
@@ -183,6 +186,29 @@ def diagnostics(st: OracleState) -> dict:
     mixed = eta * A @ D
     return {"consensus_sq": float(((X - X.mean(0)) ** 2).sum()), "delta_sq": float((D ** 2).sum()),
             "delta_mixed_sq": float((mixed ** 2).sum())}
+
+
+def step_window(st: OracleState, g: np.ndarray, col0: int):
+    """One fp32 step on the columns [col0, col0 + st.N) of a wider problem (per-block operators and identity
+    only; col0 a multiple of the block size).  `st` holds the window's x and delta.  Returns the window's message."""
+    lib = _load()
+    assert st.dtype == np.float32
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    assert g.shape == (st.n, st.N)
+    rowptr, col, val = st._csr
+    wval = np.ascontiguousarray(val, dtype=np.float32)
+    cap = message_bytes(st.kind, st.n, st.N, st.bits, st.block, st.k)
+    msg = np.zeros(cap, dtype=np.uint8)
+    used = ctypes.c_uint64(0)
+    rc = lib.dso_step_window_f32(st.n, st.N, col0, rowptr.ctypes.data, col.ctypes.data, wval.ctypes.data,
+                                 st.kind, st.bits, st.block, st.gamma, st.eta, st.seed, st.t,
+                                 st.x.ctypes.data, st.delta.ctypes.data, g.ctypes.data,
+                                 msg.ctypes.data, cap, ctypes.byref(used))
+    if rc != 0:
+        raise RuntimeError(f"oracle window step failed with code {rc}")
+    st.t += 1
+    assert used.value == cap
+    return msg
 
 
 def step(st: OracleState, g: np.ndarray, want_cv: bool = True, want_msg: bool = True):

@@ -138,15 +138,14 @@ uint64_t autotune(ds_handle* h, uint64_t base_ld, size_t state_bytes, size_t msg
     return ok ? best_skew : dsq::kPitchSkew;
 }
 
-// Diagnostics (off the hot path): one thread per column walks all rows; fp64 accumulation.
+// Diagnostics (off the hot path): a thread walks all rows of its columns (grid-stride); fp64 accumulation.
 __global__ void __launch_bounds__(256) diagnostics_kernel(const float* __restrict__ x, const float* __restrict__ delta, uint64_t ld,
                                                           uint64_t N, int n, const int32_t* __restrict__ rowptr,
                                                           const int32_t* __restrict__ col, const float* __restrict__ coef,
                                                           float eta, double* __restrict__ out) {
     __shared__ double part[3][4];
-    const uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     double cons = 0.0, dsq_ = 0.0, mixed = 0.0;
-    if (j < N) {
+    for (uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x; j < N; j += (uint64_t)gridDim.x * 256) {
         double sum = 0.0, sumsq = 0.0;
         for (int i = 0; i < n; ++i) {
             const double xv = x[(uint64_t)i * ld + j];
@@ -198,7 +197,7 @@ ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void
         return DS_EINVAL;
     const uint64_t n4 = bytes / 16;
     if (n4 == 0) return DS_OK;
-    if (n4 > (uint64_t)0x7FFFFFFF * 256) return DS_EINVAL;
+    if (n4 > 0xFFFFFF00ull) return DS_EINVAL;              // one work-item per 16 bytes, fewer than 2^32 of them
     const unsigned blocks = (unsigned)((n4 + 255) / 256);
     hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<f32x4*>(dst_dev), static_cast<const f32x4*>(src_dev), n4);
@@ -441,7 +440,8 @@ ds_status ds_diagnostics(ds_handle* h, double* out4) {
     DSQ_HIP(h, hipMalloc(&d_out, 3 * sizeof(double)));
     hipError_t e = hipMemset(d_out, 0, 3 * sizeof(double));
     if (e == hipSuccess) {
-        const unsigned blocks = (unsigned)((h->cfg.N + 255) / 256);
+        const uint64_t want = (h->cfg.N + 255) / 256;
+        const unsigned blocks = (unsigned)(want < (1u << 20) ? want : (1u << 20));
         hipLaunchKernelGGL(diagnostics_kernel, dim3(blocks), dim3(256), 0, nullptr, h->x, h->delta, h->ld, h->cfg.N, h->cfg.n,
                            h->d_rowptr, h->d_col, h->d_coef, h->cfg.eta, d_out);
         e = hipGetLastError();

@@ -440,9 +440,12 @@ template <int KIND, int BITS, int B, int SW, int NW, int RPW>
 __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int rpw_runtime) {
     using T = Tile<KIND, BITS, B, SW, NW>;
     extern __shared__ __align__(16) uint8_t lds[];
-    const uint64_t col0 = (uint64_t)blockIdx.x * T::TC;
+    // tiles are numbered along x first; the grid has a second row only when x alone would pass the
+    // 2^32 work-items a launch dimension can hold, and its last row may then have spare workgroups
+    const uint64_t tile = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const uint64_t col0 = tile * T::TC;
     if (col0 + T::TC <= a.N) T::template run<RPW, true>(a, rpw_runtime, col0, lds);
-    else                     T::template run<RPW, false>(a, rpw_runtime, col0, lds);
+    else if (col0 < a.N)     T::template run<RPW, false>(a, rpw_runtime, col0, lds);
     // Advance the step counter once per launch: the workgroup that finds all others finished does it.
     // Thread 0 is past the barrier that follows phase 1, so every wave of its workgroup has read t (the
     // value has been consumed, so the load has completed) before the workgroup counts itself finished.
@@ -452,12 +455,13 @@ __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int r
     // would write back the XCD's L2 once per workgroup; the end of the kernel publishes the new t.
     // All cells are zero again when the kernel ends.
     if (threadIdx.x == 0) {
-        const unsigned cell = blockIdx.x & 63u;
-        const unsigned long long members = (gridDim.x >> 6) + (cell < (gridDim.x & 63u) ? 1u : 0u);
+        const unsigned long long blocks = (unsigned long long)gridDim.x * gridDim.y;
+        const unsigned cell = (unsigned)(tile & 63u);
+        const unsigned long long members = (blocks >> 6) + (cell < (blocks & 63u) ? 1u : 0u);
         unsigned long long* cnt = a.t_ptr + 32ull * (1 + cell);
         if (__hip_atomic_fetch_add(cnt, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == members - 1ull) {
             __hip_atomic_store(cnt, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const unsigned long long cells = gridDim.x < 64u ? gridDim.x : 64u;
+            const unsigned long long cells = blocks < 64u ? blocks : 64u;
             unsigned long long* done = a.t_ptr + 1;
             if (__hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == cells - 1ull) {
                 __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -470,7 +474,11 @@ __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int r
 template <int KIND, int BITS, int B, int SW, int NW, int RPW>
 void launch_tile(const TileArgs& a, int rpw_runtime, hipStream_t stream) {
     using T = Tile<KIND, BITS, B, SW, NW>;
-    const unsigned tiles = (unsigned)((a.N + T::TC - 1) / T::TC);
+    const uint64_t tiles = (a.N + T::TC - 1) / T::TC;
+    // a launch dimension holds fewer than 2^32 work-items: very long vectors get a second grid row
+    const uint64_t max_x = 0xFFFFFFFFull / (NW * kWave);
+    const unsigned gx = (unsigned)(tiles < max_x ? tiles : max_x);
+    const unsigned gy = (unsigned)((tiles + gx - 1) / gx);
     const size_t lds = T::lds_bytes(a.n, a.nnz);
     auto kern = fused_tile_kernel<KIND, BITS, B, SW, NW, RPW>;
     static bool attr_set = false;
@@ -478,7 +486,7 @@ void launch_tile(const TileArgs& a, int rpw_runtime, hipStream_t stream) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(tiles), dim3(NW * kWave), lds, stream, a, rpw_runtime);
+    hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(NW * kWave), lds, stream, a, rpw_runtime);
 }
 
 template <int KIND, int BITS, int B, int SW, int NW, int RPW>

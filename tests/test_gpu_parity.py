@@ -678,6 +678,136 @@ def test_l2norm_full_size_two_steps():
     assert nb == 0
 
 
+class _DeviceArray:
+    """A borrowed device buffer for torch (no copy): __cuda_array_interface__ of a float32 / uint8 matrix."""
+
+    def __init__(self, ptr, shape, typestr):
+        self.__cuda_array_interface__ = {"shape": shape, "typestr": typestr, "data": (ptr, False), "version": 2,
+                                         "strides": None}
+
+
+def _device_view(ptr, shape, typestr="<f4"):
+    return torch.as_tensor(_DeviceArray(ptr, shape, typestr), device="cuda")
+
+
+def _long_gradient(n, N, scale, seed):
+    pitch = (N + 3) // 4 * 4
+    g = torch.zeros((n, pitch), dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    step = 1 << 28
+    for i in range(n):
+        for c in range(0, N, step):
+            e = min(N, c + step)
+            g[i, c:e] = torch.randn(e - c, generator=gen, device="cuda") * scale
+    torch.cuda.synchronize()
+    return g
+
+
+LONG_N = (1 << 31) + 4096 * 3 + 517          # columns beyond 2^31, byte offsets beyond 2^33, ragged in every tiling
+
+
+@pytest.mark.parametrize("kind,bits,block", [(wl.KIND_QUANT_MAXABS, 4, 512), (wl.KIND_SIGN_MEANABS, 0, 256)],
+                         ids=["quant4b512", "sign256"])
+def test_vectors_longer_than_2_31_columns_block_operators(kind, bits, block, monkeypatch):
+    """Three workers with 2^31 + 12,805 parameters each (77 GB of state and gradients): two steps on the GPU in
+    every launch shape (the widest ones need more than 2^32 work-items and a second grid row), then windows of
+    columns -- the start, the 2^31 crossing, the ragged end -- are compared with the oracle's windowed step
+    (the per-block operators are independent from block to block)."""
+    n, N = 3, LONG_N
+    w = wl.Config("long", n=n, N=N, topo=wl.TOPO_RING, kind=kind, gamma=0.1, eta=0.4, steps=2, grad="normal",
+                  grad_scale=0.5, bits=bits, block=block, seed=11)
+    say("case", "long vectors", kind, "generating")
+    g = _long_gradient(n, N, 0.5, 77)
+    tail0 = (N // 8192) * 8192
+    b_ = bits if kind == wl.KIND_QUANT_MAXABS else 1
+    blk_bytes = 4 + block * b_ // 8
+    windows = []
+    for c0, c1 in ((0, 8192), ((1 << 31) - 8192, (1 << 31) + 8192), (tail0 - 4096, N)):
+        st = oracle.OracleState(n=n, N=c1 - c0, W=oracle.ring_matrix(n), kind=kind, gamma=w.gamma, eta=w.eta,
+                                bits=bits, block=block, seed=w.seed)
+        gw = g[:, c0:c1].cpu().numpy()
+        oracle.step_window(st, gw, c0)
+        windows.append((c0, c1, st, oracle.step_window(st, gw, c0)))
+    monkeypatch.setenv("DSQ_PITCH_SKEW", "2560")            # no timing runs: every shape is pinned in turn
+    seen = []
+    for plan in range(12):
+        monkeypatch.setenv("DSQ_TILE_PLAN", str(plan))
+        ds = b.DeepSqueeze.from_workload(w)
+        name = ds.ds_plan_name()
+        if name in seen:                                    # index past the end: the default came back
+            ds.ds_destroy()
+            break
+        seen.append(name)
+        say("case", "long vectors", "plan", name)
+        ds.ds_step(g)
+        ds.ds_step(g)
+        torch.cuda.synchronize()
+        assert ds.ds_step_count() == 2
+        xp, dp, ld = ds.ds_state_ptrs()
+        mp, mbytes = ds.ds_message_ptr()
+        X, D = _device_view(xp, (n, ld)), _device_view(dp, (n, ld))
+        M = _device_view(mp, (n, mbytes // n), "|u1")
+        for c0, c1, st, msg in windows:
+            assert assert_close(f"{name} x[{c0}:{c1}]", X[:, c0:c1].cpu().numpy(), st.x) == 0
+            assert assert_close(f"{name} delta[{c0}:{c1}]", D[:, c0:c1].cpu().numpy(), st.delta) == 0
+            m0 = (c0 // block) * blk_bytes
+            got = M[:, m0:m0 + len(msg) // n].cpu().numpy()
+            assert np.array_equal(got.reshape(-1), msg), f"{name}: message window {c0}:{c1} differs"
+        # the padding behind column N-1 stays zero
+        assert float(X[:, N:].abs().max()) == 0.0 and float(D[:, N:].abs().max()) == 0.0
+        del X, D, M
+        ds.ds_destroy()
+    assert len(seen) >= 2, seen
+
+
+def test_vectors_longer_than_2_31_columns_topk():
+    """Top-k over 2^31 + 12,805 columns, k = 1 %: no oracle can be run piecewise on a whole-vector select, so the
+    result is checked through what defines it: k pairs with strictly ascending columns, the exact values of v,
+    nothing left behind that is larger than the smallest value sent, delta zero exactly on the sent set."""
+    n, N = 3, LONG_N
+    k = N // 100
+    gamma, eta = 0.1, 0.4
+    w = wl.Config("long", n=n, N=N, topo=wl.TOPO_RING, kind=wl.KIND_TOPK, gamma=gamma, eta=eta, steps=1,
+                  grad="normal", grad_scale=0.5, k=k, seed=11)
+    say("case", "long vectors top-k", "generating")
+    g = _long_gradient(n, N, 0.5, 78)
+    ds = b.DeepSqueeze.from_workload(w)
+    ds.ds_step(g)
+    torch.cuda.synchronize()
+    xp, dp, ld = ds.ds_state_ptrs()                            # applies the deferred tail
+    mp, mbytes = ds.ds_message_ptr()
+    torch.cuda.synchronize()
+    assert mbytes == n * k * 8
+    X, D = _device_view(xp, (n, ld)), _device_view(dp, (n, ld))
+    M = _device_view(mp, (n, k, 2), "<i4")
+    A = torch.tensor(oracle.ring_matrix(n).astype(np.float32) - np.eye(n, dtype=np.float32), device="cuda")
+    sent = []
+    for i in range(n):
+        idx = M[i, :, 0].to(torch.int64) & 0xFFFFFFFF
+        val = M[i, :, 1].contiguous().view(torch.float32)
+        assert bool((idx[1:] > idx[:-1]).all()) and int(idx[-1]) < N, "columns not strictly ascending"
+        v_at = g[i, idx] * (-gamma)                            # from x = delta = 0: v = -gamma g
+        assert bool((val == v_at).all()), "a sent value is not v at its column"
+        tau = float(val.abs().min())
+        assert float(D[i, :N].abs().max()) <= tau, "an unsent element is larger than the smallest sent one"
+        assert float(D[i, idx].abs().max()) == 0.0, "delta is not zero on the sent set"
+        assert int((D[i, :N] == 0).sum()) <= k + int((g[i, :N] == 0).sum())
+        sent.append((idx, val))
+    # line 9 on sampled columns around 0, 2^31 and the end: x = xh + eta * sum_j a_ij C[v_j]
+    for c0, c1 in ((0, 4096), ((1 << 31) - 4096, (1 << 31) + 4096), (N - 4096, N)):
+        C = torch.zeros((n, c1 - c0), device="cuda")
+        for i, (idx, val) in enumerate(sent):
+            m = (idx >= c0) & (idx < c1)
+            C[i, idx[m] - c0] = val[m]
+        xh = (g[:, c0:c1] * (-gamma)).double()
+        want = xh + float(np.float32(eta)) * (A.double() @ C.double())
+        got = X[:, c0:c1].double()
+        assert float((got - want).abs().max()) <= 1e-6 * float(want.abs().max()), "gossip update differs"
+    assert float(X[:, N:].abs().max()) == 0.0 and float(D[:, N:].abs().max()) == 0.0
+    ds.ds_destroy()
+
+
 def test_topk_config_full_size_sampled_rows():
     """Config 4 at full size.  The oracle needs about a minute for all 32 rows, so it is run on
     sampled rows: a worker and its two ring neighbours form a 3-row problem whose middle row has

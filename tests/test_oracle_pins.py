@@ -289,6 +289,28 @@ def test_hand_expanded_example_matches_rational_brute_force(golden_dir):
         np.testing.assert_allclose(np.array(D, dtype=float), rec["d"], atol=1e-15)
 
 
+def test_window_step_equals_the_columns_of_the_wide_step():
+    # the windowed entry point (used to check very long vectors piecewise) against the plain one
+    n, N, B = 5, 64 * 9 + 13, 64
+    W = oracle.ring_matrix(n)
+    r = np.random.default_rng(31)
+    x0, d0, g = (r.standard_normal((3, n, N)) * 0.3).astype(np.float32)
+    for comp in (dict(kind=KIND_QUANT_MAXABS, bits=4, block=B), dict(kind=KIND_SIGN_MEANABS, block=B),
+                 dict(kind=KIND_IDENTITY)):
+        wide = OracleState(n=n, N=N, W=W, gamma=0.1, eta=0.4, seed=7, t=5, x=x0.copy(), delta=d0.copy(), **comp)
+        oracle.step(wide, g, want_cv=False)
+        for c0, c1 in ((0, 3 * B), (4 * B, 7 * B), (8 * B, N)):
+            win = OracleState(n=n, N=c1 - c0, W=W, gamma=0.1, eta=0.4, seed=7, t=5,
+                              x=x0[:, c0:c1].copy(), delta=d0[:, c0:c1].copy(), **comp)
+            oracle.step_window(win, g[:, c0:c1], c0)
+            np.testing.assert_array_equal(win.x, wide.x[:, c0:c1])
+            np.testing.assert_array_equal(win.delta, wide.delta[:, c0:c1])
+    # a window that starts elsewhere draws other rounding words
+    a = OracleState(n=n, N=B, W=W, gamma=0.1, eta=0.4, seed=7, x=x0[:, :B].copy(), kind=KIND_QUANT_MAXABS, bits=2, block=B)
+    b_ = OracleState(n=n, N=B, W=W, gamma=0.1, eta=0.4, seed=7, x=x0[:, :B].copy(), kind=KIND_QUANT_MAXABS, bits=2, block=B)
+    assert not np.array_equal(oracle.step_window(a, g[:, :B], 0), oracle.step_window(b_, g[:, :B], B))
+
+
 # ----------------------------------------------------------------------------- the experiments' compressor
 
 def l2norm_state(v, bits, dtype=np.float32, n=1):
