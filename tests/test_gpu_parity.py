@@ -808,6 +808,61 @@ def test_vectors_longer_than_2_31_columns_topk():
     ds.ds_destroy()
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_vectors_longer_than_2_31_columns_l2norm(bits):
+    """The norm-rescaled codes over 2^31 + 12,805 columns (more than 1024 chunks per tree thread): checked through
+    the operator's defining properties, computed with torch in double on the device."""
+    n, N, L = 3, LONG_N, (1 << bits) - 1
+    gamma, eta = 0.1, 0.4
+    w = wl.Config("long", n=n, N=N, topo=wl.TOPO_RING, kind=wl.KIND_QUANT_L2NORM, gamma=gamma, eta=eta, steps=1,
+                  grad="normal", grad_scale=0.5, bits=bits, seed=11)
+    say("case", "long vectors l2norm", bits, "generating")
+    g = _long_gradient(n, N, 0.5, 79)
+    ds = b.DeepSqueeze.from_workload(w)
+    ds.ds_step(g)
+    xp, dp, ld = ds.ds_state_ptrs()                            # applies the deferred tail
+    mp, mbytes = ds.ds_message_ptr()
+    torch.cuda.synchronize()
+    row_bytes = 4 + 4 * ((N * bits + 31) // 32)
+    assert mbytes == n * row_bytes
+    X, D = _device_view(xp, (n, ld)), _device_view(dp, (n, ld))
+    M = _device_view(mp, (n, row_bytes), "|u1")
+    A = torch.tensor(oracle.ring_matrix(n).astype(np.float32) - np.eye(n, dtype=np.float32), device="cuda")
+    units = []
+    for i in range(n):
+        v = g[i, :N] * (-gamma)                                # from x = delta = 0: v = -gamma g, exactly
+        sent = float(M[i, :4].cpu().numpy().view(np.float32)[0])
+        exact = float(v.double().square().sum().sqrt())
+        assert abs(sent - exact) <= 6e-8 * exact, (sent, exact)             # the norm, rounded once to fp32
+        C = v - D[i, :N]                                       # delta = v - C[v]; exact where |C| ~ |v| ... checked below
+        unit = float(C.abs().min())
+        y = C.double() / unit
+        assert float((y - y.round()).abs().max()) < 1e-3 and float(y.abs().max()) <= L + 1e-3
+        yi = y.round().to(torch.int64)
+        assert bool((yi.abs() % 2 == 1).all())
+        # the receiver's scale: unit = nrm / ||y||, so the decoded vector has the norm that was sent
+        assert abs(unit - sent / float(yi.square().sum().double().sqrt())) <= 2e-7 * unit
+        # nearest level of the grid spanned by max|v|
+        s = float(v.abs().max())
+        target = v.double() * (L / s)
+        assert float((yi.double() - target).abs().max()) <= 1.0 + 1e-5
+        # the codes in the message are (y + L) / 2, packed little-endian, on windows at the start, across 2^31, at the end
+        for c0, c1 in ((0, 8192), ((1 << 31) - 8192, (1 << 31) + 8192), (N - 4101, N)):
+            c0 -= c0 % 4
+            per = 8 // bits
+            raw = M[i, 4 + c0 // per: 4 + (c1 + per - 1) // per].to(torch.int64)
+            codes = torch.stack([(raw >> (bits * e)) & L for e in range(per)], dim=1).reshape(-1)[:c1 - c0]
+            assert bool((codes == (yi[c0:c1] + L) // 2).all()), f"codes differ in window {c0}:{c1}"
+        units.append((yi, unit))
+        del C, y, target
+    for c0, c1 in ((0, 4096), ((1 << 31) - 4096, (1 << 31) + 4096), (N - 4096, N)):
+        C = torch.stack([yi[c0:c1].double() * float(np.float32(u)) for yi, u in units])
+        want = (g[:, c0:c1] * (-gamma)).double() + float(np.float32(eta)) * (A.double() @ C)
+        assert float((X[:, c0:c1].double() - want).abs().max()) <= 2e-6 * float(want.abs().max()), "gossip update differs"
+    assert float(X[:, N:].abs().max()) == 0.0 and float(D[:, N:].abs().max()) == 0.0
+    ds.ds_destroy()
+
+
 def test_topk_config_full_size_sampled_rows():
     """Config 4 at full size.  The oracle needs about a minute for all 32 rows, so it is run on
     sampled rows: a worker and its two ring neighbours form a 3-row problem whose middle row has
