@@ -59,7 +59,7 @@ def cpu_baseline(w, budget_s=12.0):
         oracle.step(st, gs[steps % 2], want_cv=False, want_msg=True)
         steps += 1
         el = time.perf_counter() - t0
-        if el > budget_s or steps >= 20:
+        if el > budget_s or steps >= 200:
             break
     return {"value": ws.n * ws.N * steps / el, "unit": "worker-param updates/s", "cores": 1, "kind": "oracle",
             "sample": f"first {Ns} of {w.N} columns, all {w.n} workers, {steps} steps in {el:.1f} s "

@@ -96,6 +96,7 @@ float time_plan(ds_handle* h, const dsq::TilePlan& plan, const float* g, hipEven
     for (int r = 0; r < 3; ++r) plan.launch(a, plan.rows_per_wave, nullptr);
     (void)hipEventRecord(e1, nullptr);
     float ms = 0.f;
+    if (hipGetLastError() != hipSuccess) return -1.f;          // a launch that was refused would look fast
     if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1.f;
     return ms;
 }
