@@ -156,6 +156,11 @@ SMALL = [
     small(wl.KIND_QUANT_L2NORM, 5, 4096, bits=4),
     small(wl.KIND_QUANT_L2NORM, 9, 9001, bits=2, topo=wl.TOPO_TORUS2D, torus=(3, 3)),
     small(wl.KIND_QUANT_L2NORM, 3, 4096 * 1030 + 3, bits=2),                       # > 1024 chunks: 2 tree leaves per thread
+    small(wl.KIND_QUANT_MAXABS, 3, 1, bits=4, block=256),                          # a single parameter per worker
+    small(wl.KIND_SIGN_MEANABS, 4, 1, block=512),
+    small(wl.KIND_IDENTITY, 3, 1),
+    small(wl.KIND_TOPK, 3, 1, k=1),
+    small(wl.KIND_QUANT_L2NORM, 3, 1, bits=4),
 ]
 
 
