@@ -19,7 +19,7 @@
 // its *compressed* value with coefficient W_ii - 1.
 //
 // The paper leaves C_omega generic (Assumption 1.6 only asks for a bounded
-// signal-to-noise factor).  The five operators implemented here, and the exact
+// signal-to-noise factor).  The six operators implemented here, and the exact
 // floating-point evaluation order used for `real = float`, are this
 // repository's readings; every one is stated next to the code that does it.
 //
@@ -75,7 +75,19 @@ uint32_t rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
     return out[j % 4];
 }
 
-enum Kind { IDENTITY = 0, QUANT_MAXABS = 1, SIGN_MEANABS = 2, TOPK = 3, QUANT_L2NORM = 4 };
+// The random word that decides whether element j of worker i is kept by the random sparsifier at
+// iteration t: the same addressing as the rounding words, in a stream of its own ('SPAR').
+const uint32_t kSparseTag = 0x53504152u;
+
+uint32_t keep_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
+    const uint32_t ctr[4] = {(uint32_t)(j / 4), i, (uint32_t)t, kSparseTag};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    philox4x32_10(ctr, key, out);
+    return out[j % 4];
+}
+
+enum Kind { IDENTITY = 0, QUANT_MAXABS = 1, SIGN_MEANABS = 2, TOPK = 3, QUANT_L2NORM = 4, RAND_SPARSE = 5 };
 
 template <typename real> real fma_(real a, real b, real c);
 template <> float  fma_<float>(float a, float b, float c)    { return std::fmaf(a, b, c); }
@@ -251,6 +263,45 @@ void compress_row_quant_l2norm(const real* v, real* cv, uint64_t N, int bits, Ms
 }
 
 // ---------------------------------------------------------------------------
+// C_omega, operator 5: random sparsification (named with GSpar, top-k and
+// random quantisation among the operators that satisfy Assumption 1.6): every
+// element is kept with the same probability p, independently, and the others
+// become +0.  Reading: no rescaling by 1/p -- the unbiased variant has
+// E|C[v] - v|^2 = (1/p - 1)|v|^2, outside Assumption 1.6 for p < 1/2, whereas
+// the plain mask gives exactly alpha^2 = 1 - p.  p is given through k, the
+// expected number of kept elements per worker: element j is kept iff the top
+// 24 bits of its random word are below T = floor(k 2^24 / N) (an integer test,
+// so every implementation takes the same decision); k = N keeps everything.
+// The receiver regenerates the mask from the shared seed, so only the kept
+// values travel.  Message per worker: [u32 count][count f32 values, ascending
+// index], zero-padded to a fixed capacity of `cap` values; a worker that keeps
+// more than `cap` values (8 standard deviations above k) is reported as an error.
+// ---------------------------------------------------------------------------
+uint64_t rand_sparse_capacity(uint64_t N, uint64_t k) {
+    uint64_t root = 0;
+    while (root * root < k) ++root;                       // ceil(sqrt(k))
+    const uint64_t cap = k + 8 * root + 64;
+    return cap < N ? cap : N;
+}
+
+template <typename real>
+bool compress_row_rand_sparse(const real* v, real* cv, uint64_t N, uint64_t k,
+                              uint64_t seed, uint64_t t, uint32_t i, Msg<real>& msg) {
+    const uint64_t T = (k << 24) / N;                     // k <= N < 2^32: no overflow
+    const uint64_t cap = rand_sparse_capacity(N, k);
+    std::vector<real> kept;
+    for (uint64_t j = 0; j < N; ++j) {
+        const bool keep = (uint64_t)(keep_word(seed, t, i, j) >> 8) < T;
+        cv[j] = keep ? v[j] : (real)0;
+        if (keep) kept.push_back(v[j]);
+    }
+    const bool overflow = kept.size() > cap;
+    msg.put_u32((uint32_t)(overflow ? cap : kept.size()));
+    for (uint64_t r = 0; r < cap; ++r) msg.put_f32(r < kept.size() ? kept[r] : (real)0);
+    return !overflow;
+}
+
+// ---------------------------------------------------------------------------
 // One iteration for all workers.  Dense n x N row-major arrays throughout.
 // W comes as CSR (rowptr, col, val) *including* the diagonal entry of every
 // row, columns ascending; the mixing coefficient of line 9 is
@@ -265,7 +316,8 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
     if (n < 1 || N < 1 || !rowptr || !col || !wval || !x || !delta || !g) return 1;
     if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && (block < 1 || (block & (block - 1)))) return 1;
     if ((kind == QUANT_MAXABS || kind == QUANT_L2NORM) && (bits < 1 || bits > 8 || 32 % bits)) return 1;
-    if (kind == TOPK && (k < 1 || k > N)) return 1;
+    if ((kind == TOPK || kind == RAND_SPARSE) && (k < 1 || k > N)) return 1;
+    if (kind == RAND_SPARSE && N > 0xFFFFFFFFull) return 1;
     for (int i = 0; i < n; ++i) {                         // CSR sanity: sorted, has diagonal
         bool diag = false;
         for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
@@ -281,6 +333,7 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
     real* cv = cv_out;
     if (!cv) { cv_local.resize(total); cv = cv_local.data(); }
     Msg<real> msg{msg_buf, msg_cap, 0, false};
+    bool sparse_overflow = false;
 
     // Algorithm 1, line 5: the error-compensated variable, evaluated as
     // (x - gamma g) + delta with the product fused into the first sum.
@@ -309,6 +362,8 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
             compress_row_topk<real>(vi, ci, N, k, msg);
         } else if (kind == QUANT_L2NORM) {
             compress_row_quant_l2norm<real>(vi, ci, N, bits, msg);
+        } else if (kind == RAND_SPARSE) {
+            if (!compress_row_rand_sparse<real>(vi, ci, N, k, seed, t, (uint32_t)i, msg)) sparse_overflow = true;
         } else {
             return 1;
         }
@@ -332,6 +387,7 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
         }
 
     if (msg_bytes) *msg_bytes = msg.used;
+    if (sparse_overflow) return 3;
     return msg.overflow ? 2 : 0;
 }
 
@@ -346,6 +402,10 @@ void dso_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) 
 uint32_t dso_rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
     return rounding_word(seed, t, i, j);
 }
+
+uint32_t dso_keep_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) { return keep_word(seed, t, i, j); }
+
+uint64_t dso_rand_sparse_capacity(uint64_t N, uint64_t k) { return rand_sparse_capacity(N, k); }
 
 double dso_sum_squares_tree_f32(const float* v, uint64_t N) { return sum_squares_tree<float>(v, N); }
 
@@ -364,7 +424,7 @@ int dso_step_window_f32(int n, uint64_t N, uint64_t col0, const int32_t* rowptr,
                         int kind, int bits, uint64_t block, float gamma, float eta,
                         uint64_t seed, uint64_t t, float* x, float* delta, const float* g,
                         uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
-    if (kind == TOPK || kind == QUANT_L2NORM) return 1;            // whole-vector operators have no windows
+    if (kind == TOPK || kind == QUANT_L2NORM || kind == RAND_SPARSE) return 1;   // whole-vector operators and messages have no windows
     if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && block && col0 % block) return 1;
     return step<float>(n, N, rowptr, col, wval, kind, bits, block, 0, gamma, eta, seed, t,
                        x, delta, g, nullptr, msg, msg_cap, msg_bytes, col0);

@@ -19,6 +19,7 @@ KIND_QUANT_MAXABS = 1  # stochastic b-bit block quantisation, max-abs scale
 KIND_SIGN_MEANABS = 2  # sign bit + block mean-abs scale
 KIND_TOPK = 3          # k largest magnitudes of the whole vector
 KIND_QUANT_L2NORM = 4  # b-bit codes over the whole vector + its Euclidean norm (the paper's experiments)
+KIND_RAND_SPARSE = 5   # every element kept with probability k/N, no rescaling
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ds_oracle.cpp")
@@ -55,6 +56,10 @@ def _load():
     lib.dso_philox4x32_10.argtypes = [vp, vp, vp]
     lib.dso_rounding_word.restype = u32
     lib.dso_rounding_word.argtypes = [u64, u64, u32, u64]
+    lib.dso_keep_word.restype = u32
+    lib.dso_keep_word.argtypes = [u64, u64, u32, u64]
+    lib.dso_rand_sparse_capacity.restype = u64
+    lib.dso_rand_sparse_capacity.argtypes = [u64, u64]
     lib.dso_sum_squares_tree_f32.restype = ctypes.c_double
     lib.dso_sum_squares_tree_f32.argtypes = [vp, u64]
     _lib = lib
@@ -75,6 +80,16 @@ def philox4x32_10(counter, key):
 def rounding_word(seed: int, t: int, i: int, j: int) -> int:
     """The 32-bit word that decides the stochastic rounding of element (i, j) at step t."""
     return int(_load().dso_rounding_word(seed, t, i, j))
+
+
+def keep_word(seed: int, t: int, i: int, j: int) -> int:
+    """The 32-bit word that decides whether the random sparsifier keeps element (i, j) at step t."""
+    return int(_load().dso_keep_word(seed, t, i, j))
+
+
+def rand_sparse_capacity(N: int, k: int) -> int:
+    """Values a worker's random-sparsification message has room for: min(N, k + 8 ceil(sqrt k) + 64)."""
+    return int(_load().dso_rand_sparse_capacity(N, k))
 
 
 def sum_squares_tree(v) -> float:
@@ -130,6 +145,8 @@ def message_bytes(kind: int, n: int, N: int, bits: int = 0, block: int = 0, k: i
         return n * k * 8
     if kind == KIND_QUANT_L2NORM:
         return n * (4 + 4 * ((N * bits + 31) // 32))
+    if kind == KIND_RAND_SPARSE:
+        return n * (4 + 4 * rand_sparse_capacity(N, k))
     b = bits if kind == KIND_QUANT_MAXABS else 1
     full, tail = divmod(N, block)
     per_row = full * (4 + 4 * ((block * b + 31) // 32))

@@ -17,7 +17,8 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, OracleState)
+from oracle import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE,
+                    OracleState)
 
 
 # ----------------------------------------------------------------------------- helpers
@@ -157,6 +158,7 @@ COMPRESSORS = [
     dict(kind=KIND_TOPK, k=5),
     dict(kind=KIND_QUANT_L2NORM, bits=2),
     dict(kind=KIND_QUANT_L2NORM, bits=4),
+    dict(kind=KIND_RAND_SPARSE, k=20),
 ]
 
 
@@ -436,6 +438,73 @@ def test_sum_of_squares_is_the_adjacent_pairs_tree_in_double():
     exact = math.fsum(float(t) * float(t) for t in v)
     assert abs(oracle.sum_squares_tree(v) - exact) <= 1e-13 * exact
     assert oracle.sum_squares_tree(np.zeros(0, np.float32)) == 0.0
+
+
+# ----------------------------------------------------------------------------- random sparsification
+
+def test_rand_sparse_mask_rule_message_and_residual():
+    n, N, k, seed = 4, 3001, 500, 9
+    r = np.random.default_rng(41)
+    v = r.standard_normal((n, N)).astype(np.float32)
+    st = OracleState(n=n, N=N, W=np.eye(n), kind=KIND_RAND_SPARSE, k=k, gamma=0.0, eta=0.5, seed=seed, t=6, x=v.copy())
+    cv, msg = oracle.step(st, np.zeros_like(v))
+    T = (k << 24) // N
+    SPAR = int.from_bytes(b"SPAR", "big")
+    cap = k + 8 * 23 + 64                                       # ceil(sqrt(500)) = 23
+    assert oracle.rand_sparse_capacity(N, k) == cap and len(msg) == n * (4 + 4 * cap)
+    for i in range(n):
+        # the mask: top 24 bits of the element's own Philox word (stream 'SPAR') below floor(k 2^24 / N)
+        words = [oracle.philox4x32_10([j // 4, i, 6, SPAR], [seed, 0])[j % 4] for j in range(N)]
+        keep = np.array([(int(wd) >> 8) < T for wd in words])
+        assert [oracle.keep_word(seed, 6, i, j) for j in (0, 1, 5, N - 1)] == [int(words[j]) for j in (0, 1, 5, N - 1)]
+        np.testing.assert_array_equal(cv[i], np.where(keep, v[i], np.float32(0)))
+        np.testing.assert_array_equal(st.delta[i], np.where(keep, np.float32(0), v[i]))
+        row = msg[i * (4 + 4 * cap):(i + 1) * (4 + 4 * cap)]
+        count = int(np.frombuffer(row[:4].tobytes(), np.uint32)[0])
+        vals = np.frombuffer(row[4:].tobytes(), np.float32)
+        assert count == keep.sum()
+        np.testing.assert_array_equal(vals[:count], v[i][keep])                 # ascending index
+        assert np.all(row[4 + 4 * count:] == 0)
+    # the keep stream is not the rounding stream
+    assert oracle.keep_word(seed, 6, 0, 0) != oracle.rounding_word(seed, 6, 0, 0)
+    assert oracle.rand_sparse_capacity(50, 40) == 50            # never more than N
+
+
+def test_rand_sparse_rate_independence_and_signal_to_noise():
+    # keep rate = floor(k 2^24 / N) / 2^24 within 5 sigma; masks of different workers and steps are unrelated;
+    # |C[v] - v|^2 / |v|^2 averages to 1 - p: the alpha^2 of Assumption 1.6
+    n, N, k = 3, 200_000, 20_000
+    p = ((k << 24) // N) / 2.0 ** 24
+    r = np.random.default_rng(42)
+    v = r.standard_normal((n, N)).astype(np.float64)
+    st = OracleState(n=n, N=N, W=np.eye(n), kind=KIND_RAND_SPARSE, k=k, gamma=0.0, eta=0.5, seed=1, dtype=np.float64, x=v.copy())
+    cv1, _ = oracle.step(st, np.zeros_like(v), want_msg=False)
+    st.x[:], st.delta[:] = v, 0.0
+    cv2, _ = oracle.step(st, np.zeros_like(v), want_msg=False)                  # next step: another mask
+    m1, m2 = cv1 != 0, cv2 != 0
+    sd = np.sqrt(p * (1 - p) / N)
+    assert np.all(np.abs(m1.mean(1) - p) < 5 * sd) and np.all(np.abs(m2.mean(1) - p) < 5 * sd)
+    for a, b_ in ((m1[0], m1[1]), (m1[0], m2[0]), (m1[2], m2[1])):
+        both = (a & b_).mean()
+        assert abs(both - p * p) < 5 * np.sqrt(p * p * (1 - p * p) / N)
+    # neighbours inside a Philox group of four are unrelated too
+    assert abs((m1[0][0::4] & m1[0][1::4]).mean() - p * p) < 5 * np.sqrt(p * p / (N / 4))
+    alpha2 = ((cv1 - v) ** 2).sum(1) / (v ** 2).sum(1)
+    assert np.all(np.abs(alpha2 - (1 - p)) < 0.01)
+    np.testing.assert_array_equal(cv1[m1], v[m1])                               # kept values are exact, no rescaling
+
+
+def test_rand_sparse_keeping_everything_is_dpsgd():
+    n, N = 5, 257
+    W = oracle.ring_matrix(n)
+    r = np.random.default_rng(43)
+    gs = r.standard_normal((4, n, N)).astype(np.float32)
+    a = OracleState(n=n, N=N, W=W, kind=KIND_RAND_SPARSE, k=N, gamma=0.1, eta=0.4)
+    b_ = OracleState(n=n, N=N, W=W, kind=KIND_IDENTITY, gamma=0.1, eta=0.4)
+    for g in gs:
+        oracle.step(a, g, want_msg=False), oracle.step(b_, g, want_msg=False)
+    np.testing.assert_array_equal(a.x, b_.x)
+    assert np.all(a.delta == 0)
 
 
 # ----------------------------------------------------------------------------- P7: quantiser
