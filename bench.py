@@ -34,6 +34,8 @@ def algorithmic_bytes_per_param(w) -> float:
         msg = 8 * w.k / w.N
     elif w.kind == wl.KIND_QUANT_L2NORM:
         msg = w.bits / 8
+    elif w.kind == wl.KIND_RAND_SPARSE:
+        msg = 4 * w.k / w.N
     else:
         msg = 4.0
     return 20.0 + msg
@@ -71,7 +73,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configuration list (5, 6: the extra workloads)")
+    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configuration list (5, 6, 7: the extra workloads)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--hip-graph", action="store_true",
                     help="capture the K timed steps into one HIP graph and time its replay (for launch-bound sizes)")
@@ -168,7 +170,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "N": w.N, "plan": ds.ds_plan_name(), "gradient_buffers": nbuf, "launch": "hip-graph" if graph is not None else "eager",
-                   "compressor": {1: f"quant{w.bits}b/B{w.block}", 2: f"sign/B{w.block}", 3: f"top-{w.k}", 0: "identity", 4: f"l2norm{w.bits}b"}[w.kind]},
+                   "compressor": {1: f"quant{w.bits}b/B{w.block}", 2: f"sign/B{w.block}", 3: f"top-{w.k}", 0: "identity", 4: f"l2norm{w.bits}b", 5: f"rand-{w.k}"}[w.kind]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_param": beta, "device_ms_per_step": dev_ms / K, "plain_copy_GBps": copy_gbs,

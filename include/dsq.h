@@ -54,7 +54,7 @@ typedef enum {
     DS_COMP_SIGN_MEANABS = 2, /* sign bit per element, scale = mean |v| of the block            */
     DS_COMP_TOPK = 3,         /* the k largest |v| of each worker's whole vector, ties to the   */
                               /* lower index; message = k (u32 index, f32 value) pairs          */
-    DS_COMP_QUANT_L2NORM = 4  /* the compression of the paper's experiments (section             */
+    DS_COMP_QUANT_L2NORM = 4, /* the compression of the paper's experiments (section             */
                               /* "Experimental Setup", paragraph "Compression"): a `bits`-bit     */
                               /* code per element of the worker's whole vector plus ONE number,   */
                               /* its Euclidean norm, to which the receiver rescales what it       */
@@ -62,6 +62,12 @@ typedef enum {
                               /* level (ties to the even code); code q stands for y = 2q - L,     */
                               /* C[v] = y * (norm / ||y||_2).  Message per worker:                */
                               /* [f32 norm][ceil(N*bits/32) u32 words]; bits in {2, 4}            */
+    DS_COMP_RAND_SPARSE = 5   /* random sparsification (named next to top-k under Assumption 1.6): */
+                              /* every element is kept independently with probability k/N (floor   */
+                              /* to a multiple of 2^-24) and not rescaled; the mask comes from the  */
+                              /* shared seed, so the message carries values only:                  */
+                              /* [u32 count][count f32, ascending column], zero-padded to          */
+                              /* min(N, k + 8 ceil(sqrt k) + 64) values per worker                  */
 } ds_comp_kind;
 
 typedef struct {
@@ -69,7 +75,8 @@ typedef struct {
     int32_t  bits;    /* QUANT_MAXABS, QUANT_L2NORM: 2 or 4; otherwise ignored                  */
     int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 256 <= block <= 2048          */
     int32_t  reserved;
-    uint64_t k;       /* TOPK: 1 <= k <= N; otherwise ignored                                   */
+    uint64_t k;       /* TOPK: 1 <= k <= N; RAND_SPARSE: expected kept elements per worker,     */
+                      /* 1 <= k <= N; otherwise ignored                                         */
 } ds_comp;
 
 typedef struct {

@@ -28,6 +28,9 @@ struct ds_handle {
     std::vector<dsq::TilePlan> tile_candidates;
     dsq::TopkState* topk = nullptr;
     dsq::L2State* l2q = nullptr;
+    uint32_t* d_keep = nullptr;          // random sparsifier, one allocation: n x nsweeps offsets inside groups,
+                                         // n x ngroups group offsets, n previous counts, one overflow flag
+    uint64_t nsweeps = 0, ngroups = 0;
     std::string err;
     std::string plan_name;
 };
@@ -58,6 +61,7 @@ void release(ds_handle* h) {
     if (h->msg) (void)hipFree(h->msg);
     if (h->d_rowptr) (void)hipFree(h->d_rowptr);   // d_col and d_coef point into the same allocation
     if (h->d_t) (void)hipFree(h->d_t);
+    if (h->d_keep) (void)hipFree(h->d_keep);
     delete h;
 }
 
@@ -78,6 +82,14 @@ dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     a.n = h->cfg.n; a.nnz = (int)h->graph.col.size();
     a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
     a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32); a.t_ptr = h->d_t;
+    if (h->cfg.comp.kind == DS_COMP_RAND_SPARSE) {
+        a.keep_off = h->d_keep;
+        a.keep_group_off = h->d_keep + (size_t)h->cfg.n * h->nsweeps;
+        a.nsweeps = h->nsweeps;
+        a.ngroups = h->ngroups;
+        a.keep_thr = (uint32_t)((h->cfg.comp.k << 24) / h->cfg.N);        // floor(k 2^24 / N) <= 2^24
+        a.msg_cap = (uint32_t)((h->msg_row_bytes - 4) / 4);
+    }
     return a;
 }
 
@@ -264,6 +276,16 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
               hipMemcpy(h->d_coef, h->graph.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice) == hipSuccess &&
               hipDeviceSynchronize() == hipSuccess;
     if (!ok) { std::fprintf(stderr, "ds_init: device initialisation failed\n"); return bail(DS_EHIP); }
+    if (cfg->comp.kind == DS_COMP_RAND_SPARSE) {
+        h->nsweeps = (cfg->N + dsq::kSweep - 1) / dsq::kSweep;
+        h->ngroups = (h->nsweeps + 15) / 16;
+        const size_t words = (size_t)cfg->n * (h->nsweeps + h->ngroups) + (size_t)cfg->n + 1;
+        if (hipMalloc(&h->d_keep, words * sizeof(uint32_t)) != hipSuccess || hipMemset(h->d_keep, 0, words * sizeof(uint32_t)) != hipSuccess ||
+            hipDeviceSynchronize() != hipSuccess) {
+            std::fprintf(stderr, "ds_init: allocating the random sparsifier's offsets failed\n");
+            return bail(DS_ENOMEM);
+        }
+    }
 
     // working row pitch: DSQ_PITCH_SKEW=<floats, multiple of 4, <= 12288> pins it; otherwise large tile-kernel
     // problems are timed per candidate, everything else takes the default
@@ -321,6 +343,11 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
         if (st != DS_OK) return fail(h, st, "launching the norm-rescaled step failed");
     } else {
         const dsq::TileArgs a = tile_args(h, g_dev, g_ld);
+        if (h->cfg.comp.kind == DS_COMP_RAND_SPARSE) {
+            uint32_t* groups = h->d_keep + (size_t)h->cfg.n * h->nsweeps;
+            uint32_t* prev = groups + (size_t)h->cfg.n * h->ngroups;
+            dsq::launch_keep_offsets(a, h->d_keep, groups, prev, prev + h->cfg.n, stream);
+        }
         h->tile.launch(a, h->tile.rows_per_wave, stream);
     }
     DSQ_HIP(h, hipGetLastError());
@@ -413,6 +440,11 @@ ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t*
     if (!host_buf || cap < total) return fail(h, DS_EINVAL, "message buffer too small");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     DSQ_HIP(h, hipMemcpy(host_buf, h->msg, total, hipMemcpyDeviceToHost));
+    if (h->d_keep) {
+        uint32_t overflow = 0;
+        DSQ_HIP(h, hipMemcpy(&overflow, h->d_keep + (size_t)h->cfg.n * (h->nsweeps + h->ngroups) + h->cfg.n, sizeof(overflow), hipMemcpyDeviceToHost));
+        if (overflow) return fail(h, DS_ESTATE, "a worker kept more values than its message has room for (x and delta are unaffected)");
+    }
     return DS_OK;
 }
 

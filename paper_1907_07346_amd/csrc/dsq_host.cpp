@@ -75,6 +75,9 @@ ds_status validate_config(const ds_config* cfg, std::string& err, std::string* w
         case DS_COMP_QUANT_L2NORM:
             if (c.bits != 2 && c.bits != 4) { err = "bits must be 2 or 4"; return DS_EINVAL; }
             break;
+        case DS_COMP_RAND_SPARSE:
+            if (c.k < 1 || c.k > cfg->N) { err = "k (expected number of kept elements) must be in [1, N]"; return DS_EINVAL; }
+            break;
         default: err = "unknown compressor"; return DS_EINVAL;
     }
     if (warn && cfg->eta > 0.5f) *warn = "warning: eta > 1/2, outside the range of the paper's Theorem 1 (W_eff may not be PSD)";
@@ -125,12 +128,20 @@ ds_status build_graph(const ds_config* cfg, Graph& g, std::string& err) {
     return DS_OK;
 }
 
+uint64_t rand_sparse_capacity(uint64_t N, uint64_t k) {
+    uint64_t root = 0;
+    while (root * root < k) ++root;                       // ceil(sqrt(k)), k < 2^32
+    const uint64_t cap = k + 8 * root + 64;               // 8 standard deviations of the kept count and some
+    return cap < N ? cap : N;
+}
+
 uint64_t message_row_bytes(const ds_config* cfg) {
     const ds_comp& c = cfg->comp;
     switch (c.kind) {
         case DS_COMP_IDENTITY: return cfg->N * 4;
         case DS_COMP_TOPK: return c.k * 8;
         case DS_COMP_QUANT_L2NORM: return 4 + 4 * ((cfg->N * (uint64_t)c.bits + 31) / 32);
+        case DS_COMP_RAND_SPARSE: return 4 + 4 * rand_sparse_capacity(cfg->N, c.k);
         case DS_COMP_QUANT_MAXABS:
         case DS_COMP_SIGN_MEANABS: {
             const uint64_t b = (c.kind == DS_COMP_QUANT_MAXABS) ? (uint64_t)c.bits : 1;

@@ -47,6 +47,12 @@ struct TileArgs {
     int n, nnz;                // workers; stored entries of W - I
     float gamma, eta;
     uint32_t seed_lo, seed_hi;
+    // random sparsifier only:
+    const uint32_t* keep_off;          // n x nsweeps: kept values before each 256-column sweep inside its group of 16
+    const uint32_t* keep_group_off;    // n x ngroups: values the row's message holds before each group
+    uint64_t nsweeps, ngroups;         // ceil(N / 256), ceil(nsweeps / 16)
+    uint32_t keep_thr;                 // an element is kept iff the top 24 bits of its random word are below this
+    uint32_t msg_cap;                  // values a row's message has room for
     unsigned long long* t_ptr;         // kStepCells 64-bit cells in device memory.  [0]: the step counter t, read by
                                        // the kernel and advanced by its last workgroup to finish, so that a captured
                                        // HIP graph of ds_step keeps moving along the random stream on replay.
@@ -63,6 +69,15 @@ struct TilePlan {
     int rows_per_wave = 0;     // rows each wave owns (held in registers when the variant says so)
     int sweeps = 0;            // 256-column sweeps per tile
 };
+
+// Random sparsifier: counts the kept elements of every 256-column sweep of this step (from the random words
+// alone) and turns them into message offsets: local_off (n x nsweeps, = TileArgs::keep_off of the tile launch
+// that follows) inside groups of 16 sweeps, group_tot (n x ngroups, = TileArgs::keep_group_off) across the
+// groups.  Writes the per-row count into the message header (prev_count, n words, remembers it so that stale
+// values behind a shorter message are cleared) and raises *overflow if a row keeps more than msg_cap values.
+void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group_tot, uint32_t* prev_count, uint32_t* overflow,
+                         hipStream_t stream);
+uint64_t rand_sparse_capacity(uint64_t N, uint64_t k);
 
 // Lists the variants that fit (n, compressor), best guess first; returns false with `err` set if none does.
 bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plans, std::string& err);

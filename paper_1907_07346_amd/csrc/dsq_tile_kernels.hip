@@ -42,6 +42,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 constexpr uint32_t kQuantStreamTag = 0x51554E54u;   // 4th counter word of the rounding stream
+constexpr uint32_t kSparseStreamTag = 0x53504152u;  // ... and of the stream that draws the random sparsifier's mask
 
 // 16-byte streaming accesses.  x, g and delta are touched exactly once per step, so they are
 // marked non-temporal: on gfx950 that keeps the streams from displacing each other in L2 / MALL.
@@ -99,6 +100,7 @@ template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 4> { using lane_t = uint16_t
 template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 2> { using lane_t = uint8_t;  static constexpr int row_bytes_per_sweep = 64; };
 template <> struct CodeTraits<DS_COMP_SIGN_MEANABS, 1> { using lane_t = uint32_t; static constexpr int row_bytes_per_sweep = 32; };
 template <> struct CodeTraits<DS_COMP_IDENTITY, 32>    { using lane_t = float4;   static constexpr int row_bytes_per_sweep = 1024; };
+template <> struct CodeTraits<DS_COMP_RAND_SPARSE, 32> { using lane_t = float4;   static constexpr int row_bytes_per_sweep = 1024; };
 
 __device__ __forceinline__ float comp(const float4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
 __device__ __forceinline__ void set_comp(float4& v, int c, float f) { if (c == 0) v.x = f; else if (c == 1) v.y = f; else if (c == 2) v.z = f; else v.w = f; }
@@ -248,6 +250,49 @@ struct Tile {
                         reinterpret_cast<uint32_t*>(lds_row)[s * 8 + (lane >> 3)] = word;
                         const uint32_t widx = (uint32_t)(s - b * SPB) * 8u + (uint32_t)(lane >> 3);
                         if (FULL || widx < nwords) reinterpret_cast<uint32_t*>(msg_blk + 4)[widx] = word;
+                    }
+                }
+            } else if constexpr (KIND == DS_COMP_RAND_SPARSE) {
+                // C[v] = v on a random mask (kept iff the top 24 bits of the element's Philox word are below
+                // the threshold), +0 elsewhere; the message is the kept values in column order, written at
+                // the sweep's offset (counted beforehand from the same words) plus the rank inside the sweep.
+                const uint32_t t_lo = (uint32_t)*a.t_ptr;
+                float* vals = reinterpret_cast<float*>(msg_row + 4);
+#pragma unroll
+                for (int s = b * SPB; s < (b + 1) * SPB; ++s) {
+                    const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                    uint32_t rnd[4];
+                    philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, t_lo, kSparseStreamTag, a.seed_lo, a.seed_hi, rnd);
+                    uint32_t keep = 0;
+                    float4 cv, dnew;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float vc = comp(v[s], c);
+                        const bool k = ((rnd[c] >> 8) < a.keep_thr) && (FULL || j + c < a.N);
+                        keep |= (k ? 1u : 0u) << c;
+                        const float cc = k ? vc : 0.f;
+                        set_comp(cv, c, cc);
+                        set_comp(dnew, c, vc - cc);                  // line 6: delta = v - C[v]
+                    }
+                    st4(dout + s * kSweep, dnew);
+                    reinterpret_cast<float4*>(lds_row)[s * kWave + lane] = cv;
+                    const uint32_t mine = __popc(keep);
+                    uint32_t inc = mine;                             // inclusive prefix over the lanes
+#pragma unroll
+                    for (int o = 1; o < kWave; o <<= 1) {
+                        const uint32_t up = __shfl_up(inc, o);
+                        if (lane >= o) inc += up;
+                    }
+                    const uint64_t sweep = (col0 >> 8) + (uint64_t)s;
+                    if (FULL || sweep < a.nsweeps) {
+                        uint32_t pos = a.keep_group_off[(uint64_t)i * a.ngroups + (sweep >> 4)] +
+                                       a.keep_off[(uint64_t)i * a.nsweeps + sweep] + inc - mine;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c)
+                            if (keep & (1u << c)) {
+                                if (pos < a.msg_cap) vals[pos] = comp(v[s], c);
+                                ++pos;
+                            }
                     }
                 }
             } else {   // DS_COMP_IDENTITY: C[v] = v, delta = 0, the message is v itself
@@ -436,6 +481,92 @@ struct Tile {
     }
 };
 
+// ---- random sparsifier: where each 256-column sweep's kept values go in the message -----------
+// The mask depends on (seed, step, worker, column) only, so the number of kept elements of every
+// sweep can be counted before the state is touched: one wave per sweep, no memory reads.  A
+// workgroup covers a group of 16 sweeps and leaves each sweep's offset inside the group plus the
+// group's total; the per-row scan then runs over the groups only.
+constexpr int kKeepGroup = 16;                                        // sweeps per group (= waves per workgroup)
+__global__ void __launch_bounds__(kKeepGroup* kWave) keep_count_kernel(TileArgs a, uint32_t* __restrict__ local_off,
+                                                                       uint32_t* __restrict__ group_tot) {
+    __shared__ uint32_t cnts[kKeepGroup];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const uint64_t sweep = (uint64_t)blockIdx.x * kKeepGroup + wave;
+    const int i = blockIdx.y;
+    const uint32_t t_lo = (uint32_t)*a.t_ptr;
+    uint32_t cnt = 0;
+    if (sweep < a.nsweeps) {                                          // uniform per wave
+        const uint64_t j = sweep * kSweep + 4 * lane;
+        uint32_t rnd[4];
+        philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, t_lo, kSparseStreamTag, a.seed_lo, a.seed_hi, rnd);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) cnt += (((rnd[c] >> 8) < a.keep_thr) && (j + c < a.N)) ? 1u : 0u;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) cnt += __shfl_xor(cnt, o);
+    }
+    if (lane == 0) cnts[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x < kKeepGroup) {
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kKeepGroup; ++w) {
+            if (w < (int)threadIdx.x) before += cnts[w];
+            total += cnts[w];
+        }
+        const uint64_t sw = (uint64_t)blockIdx.x * kKeepGroup + threadIdx.x;
+        if (sw < a.nsweeps) local_off[(uint64_t)i * a.nsweeps + sw] = before;
+        if (threadIdx.x == 0) group_tot[(uint64_t)i * a.ngroups + blockIdx.x] = total;
+    }
+}
+
+// Per row: group totals -> exclusive group offsets (in place), the count into the message header,
+// stale values behind a shorter message cleared, and a flag if a row keeps more values than its
+// message has room for.
+__global__ void __launch_bounds__(1024) keep_scan_kernel(TileArgs a, uint32_t* __restrict__ group_tot, uint32_t* __restrict__ prev_count,
+                                                         uint32_t* __restrict__ overflow) {
+    __shared__ uint32_t wave_tot[16];
+    const int i = blockIdx.x;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    uint32_t* row = group_tot + (uint64_t)i * a.ngroups;
+    // each thread owns a run of consecutive groups
+    const uint64_t per = (a.ngroups + 1023) / 1024;
+    const uint64_t lo = (threadIdx.x * per < a.ngroups) ? threadIdx.x * per : a.ngroups;
+    const uint64_t hi = (lo + per < a.ngroups) ? lo + per : a.ngroups;
+    uint32_t sum = 0;
+    for (uint64_t q = lo; q < hi; ++q) sum += row[q];
+    uint32_t inc = sum;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const uint32_t up = __shfl_up(inc, o);
+        if (lane >= o) inc += up;
+    }
+    if (lane == kWave - 1) wave_tot[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        if (w < wave) base += wave_tot[w];
+        total += wave_tot[w];
+    }
+    uint32_t run = base + inc - sum;
+    for (uint64_t q = lo; q < hi; ++q) {
+        const uint32_t c = row[q];
+        row[q] = run;
+        run += c;
+    }
+    // the message is zero behind its last value: clear what the previous step wrote beyond this step's count
+    const uint32_t now = total < a.msg_cap ? total : a.msg_cap;
+    const uint32_t before = prev_count[i];
+    float* vals = reinterpret_cast<float*>(a.msg + (uint64_t)i * a.msg_row_bytes + 4);
+    for (uint32_t q = now + threadIdx.x; q < before; q += 1024) vals[q] = 0.f;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        *reinterpret_cast<uint32_t*>(a.msg + (uint64_t)i * a.msg_row_bytes) = now;
+        prev_count[i] = now;
+        if (total > a.msg_cap) atomicOr(overflow, 1u);
+    }
+}
+
 template <int KIND, int BITS, int B, int SW, int NW, int RPW>
 __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int rpw_runtime) {
     using T = Tile<KIND, BITS, B, SW, NW>;
@@ -572,6 +703,14 @@ bool pick_for_kind(int block, int n, int nnz, std::vector<TilePlan>& plan, std::
 
 }  // namespace
 
+static_assert(kKeepGroup == 16, "the tile kernel finds a sweep's group with a shift by 4");
+
+void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group_tot, uint32_t* prev_count, uint32_t* overflow,
+                         hipStream_t stream) {
+    hipLaunchKernelGGL(keep_count_kernel, dim3((unsigned)a.ngroups, a.n), dim3(kKeepGroup * kWave), 0, stream, a, local_off, group_tot);
+    hipLaunchKernelGGL(keep_scan_kernel, dim3(a.n), dim3(1024), 0, stream, a, group_tot, prev_count, overflow);
+}
+
 bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plan, std::string& err) {
     switch (cfg.comp.kind) {
         case DS_COMP_QUANT_MAXABS:
@@ -583,6 +722,8 @@ bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& pla
             return pick_for_kind<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, cfg.n, nnz, plan, err);
         case DS_COMP_IDENTITY:
             return pick_for_block<DS_COMP_IDENTITY, 32, 512>(cfg.n, nnz, plan, err);
+        case DS_COMP_RAND_SPARSE:
+            return pick_for_block<DS_COMP_RAND_SPARSE, 32, 512>(cfg.n, nnz, plan, err);
         default:
             err = "no tile kernel for this compressor";
             return false;

@@ -17,7 +17,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM = 0, 1, 2, 3, 4
+KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE = 0, 1, 2, 3, 4, 5
 TOPO_RING, TOPO_TORUS2D, TOPO_CSR = 0, 1, 2
 
 _TAG_CENTRE, _TAG_NOISE = 0x43454E54, 0x47524144   # 'CENT', 'GRAD'
@@ -43,7 +43,7 @@ class Config:
 
     def scaled(self, N: int, steps: Optional[int] = None) -> "Config":
         """Same workload at another vector length (k follows as 1 % of N for top-k)."""
-        k = max(1, N // 100) if self.kind == KIND_TOPK else 0
+        k = max(1, N // 100) if self.kind in (KIND_TOPK, KIND_RAND_SPARSE) else 0
         return replace(self, N=N, k=k, steps=self.steps if steps is None else steps,
                        name=f"{self.name}@N={N}")
 
@@ -72,12 +72,15 @@ def configs():
 def extra_configs():
     """Workloads beyond the benchmark's list: the compression of the paper's own experiments (b-bit codes plus
     the tensor's Euclidean norm) on its setting (8 workers on a ring, a vector of ResNet-20 size, 4 bits) and
-    at a bandwidth-bound size (the shape of configuration 1, 2 bits)."""
+    at a bandwidth-bound size (the shape of configuration 1, 2 bits); random sparsification at the shape of
+    configuration 4 (1 % kept)."""
     return [
         Config("x5_ring8_l2norm4b_resnet20", n=8, N=272_474, topo=TOPO_RING, kind=KIND_QUANT_L2NORM, bits=4,
                gamma=0.1, eta=0.5, steps=100, grad="normal", grad_scale=0.01),
         Config("x6_ring16_l2norm2b_resnet18", n=16, N=11_173_962, topo=TOPO_RING, kind=KIND_QUANT_L2NORM, bits=2,
                gamma=0.05, eta=0.3, steps=100, grad="normal", grad_scale=0.01),
+        Config("x7_ring32_rand1pct_resnet50", n=32, N=25_557_032, topo=TOPO_RING, kind=KIND_RAND_SPARSE,
+               k=25_557_032 // 100, gamma=0.05, eta=0.2, steps=50, grad="normal", grad_scale=1e-3),
     ]
 
 

@@ -161,6 +161,12 @@ SMALL = [
     small(wl.KIND_IDENTITY, 3, 1),
     small(wl.KIND_TOPK, 3, 1, k=1),
     small(wl.KIND_QUANT_L2NORM, 3, 1, bits=4),
+    small(wl.KIND_RAND_SPARSE, 8, 512 * 9 + 37, k=460),                            # random sparsifier, 10 % kept
+    small(wl.KIND_RAND_SPARSE, 16, 30_011, k=300),
+    small(wl.KIND_RAND_SPARSE, 3, 7, k=3),
+    small(wl.KIND_RAND_SPARSE, 5, 1000, k=1000),                                    # keeps everything
+    small(wl.KIND_RAND_SPARSE, 40, 256 * 5 + 1, k=64, topo=wl.TOPO_TORUS2D, torus=(5, 8)),
+    small(wl.KIND_RAND_SPARSE, 3, 1, k=1),
 ]
 
 
@@ -216,7 +222,8 @@ def test_general_graph_csr():
     for w in (small(wl.KIND_QUANT_MAXABS, n, 512 * 3 + 9, bits=4, block=512),
               small(wl.KIND_SIGN_MEANABS, n, 777, block=256),
               small(wl.KIND_TOPK, n, 12_345, k=77),
-              small(wl.KIND_QUANT_L2NORM, n, 4096 + 77, bits=2)):
+              small(wl.KIND_QUANT_L2NORM, n, 4096 + 77, bits=2),
+              small(wl.KIND_RAND_SPARSE, n, 5000, k=400)):
         say("case", w.name)
         # the oracle rounds W to fp32 exactly like the CSR handed to the library
         lock_step(w, steps=2, W=W, csr=(rp, co, va.astype(np.float32)))
@@ -477,7 +484,8 @@ def test_two_handles_interleaved():
 
 @pytest.mark.parametrize("w", [small(wl.KIND_QUANT_MAXABS, 8, 512 * 9 + 37, bits=4, block=512),
                                small(wl.KIND_TOPK, 8, 30_011, k=300),
-                               small(wl.KIND_QUANT_L2NORM, 8, 4096 * 5 + 11, bits=2)], ids=lambda w: w.name)
+                               small(wl.KIND_QUANT_L2NORM, 8, 4096 * 5 + 11, bits=2),
+                               small(wl.KIND_RAND_SPARSE, 8, 20_000, k=1500)], ids=lambda w: w.name)
 def test_hip_graph_replay(w):
     """ds_step captured once into a HIP graph and replayed: the step counter lives on the device, so every
     replay draws fresh rounding words; each replay is checked against the oracle, with eager work between."""
@@ -599,12 +607,13 @@ def test_config0_full_size_100_steps():
     say(w.name, "free run: state elements differing bitwise:", nbits)
 
 
-SCALED = [(1, 1024 * 37 + 74, None), (2, 256 * 201 + 40, None), (3, 512 * 21 + 100, None), (4, 150_001, None)]
+SCALED = [(1, 1024 * 37 + 74, None), (2, 256 * 201 + 40, None), (3, 512 * 21 + 100, None), (4, 150_001, None),
+          (5, 272_474, 20), (6, 4096 * 9 + 77, 30), (7, 150_001, None)]
 
 
 @pytest.mark.parametrize("idx,N,steps", SCALED, ids=lambda v: str(v))
 def test_configs_scaled_full_length_free_run(idx, N, steps):
-    w = wl.configs()[idx].scaled(N)
+    w = (wl.configs() + wl.extra_configs())[idx].scaled(N)
     say("case", w.name, "free run", w.steps, "steps")
     nbits = free_run(w, w.steps if steps is None else steps)
     say(w.name, "free run: state elements differing bitwise:", nbits)
