@@ -29,7 +29,8 @@ struct ds_handle {
     dsq::TopkState* topk = nullptr;
     dsq::L2State* l2q = nullptr;
     uint32_t* d_keep = nullptr;          // random sparsifier, one allocation: n x nsweeps offsets inside groups,
-                                         // n x ngroups group offsets, n previous counts, one overflow flag
+                                         // n x ngroups group offsets, n previous counts, one overflow flag,
+                                         // 2 x n x nsweeps raw counts (steps of even / odd t)
     uint64_t nsweeps = 0, ngroups = 0;
     std::string err;
     std::string plan_name;
@@ -85,6 +86,7 @@ dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     if (h->cfg.comp.kind == DS_COMP_RAND_SPARSE) {
         a.keep_off = h->d_keep;
         a.keep_group_off = h->d_keep + (size_t)h->cfg.n * h->nsweeps;
+        a.keep_raw = h->d_keep + (size_t)h->cfg.n * (h->nsweeps + h->ngroups) + h->cfg.n + 1;
         a.nsweeps = h->nsweeps;
         a.ngroups = h->ngroups;
         a.keep_thr = (uint32_t)((h->cfg.comp.k << 24) / h->cfg.N);        // floor(k 2^24 / N) <= 2^24
@@ -146,6 +148,7 @@ uint64_t autotune(ds_handle* h, uint64_t base_ld, size_t state_bytes, size_t msg
     (void)hipMemset(h->delta, 0, state_bytes);
     (void)hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4);
     (void)hipMemset(h->d_t, 0, dsq::kStepCells * sizeof(unsigned long long));   // the timed launches advanced t
+    (void)hipMemset(h->d_t + 2, 0xFF, sizeof(unsigned long long));              // ... and no keep counts are valid
     (void)hipDeviceSynchronize();
     if (!ok) h->tile = h->tile_candidates.front();
     return ok ? best_skew : dsq::kPitchSkew;
@@ -271,6 +274,7 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     bool ok = hipMemset(h->x, 0, state_bytes) == hipSuccess && hipMemset(h->delta, 0, state_bytes) == hipSuccess &&
               hipMemset(h->msg, 0, msg_bytes ? msg_bytes : 4) == hipSuccess &&
               hipMemset(h->d_t, 0, dsq::kStepCells * sizeof(unsigned long long)) == hipSuccess &&
+              hipMemset(h->d_t + 2, 0xFF, sizeof(unsigned long long)) == hipSuccess &&   // tag of the keep counts: none yet
               hipMemcpy(h->d_rowptr, h->graph.rowptr.data(), (cfg->n + 1) * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->d_col, h->graph.col.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->d_coef, h->graph.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice) == hipSuccess &&
@@ -279,7 +283,7 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     if (cfg->comp.kind == DS_COMP_RAND_SPARSE) {
         h->nsweeps = (cfg->N + dsq::kSweep - 1) / dsq::kSweep;
         h->ngroups = (h->nsweeps + 15) / 16;
-        const size_t words = (size_t)cfg->n * (h->nsweeps + h->ngroups) + (size_t)cfg->n + 1;
+        const size_t words = (size_t)cfg->n * (3 * h->nsweeps + h->ngroups) + (size_t)cfg->n + 1;
         if (hipMalloc(&h->d_keep, words * sizeof(uint32_t)) != hipSuccess || hipMemset(h->d_keep, 0, words * sizeof(uint32_t)) != hipSuccess ||
             hipDeviceSynchronize() != hipSuccess) {
             std::fprintf(stderr, "ds_init: allocating the random sparsifier's offsets failed\n");

@@ -50,14 +50,16 @@ struct TileArgs {
     // random sparsifier only:
     const uint32_t* keep_off;          // n x nsweeps: kept values before each 256-column sweep inside its group of 16
     const uint32_t* keep_group_off;    // n x ngroups: values the row's message holds before each group
+    uint32_t* keep_raw;                // 2 x n x nsweeps: kept elements per sweep; half [t & 1] belongs to step t
     uint64_t nsweeps, ngroups;         // ceil(N / 256), ceil(nsweeps / 16)
     uint32_t keep_thr;                 // an element is kept iff the top 24 bits of its random word are below this
     uint32_t msg_cap;                  // values a row's message has room for
     unsigned long long* t_ptr;         // kStepCells 64-bit cells in device memory.  [0]: the step counter t, read by
                                        // the kernel and advanced by its last workgroup to finish, so that a captured
                                        // HIP graph of ds_step keeps moving along the random stream on replay.
-                                       // [1]: finished first-level cells; [32 (1+c)], c < 64: finished workgroups
-                                       // with blockIdx % 64 == c.  All but [0] are zero between launches.
+                                       // [1]: finished first-level cells; [2]: random sparsifier: the step whose keep
+                                       // counts are in keep_raw (~0 if none); [32 (1+c)], c < 64: finished workgroups
+                                       // with blockIdx % 64 == c.  All but [0] and [2] are zero between launches.
 };
 
 // A compiled variant of the fused tile kernel, chosen once at init.
@@ -70,11 +72,12 @@ struct TilePlan {
     int sweeps = 0;            // 256-column sweeps per tile
 };
 
-// Random sparsifier: counts the kept elements of every 256-column sweep of this step (from the random words
-// alone) and turns them into message offsets: local_off (n x nsweeps, = TileArgs::keep_off of the tile launch
-// that follows) inside groups of 16 sweeps, group_tot (n x ngroups, = TileArgs::keep_group_off) across the
-// groups.  Writes the per-row count into the message header (prev_count, n words, remembers it so that stale
-// values behind a shorter message are cleared) and raises *overflow if a row keeps more than msg_cap values.
+// Random sparsifier: makes sure the kept-element counts of this step's 256-column sweeps are in keep_raw (the tile
+// kernel of the previous step normally left them there; otherwise they are recounted from the random words) and
+// turns them into message offsets: local_off (n x nsweeps, = TileArgs::keep_off of the tile launch that follows)
+// inside groups of 16 sweeps, group_tot (n x ngroups, = TileArgs::keep_group_off) across the groups.  Writes
+// the per-row count into the message header (prev_count, n words, remembers it so that stale values behind a
+// shorter message are cleared) and raises *overflow if a row keeps more than msg_cap values.
 void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group_tot, uint32_t* prev_count, uint32_t* overflow,
                          hipStream_t stream);
 uint64_t rand_sparse_capacity(uint64_t N, uint64_t k);

@@ -284,6 +284,17 @@ struct Tile {
                         if (lane >= o) inc += up;
                     }
                     const uint64_t sweep = (col0 >> 8) + (uint64_t)s;
+                    // While the streams are in flight: how many elements of this sweep step t+1 will keep (its
+                    // message offsets are needed before its tile kernel starts; counted here, the integer work
+                    // hides behind the memory traffic instead of taking a pass of its own).
+                    philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, t_lo + 1u, kSparseStreamTag, a.seed_lo, a.seed_hi, rnd);
+                    uint32_t next = 0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) next += (((rnd[c] >> 8) < a.keep_thr) && (FULL || j + c < a.N)) ? 1u : 0u;
+#pragma unroll
+                    for (int o = 1; o < kWave; o <<= 1) next += __shfl_xor(next, o);
+                    if (lane == 0 && (FULL || sweep < a.nsweeps))
+                        a.keep_raw[(uint64_t)((t_lo + 1u) & 1u) * a.n * a.nsweeps + (uint64_t)i * a.nsweeps + sweep] = next;
                     if (FULL || sweep < a.nsweeps) {
                         uint32_t pos = a.keep_group_off[(uint64_t)i * a.ngroups + (sweep >> 4)] +
                                        a.keep_off[(uint64_t)i * a.nsweeps + sweep] + inc - mine;
@@ -483,40 +494,46 @@ struct Tile {
 
 // ---- random sparsifier: where each 256-column sweep's kept values go in the message -----------
 // The mask depends on (seed, step, worker, column) only, so the number of kept elements of every
-// sweep can be counted before the state is touched: one wave per sweep, no memory reads.  A
-// workgroup covers a group of 16 sweeps and leaves each sweep's offset inside the group plus the
-// group's total; the per-row scan then runs over the groups only.
-constexpr int kKeepGroup = 16;                                        // sweeps per group (= waves per workgroup)
-__global__ void __launch_bounds__(kKeepGroup* kWave) keep_count_kernel(TileArgs a, uint32_t* __restrict__ local_off,
-                                                                       uint32_t* __restrict__ group_tot) {
-    __shared__ uint32_t cnts[kKeepGroup];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const uint64_t sweep = (uint64_t)blockIdx.x * kKeepGroup + wave;
+// sweep is known before the state is touched.  Normally the tile kernel of step t-1 has left the
+// counts of step t in keep_raw[t & 1] (and t in the tag cell t_ptr[2]); this kernel recounts them
+// when that is not so (first step, or the step counter was set from outside): one wave per sweep,
+// no memory reads.
+constexpr int kKeepGroup = 16;                                        // sweeps per offset group
+__global__ void __launch_bounds__(256) keep_count_if_stale_kernel(TileArgs a) {
+    const unsigned long long t = a.t_ptr[0];
+    if (a.t_ptr[2] == t) return;                                      // uniform: the counts are there
+    const int lane = threadIdx.x & (kWave - 1);
     const int i = blockIdx.y;
-    const uint32_t t_lo = (uint32_t)*a.t_ptr;
-    uint32_t cnt = 0;
-    if (sweep < a.nsweeps) {                                          // uniform per wave
+    uint32_t* raw = a.keep_raw + (uint64_t)(t & 1ull) * a.n * a.nsweeps + (uint64_t)i * a.nsweeps;
+    for (uint64_t sweep = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6); sweep < a.nsweeps; sweep += (uint64_t)gridDim.x * 4) {
         const uint64_t j = sweep * kSweep + 4 * lane;
         uint32_t rnd[4];
-        philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, t_lo, kSparseStreamTag, a.seed_lo, a.seed_hi, rnd);
+        philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, (uint32_t)t, kSparseStreamTag, a.seed_lo, a.seed_hi, rnd);
+        uint32_t cnt = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) cnt += (((rnd[c] >> 8) < a.keep_thr) && (j + c < a.N)) ? 1u : 0u;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) cnt += __shfl_xor(cnt, o);
+        if (lane == 0) raw[sweep] = cnt;
     }
-    if (lane == 0) cnts[wave] = cnt;
-    __syncthreads();
-    if (threadIdx.x < kKeepGroup) {
-        uint32_t before = 0, total = 0;
+}
+
+// Counts of step t -> each sweep's offset inside its group of 16 sweeps, and the groups' totals.
+__global__ void __launch_bounds__(256) keep_local_scan_kernel(TileArgs a, uint32_t* __restrict__ local_off, uint32_t* __restrict__ group_tot) {
+    const unsigned long long t = a.t_ptr[0];
+    const int i = blockIdx.y;
+    const uint64_t sweep = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint32_t* raw = a.keep_raw + (uint64_t)(t & 1ull) * a.n * a.nsweeps + (uint64_t)i * a.nsweeps;
+    const uint32_t cnt = (sweep < a.nsweeps) ? raw[sweep] : 0u;
+    uint32_t inc = cnt;
+    const int sub = threadIdx.x & (kKeepGroup - 1);
 #pragma unroll
-        for (int w = 0; w < kKeepGroup; ++w) {
-            if (w < (int)threadIdx.x) before += cnts[w];
-            total += cnts[w];
-        }
-        const uint64_t sw = (uint64_t)blockIdx.x * kKeepGroup + threadIdx.x;
-        if (sw < a.nsweeps) local_off[(uint64_t)i * a.nsweeps + sw] = before;
-        if (threadIdx.x == 0) group_tot[(uint64_t)i * a.ngroups + blockIdx.x] = total;
+    for (int o = 1; o < kKeepGroup; o <<= 1) {
+        const uint32_t up = __shfl_up(inc, o, kKeepGroup);
+        if (sub >= o) inc += up;
     }
+    if (sweep < a.nsweeps) local_off[(uint64_t)i * a.nsweeps + sweep] = inc - cnt;
+    if (sub == kKeepGroup - 1 && (sweep >> 4) < a.ngroups) group_tot[(uint64_t)i * a.ngroups + (sweep >> 4)] = inc;
 }
 
 // Per row: group totals -> exclusive group offsets (in place), the count into the message header,
@@ -596,7 +613,9 @@ __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int r
             unsigned long long* done = a.t_ptr + 1;
             if (__hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == cells - 1ull) {
                 __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_fetch_add(a.t_ptr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned long long t = __hip_atomic_fetch_add(a.t_ptr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // random sparsifier: this launch has left the keep counts of step t+1 behind
+                if constexpr (KIND == DS_COMP_RAND_SPARSE) __hip_atomic_store(a.t_ptr + 2, t + 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
@@ -707,7 +726,9 @@ static_assert(kKeepGroup == 16, "the tile kernel finds a sweep's group with a sh
 
 void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group_tot, uint32_t* prev_count, uint32_t* overflow,
                          hipStream_t stream) {
-    hipLaunchKernelGGL(keep_count_kernel, dim3((unsigned)a.ngroups, a.n), dim3(kKeepGroup * kWave), 0, stream, a, local_off, group_tot);
+    const uint64_t want = (a.nsweeps + 3) / 4;
+    hipLaunchKernelGGL(keep_count_if_stale_kernel, dim3((unsigned)(want < 512 ? want : 512), a.n), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(keep_local_scan_kernel, dim3((unsigned)((a.nsweeps + 255) / 256), a.n), dim3(256), 0, stream, a, local_off, group_tot);
     hipLaunchKernelGGL(keep_scan_kernel, dim3(a.n), dim3(1024), 0, stream, a, group_tot, prev_count, overflow);
 }
 

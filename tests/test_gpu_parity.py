@@ -579,6 +579,27 @@ def test_l2norm_worked_example_and_zero_rows_on_gpu(golden_dir):
     ds.ds_destroy()
 
 
+def test_rand_sparse_step_counter_set_from_outside():
+    # the tile kernel of step t leaves the keep counts of step t+1 behind; when the step counter is then set to
+    # something else, the counts are stale and must be recounted (and are reused if the counter comes back)
+    w = small(wl.KIND_RAND_SPARSE, 8, 256 * 40 + 3, k=900)
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w)
+    for t_next in (None, None, 41, None, 7, 8, None):
+        if t_next is not None:
+            x, d = ds.ds_read_state()
+            ds.ds_write_state(x, d, t_next)
+            st.t = t_next
+        g = wl.gradient(w, st.t)
+        ds.ds_step(upload(g))
+        _, msg = oracle.step(st, g, want_cv=False)
+        assert np.array_equal(ds.ds_read_messages(), msg), f"messages differ at t = {st.t - 1}"
+        assert ds.ds_step_count() == st.t
+    x, d = ds.ds_read_state()
+    assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+    ds.ds_destroy()
+
+
 def test_step_on_a_side_stream_and_determinism():
     w = small(wl.KIND_TOPK, 8, 50_000, k=500)
     outs = []
