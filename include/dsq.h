@@ -73,7 +73,7 @@ typedef enum {
 typedef struct {
     int32_t  kind;    /* ds_comp_kind */
     int32_t  bits;    /* QUANT_MAXABS, QUANT_L2NORM: 2 or 4; otherwise ignored                  */
-    int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 256 <= block <= 2048          */
+    int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 64 <= block <= 2048           */
     int32_t  reserved;
     uint64_t k;       /* TOPK: 1 <= k <= N; RAND_SPARSE: expected kept elements per worker,     */
                       /* 1 <= k <= N; otherwise ignored                                         */

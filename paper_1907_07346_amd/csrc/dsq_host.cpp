@@ -66,7 +66,7 @@ ds_status validate_config(const ds_config* cfg, std::string& err, std::string* w
             [[fallthrough]];
         case DS_COMP_SIGN_MEANABS:
             if (c.block < kMinBlock || c.block > kMaxBlock || !is_pow2((uint64_t)c.block)) {
-                err = "block must be a power of two between 256 and 2048"; return DS_EINVAL;
+                err = "block must be a power of two between 64 and 2048"; return DS_EINVAL;
             }
             break;
         case DS_COMP_TOPK:

@@ -18,7 +18,7 @@ constexpr uint64_t kPitchAlign = 4096;    // x / delta row pitch: N rounded up t
 constexpr uint64_t kPitchSkew = 2560;     // ... plus 10 KB, so that rows do not sit a power of two apart: with all rows
                                           // of a column tile in flight at once, HBM channel hashing made a 16 MiB pitch
                                           // 12 % slower than this one on MI355X (measured, 64 rows x 4 Mi columns)
-constexpr int kMinBlock = 256, kMaxBlock = 2048;
+constexpr int kMinBlock = 64, kMaxBlock = 2048;
 constexpr size_t kStepCells = 32 * 65;    // 64-bit cells behind the step counter (see TileArgs::t_ptr)
 
 // Host-side description of W - I in CSR form (diagonal always present, columns ascending).

@@ -95,6 +95,22 @@ __device__ __forceinline__ float wave_sum_tree(float v) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// Blocks narrower than a sweep (64 or 128 columns = 16 or 32 lanes): butterfly inside the group of lanes that
+// holds the block; every lane of the group ends with the result.  For the sum this is again the balanced
+// adjacent-pairs tree (the two partners of a level add the same two numbers).
+template <int G>
+__device__ __forceinline__ float group_max(float v) {
+#pragma unroll
+    for (int o = 1; o < G; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+template <int G>
+__device__ __forceinline__ float group_sum_tree(float v) {
+#pragma unroll
+    for (int o = 1; o < G; o <<= 1) v = v + __shfl_xor(v, o);
+    return v;
+}
+
 template <int KIND, int BITS> struct CodeTraits;
 template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 4> { using lane_t = uint16_t; static constexpr int row_bytes_per_sweep = 128; };
 template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 2> { using lane_t = uint8_t;  static constexpr int row_bytes_per_sweep = 64; };
@@ -108,17 +124,103 @@ __device__ __forceinline__ void set_comp(float4& v, int c, float f) { if (c == 0
 template <int KIND, int BITS, int B, int SW, int NW>
 struct Tile {
     static constexpr int TC = SW * kSweep;                 // columns per tile
-    static constexpr int SPB = B / kSweep;                 // sweeps per scale block
-    static constexpr int BPT = SW / SPB;                   // scale blocks per tile
+    static constexpr bool SUB = B < kSweep;                // several scale blocks share one sweep
+    static constexpr int BPS = SUB ? kSweep / B : 1;       // scale blocks per sweep (SUB)
+    static constexpr int G = SUB ? B / 4 : kWave;          // lanes that hold one block of a sweep
+    static constexpr int SPB = SUB ? 1 : B / kSweep;       // sweeps per scale block
+    static constexpr int BPT = SUB ? SW * BPS : SW / SPB;  // scale blocks per tile
     static constexpr int L = BITS < 31 ? (1 << (BITS & 15)) - 1 : 0;   // top quantisation level
     using CT = CodeTraits<KIND, BITS>;
     static constexpr int ROW_CODE_BYTES = SW * CT::row_bytes_per_sweep;
     static constexpr int MSG_BLOCK_BYTES = 4 + B * (BITS & 15) / 8;   // [scale][codes] of a full block
-    static_assert(B % kSweep == 0 && SW % SPB == 0, "tile must hold whole blocks");
+    static_assert((SUB ? kSweep % B == 0 : B % kSweep == 0) && SW % SPB == 0, "tile must hold whole blocks");
 
     // LDS: [codes of all rows][decode units of all rows][rowptr n+1][col nnz][coef nnz]
     static __host__ __device__ constexpr size_t lds_bytes(int n, int nnz) {
         return (size_t)n * ROW_CODE_BYTES + (size_t)n * BPT * sizeof(float) + (size_t)(n + 1 + 2 * nnz) * 4;
+    }
+
+    // ---- lines 6-7 for blocks of 64 or 128 columns: G = B/4 lanes hold one block of a sweep --------
+    template <bool FULL>
+    static __device__ __forceinline__ void compress_sub_blocks(const TileArgs& a, int i, uint64_t col0, int lane, const float4 (&v)[SW],
+                                                               uint8_t* msg_row, uint8_t* lds_row, float* lds_units, float* dout) {
+        const int grp = lane / G, in_blk = lane % G;                  // block of the sweep, lane-slot inside the block
+        [[maybe_unused]] uint32_t t_lo = 0;
+        if constexpr (KIND == DS_COMP_QUANT_MAXABS) t_lo = (uint32_t)*a.t_ptr;
+#pragma unroll
+        for (int s = 0; s < SW; ++s) {
+            const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+            const uint64_t bcol0 = col0 + (uint64_t)s * kSweep + (uint64_t)grp * B;
+            const bool block_live = FULL || (bcol0 < a.N);
+            const uint64_t m = FULL ? (uint64_t)B : (block_live ? (a.N - bcol0 < (uint64_t)B ? a.N - bcol0 : (uint64_t)B) : 0);
+            const uint32_t nwords = (uint32_t)((m * BITS + 31) / 32);
+            uint8_t* msg_blk = msg_row + (bcol0 / B) * MSG_BLOCK_BYTES;
+            if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
+                const float mx = fmaxf(fmaxf(fabsf(v[s].x), fabsf(v[s].y)), fmaxf(fabsf(v[s].z), fabsf(v[s].w)));
+                const float scale = group_max<G>(mx);
+                const float hl = 0.5f * (float)L;
+                const float unit = scale / (float)L;
+                const float inv = (scale > 0.f) ? hl / scale : 0.f;
+                if (in_blk == 0) {
+                    lds_units[i * BPT + s * BPS + grp] = unit;
+                    if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
+                }
+                uint32_t rnd[4];
+                philox4x32_10((uint32_t)(j >> 2), (uint32_t)i, t_lo, kQuantStreamTag, a.seed_lo, a.seed_hi, rnd);
+                uint32_t codes = 0;
+                float4 dnew;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float vc = comp(v[s], c);
+                    float tt = fmaf(vc, inv, hl);
+                    tt = (tt > 0.f) ? tt : 0.f;
+                    tt = (tt < (float)L) ? tt : (float)L;
+                    const float q0 = floorf(tt);
+                    const float fr = tt - q0;
+                    const float u = (float)(rnd[c] >> 8) * (1.0f / 16777216.0f);
+                    int q = (int)q0 + ((u < fr) ? 1 : 0);
+                    q = q < L ? q : L;
+                    if (!(scale > 0.f)) q = 0;
+                    float cv = (float)(2 * q - L) * unit;
+                    if (!FULL && !(j + c < a.N)) { q = 0; cv = 0.f; }
+                    codes |= (uint32_t)q << (BITS * c);
+                    set_comp(dnew, c, vc - cv);                      // line 6: delta = v - C[v]
+                }
+                st4(dout + s * kSweep, dnew);
+                using lane_t = typename CT::lane_t;
+                reinterpret_cast<lane_t*>(lds_row)[s * kWave + lane] = (lane_t)codes;
+                const uint32_t word = (uint32_t)in_blk * (uint32_t)sizeof(lane_t) / 4u;
+                if (FULL || word < nwords) reinterpret_cast<lane_t*>(msg_blk + 4)[in_blk] = (lane_t)codes;
+            } else if constexpr (KIND == DS_COMP_SIGN_MEANABS) {
+                const float sum = group_sum_tree<G>((fabsf(v[s].x) + fabsf(v[s].y)) + (fabsf(v[s].z) + fabsf(v[s].w)));
+                const float scale = block_live ? sum / (float)m : 0.f;
+                if (in_blk == 0) {
+                    lds_units[i * BPT + s * BPS + grp] = scale;
+                    if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
+                }
+                uint32_t nib = 0;
+                float4 dnew;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float vc = comp(v[s], c);
+                    uint32_t neg = __float_as_uint(vc) >> 31;
+                    float cv = neg ? -scale : scale;
+                    if (!FULL && !(j + c < a.N)) { neg = 0; cv = 0.f; }
+                    nib |= neg << c;
+                    set_comp(dnew, c, vc - cv);
+                }
+                st4(dout + s * kSweep, dnew);
+                uint32_t word = nib << (4 * (lane & 7));              // 8 lanes share one 32-bit word
+                word |= __shfl_xor(word, 1);
+                word |= __shfl_xor(word, 2);
+                word |= __shfl_xor(word, 4);
+                if ((lane & 7) == 0) {
+                    reinterpret_cast<uint32_t*>(lds_row)[s * 8 + (lane >> 3)] = word;
+                    const uint32_t widx = (uint32_t)in_blk >> 3;
+                    if (FULL || widx < nwords) reinterpret_cast<uint32_t*>(msg_blk + 4)[widx] = word;
+                }
+            }
+        }
     }
 
     // ---- phase 1 for one row: returns xh (x - gamma g) in registers ---------------------------
@@ -156,8 +258,12 @@ struct Tile {
         uint8_t* lds_row = lds_codes + (size_t)i * ROW_CODE_BYTES;
         float* dout = a.delta + (uint64_t)i * a.ld + col0 + 4 * lane;
 
+        if constexpr (SUB) {
+            compress_sub_blocks<FULL>(a, i, col0, lane, v, msg_row, lds_row, lds_units, dout);
+            return;
+        }
 #pragma unroll
-        for (int b = 0; b < BPT; ++b) {
+        for (int b = 0; b < (SUB ? 0 : BPT); ++b) {
             const uint64_t bcol0 = col0 + (uint64_t)b * B;            // first column of the block
             const bool block_live = FULL || (bcol0 < a.N);
             const uint64_t m = FULL ? (uint64_t)B : (block_live ? (a.N - bcol0 < (uint64_t)B ? a.N - bcol0 : (uint64_t)B) : 0);
@@ -332,31 +438,31 @@ struct Tile {
         if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
             using lane_t = typename CT::lane_t;
             uint32_t codes[SW];
-            float unit[BPT];
+            float unit[SW];                                          // of the block this lane's columns are in
 #pragma unroll
             for (int s = 0; s < SW; ++s) codes[s] = reinterpret_cast<const lane_t*>(nrow)[s * kWave + lane];
 #pragma unroll
-            for (int b = 0; b < BPT; ++b) unit[b] = lds_units[nb * BPT + b];
+            for (int s = 0; s < SW; ++s) unit[s] = lds_units[nb * BPT + (SUB ? s * BPS + lane / G : s / SPB)];
 #pragma unroll
             for (int s = 0; s < SW; ++s)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int q = (int)((codes[s] >> (BITS * c)) & (uint32_t)L);
-                    acc[s][c] = fmaf(w, (float)(2 * q - L) * unit[s / SPB], acc[s][c]);
+                    acc[s][c] = fmaf(w, (float)(2 * q - L) * unit[s], acc[s][c]);
                 }
         } else if constexpr (KIND == DS_COMP_SIGN_MEANABS) {
             uint32_t word[SW];
-            float scale[BPT];
+            float scale[SW];
 #pragma unroll
             for (int s = 0; s < SW; ++s) word[s] = reinterpret_cast<const uint32_t*>(nrow)[s * 8 + (lane >> 3)];
 #pragma unroll
-            for (int b = 0; b < BPT; ++b) scale[b] = lds_units[nb * BPT + b];
+            for (int s = 0; s < SW; ++s) scale[s] = lds_units[nb * BPT + (SUB ? s * BPS + lane / G : s / SPB)];
 #pragma unroll
             for (int s = 0; s < SW; ++s) {
                 const uint32_t nib = word[s] >> (4 * (lane & 7));
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    acc[s][c] = fmaf(w, ((nib >> c) & 1u) ? -scale[s / SPB] : scale[s / SPB], acc[s][c]);
+                    acc[s][c] = fmaf(w, ((nib >> c) & 1u) ? -scale[s] : scale[s], acc[s][c]);
             }
         } else {
 #pragma unroll
@@ -712,11 +818,13 @@ bool pick_for_block(int n, int nnz, std::vector<TilePlan>& plans, std::string& e
 template <int KIND, int BITS>
 bool pick_for_kind(int block, int n, int nnz, std::vector<TilePlan>& plan, std::string& err) {
     switch (block) {
+        case 64:   return pick_for_block<KIND, BITS, 64>(n, nnz, plan, err);
+        case 128:  return pick_for_block<KIND, BITS, 128>(n, nnz, plan, err);
         case 256:  return pick_for_block<KIND, BITS, 256>(n, nnz, plan, err);
         case 512:  return pick_for_block<KIND, BITS, 512>(n, nnz, plan, err);
         case 1024: return pick_for_block<KIND, BITS, 1024>(n, nnz, plan, err);
         case 2048: return pick_for_block<KIND, BITS, 2048>(n, nnz, plan, err);
-        default: err = "block must be a power of two between 256 and 2048"; return false;
+        default: err = "block must be a power of two between 64 and 2048"; return false;
     }
 }
 

@@ -167,6 +167,13 @@ SMALL = [
     small(wl.KIND_RAND_SPARSE, 5, 1000, k=1000),                                    # keeps everything
     small(wl.KIND_RAND_SPARSE, 40, 256 * 5 + 1, k=64, topo=wl.TOPO_TORUS2D, torus=(5, 8)),
     small(wl.KIND_RAND_SPARSE, 3, 1, k=1),
+    small(wl.KIND_QUANT_MAXABS, 8, 64 * 37 + 5, bits=4, block=64),                 # blocks narrower than a sweep
+    small(wl.KIND_QUANT_MAXABS, 16, 128 * 19 + 77, bits=2, block=128),
+    small(wl.KIND_QUANT_MAXABS, 5, 64 * 3 + 63, bits=2, block=64),
+    small(wl.KIND_QUANT_MAXABS, 20, 128 * 9, bits=4, block=128, topo=wl.TOPO_TORUS2D, torus=(4, 5)),
+    small(wl.KIND_SIGN_MEANABS, 8, 64 * 41 + 33, block=64),
+    small(wl.KIND_SIGN_MEANABS, 33, 128 * 7 + 1, block=128),
+    small(wl.KIND_SIGN_MEANABS, 3, 30, block=64),
 ]
 
 
@@ -182,7 +189,8 @@ def test_gradient_pitch_larger_than_N(w):
     lock_step(w, steps=2, pitch=((w.N + 3) // 4) * 4 + 64)
 
 
-@pytest.mark.parametrize("w", [SMALL[1], SMALL[4], SMALL[5], SMALL[10], SMALL[13]], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [SMALL[1], SMALL[4], SMALL[5], SMALL[10], SMALL[13], SMALL[-7], SMALL[-6], SMALL[-2]],
+                         ids=lambda w: w.name)
 def test_every_candidate_launch_shape(w, monkeypatch):
     # ds_init picks the launch shape by timing; here each candidate is pinned in turn and checked
     seen = []

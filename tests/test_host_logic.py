@@ -40,7 +40,7 @@ def test_validate_accepts_the_five_benchmark_configs():
     (dict(n=0), "n must"), (dict(N=0), "N must"), (dict(n=2), "ring needs"),
     (dict(topo=wl.TOPO_TORUS2D, n=8, torus=(2, 4)), "torus sides"),
     (dict(topo=wl.TOPO_TORUS2D, n=10, torus=(3, 3)), "must equal n"),
-    (dict(bits=3), "bits"), (dict(block=300), "power of two"), (dict(block=128), "power of two"),
+    (dict(bits=3), "bits"), (dict(block=300), "power of two"), (dict(block=32), "power of two"),
     (dict(block=8192), "power of two"), (dict(kind=wl.KIND_TOPK, k=0), "k must"),
     (dict(kind=wl.KIND_TOPK, k=10 ** 9), "k must"), (dict(gamma=float("nan")), "finite"),
     (dict(eta=float("inf")), "finite"), (dict(kind=9), "unknown compressor"), (dict(topo=7), "unknown topology"),
