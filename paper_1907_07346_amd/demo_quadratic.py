@@ -1,0 +1,89 @@
+"""Free run of DeepSqueeze on a synthetic quadratic, entirely on the GPU.
+
+n workers on a ring minimise  f(x) = 1/n sum_i 1/2 |x - c_i|^2  (minimiser: the mean of the c_i) from noisy
+gradients g_i = (x_i - c_i) + sigma xi.  The gradients are formed with torch from the library's own state
+buffer (borrowed through ds_state_ptrs), so nothing crosses PCIe between steps; ds_diagnostics gives the
+consensus distance and the carried compression error.  This illustrates the behaviour the paper's Theorem 1
+describes (convergence under compression thanks to the error compensation); it is not the paper's experiment,
+whose data and model are not available here.
+
+    python -m paper_1907_07346_amd.demo_quadratic [--steps 300] [--N 65536] [--workers 8]
+"""
+from __future__ import annotations
+
+import argparse
+
+import torch
+
+from . import binding as b
+from . import workloads as wl
+
+
+class _Borrowed:
+    def __init__(self, ptr, shape):
+        self.__cuda_array_interface__ = {"shape": shape, "typestr": "<f4", "data": (ptr, False), "version": 2,
+                                         "strides": None}
+
+
+def run(kind, n, N, steps, gamma, eta, sigma, report, **comp):
+    cfg, keep = b.make_config(n, N, wl.TOPO_RING, kind, gamma, eta, seed=1, **comp)
+    ds = b.DeepSqueeze(cfg, keep)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    c = torch.randn((n, N), generator=gen, device="cuda")
+    opt = c.mean(0)
+    f_opt = float(0.5 * ((opt - c) ** 2).sum(1).mean())
+    xp, _, ld = ds.ds_state_ptrs()
+    g = torch.zeros((n, ld), device="cuda")
+    rows = []
+    for t in range(steps + 1):
+        if t in report:
+            ds.ds_state_ptrs()                                  # completes a deferred tail, if the path has one
+            x = torch.as_tensor(_Borrowed(xp, (n, ld)), device="cuda")[:, :N]
+            xbar = x.mean(0)
+            gap = float(0.5 * ((xbar - c) ** 2).sum(1).mean()) - f_opt
+            d = ds.ds_diagnostics()
+            rows.append((t, gap / N, d["consensus_sq"] / (n * N), d["delta_sq"] / (n * N)))
+        if t == steps:
+            break
+        ds.ds_state_ptrs()
+        x = torch.as_tensor(_Borrowed(xp, (n, ld)), device="cuda")
+        g[:, :N] = (x[:, :N] - c) + sigma * torch.randn((n, N), generator=gen, device="cuda")
+        ds.ds_step(g)
+    bytes_per_step = ds.ds_diagnostics()["message_bytes"]
+    ds.ds_destroy()
+    return rows, bytes_per_step
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--N", type=int, default=65536)
+    ap.add_argument("--workers", type=int, default=8)
+    ap.add_argument("--gamma", type=float, default=0.1)
+    ap.add_argument("--sigma", type=float, default=0.1)
+    args = ap.parse_args()
+    n, N = args.workers, args.N
+    report = sorted({0, args.steps // 10, args.steps // 3, args.steps})
+    cases = [
+        ("identity (D-PSGD)", wl.KIND_IDENTITY, 0.5, {}),
+        ("4-bit blocks of 512", wl.KIND_QUANT_MAXABS, 0.5, dict(bits=4, block=512)),
+        ("2-bit blocks of 64", wl.KIND_QUANT_MAXABS, 0.3, dict(bits=2, block=64)),
+        ("2-bit blocks of 1024", wl.KIND_QUANT_MAXABS, 0.3, dict(bits=2, block=1024)),
+        ("sign, blocks of 256", wl.KIND_SIGN_MEANABS, 0.2, dict(block=256)),
+        ("top 1 %", wl.KIND_TOPK, 0.2, dict(k=max(1, N // 100))),
+        ("random 10 %", wl.KIND_RAND_SPARSE, 0.2, dict(k=max(1, N // 10))),
+        ("4 bits + norm (paper)", wl.KIND_QUANT_L2NORM, 0.5, dict(bits=4)),
+        ("2 bits + norm (paper)", wl.KIND_QUANT_L2NORM, 0.3, dict(bits=2)),
+    ]
+    print(f"{n} workers on a ring, N = {N}, gamma = {args.gamma}, sigma = {args.sigma}; per parameter: "
+          f"f(mean x) - f*, consensus distance, carried error")
+    for name, kind, eta, comp in cases:
+        rows, nbytes = run(kind, n, N, args.steps, args.gamma, eta, args.sigma, report, **comp)
+        ratio = n * N * 4 / nbytes
+        line = "  ".join(f"t={t}: {gap:.2e} {cons:.2e} {dsq:.2e}" for t, gap, cons, dsq in rows)
+        print(f"{name:24s} eta={eta:.1f} msg {ratio:6.1f}x smaller | {line}", flush=True)
+
+
+if __name__ == "__main__":
+    main()
