@@ -85,7 +85,8 @@ def extra_configs():
 
 
 def _rng(seed: int, tag: int, t: int) -> np.random.Generator:
-    return np.random.Generator(np.random.Philox(key=[(seed << 32) ^ tag, t]))
+    key0 = (((seed << 32) ^ (seed >> 32)) & 0xFFFFFFFFFFFFFFFF) ^ tag          # 64-bit seeds fold into one key word
+    return np.random.Generator(np.random.Philox(key=[key0, t]))
 
 
 def centres(cfg: Config) -> np.ndarray:

@@ -183,6 +183,38 @@ def test_lock_step_small_shapes(w):
     lock_step(w, steps=3)
 
 
+def _random_cases(count, seed):
+    r = np.random.default_rng(seed)
+    edges = [1, 3, 4, 5, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1023, 1025, 2047, 2049, 4095, 4096, 4097, 8191, 8193]
+    cases = []
+    for c in range(count):
+        kind = int(r.choice([wl.KIND_IDENTITY, wl.KIND_QUANT_MAXABS, wl.KIND_SIGN_MEANABS, wl.KIND_TOPK,
+                             wl.KIND_QUANT_L2NORM, wl.KIND_RAND_SPARSE], p=[0.08, 0.32, 0.2, 0.15, 0.15, 0.1]))
+        if r.random() < 0.3:
+            rows, cols = int(r.integers(3, 9)), int(r.integers(3, 9))
+            topo, torus, n = wl.TOPO_TORUS2D, (rows, cols), rows * cols
+        else:
+            topo, torus, n = wl.TOPO_RING, (0, 0), int(r.integers(3, 41))
+        N = int(r.choice(edges)) + int(r.integers(0, 3)) * int(r.choice([256, 512, 4096])) if r.random() < 0.7 \
+            else int(r.integers(1, 20_000))
+        bits = int(r.choice([2, 4])) if kind in (wl.KIND_QUANT_MAXABS, wl.KIND_QUANT_L2NORM) else 0
+        block = int(r.choice([64, 128, 256, 512, 1024, 2048])) if kind in (wl.KIND_QUANT_MAXABS, wl.KIND_SIGN_MEANABS) else 0
+        k = int(r.integers(1, N + 1)) if kind in (wl.KIND_TOPK, wl.KIND_RAND_SPARSE) else 0
+        cases.append(wl.Config(f"rnd{c}_k{kind}_n{n}_N{N}_b{bits}_B{block}_k{k}", n=n, N=N, topo=topo, torus=torus, kind=kind,
+                               gamma=float(r.choice([0.01, 0.1, 0.5])), eta=float(r.choice([0.1, 0.3, 0.5])), steps=2,
+                               grad=str(r.choice(["normal", "student_t3"])), grad_scale=float(r.choice([1e-3, 0.5, 30.0])),
+                               bits=bits, block=block, k=k, seed=int(r.integers(0, 2 ** 40))))
+    return cases
+
+
+def test_randomized_small_configs():
+    """120 seeded random configurations (sizes around the tile, sweep and chunk edges; rings and tori; every
+    compressor): two lock-step iterations each, everything compared bit for bit."""
+    for w in _random_cases(120, seed=2024):
+        say("case", w.name)
+        lock_step(w, steps=2)
+
+
 @pytest.mark.parametrize("w", [SMALL[0], SMALL[10], SMALL[17]], ids=lambda w: w.name)
 def test_gradient_pitch_larger_than_N(w):
     say("case", w.name)
