@@ -215,6 +215,36 @@ def test_randomized_small_configs():
         lock_step(w, steps=2)
 
 
+def test_randomized_free_runs_on_random_graphs():
+    """40 seeded random configurations on random connected graphs (Metropolis weights, given as CSR): five steps
+    without touching the state in between -- so deferred tails go through the next step's first pass -- with W,
+    gamma and eta changed once on the way; messages compared after every step, the state at the end."""
+    r = np.random.default_rng(77)
+    for w in _random_cases(40, seed=4048):
+        n = w.n
+        Ws = [_random_graph(n, int(r.integers(0, 2 * n)), seed=int(r.integers(0, 1 << 30))) for _ in range(2)]
+        say("case", w.name)
+        rp, co, va = oracle.dense_to_csr(Ws[0])
+        cfg, keep = b.make_config(n, w.N, wl.TOPO_CSR, w.kind, w.gamma, w.eta, bits=w.bits, block=w.block, k=w.k,
+                                  seed=w.seed, W_csr=(rp, co, va.astype(np.float32)))
+        ds = b.DeepSqueeze(cfg, keep)
+        st = oracle_state(w, Ws[0])
+        for t in range(5):
+            if t == 3:
+                rp, co, va = oracle.dense_to_csr(Ws[1])
+                ds.ds_set_mixing((rp, co, va.astype(np.float32)))
+                st.set_W(Ws[1])
+                st.gamma, st.eta = st.gamma * 0.5, min(0.5, st.eta * 1.5)
+                ds.ds_set_rates(st.gamma, st.eta)
+            g = wl.gradient(w, t)
+            ds.ds_step(upload(g))
+            _, msg = oracle.step(st, g, want_cv=False)
+            assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} step {t}: messages differ"
+        x, d = ds.ds_read_state()
+        assert assert_close(f"{w.name} x", x, st.x) + assert_close(f"{w.name} delta", d, st.delta) == 0
+        ds.ds_destroy()
+
+
 @pytest.mark.parametrize("w", [SMALL[0], SMALL[10], SMALL[17]], ids=lambda w: w.name)
 def test_gradient_pitch_larger_than_N(w):
     say("case", w.name)
