@@ -737,10 +737,17 @@ void launch_tile(const TileArgs& a, int rpw_runtime, hipStream_t stream) {
     const unsigned gy = (unsigned)((tiles + gx - 1) / gx);
     const size_t lds = T::lds_bytes(a.n, a.nnz);
     auto kern = fused_tile_kernel<KIND, BITS, B, SW, NW, RPW>;
-    static bool attr_set = false;
-    if (lds > 48 * 1024 && !attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
+    // more than the default dynamic LDS has to be asked for once per kernel and device (handles are
+    // bound to one device, but a process may hold handles on several)
+    static unsigned long long attr_devices = 0;
+    if (lds > 48 * 1024) {
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        const unsigned long long bit = 1ull << (dev & 63);
+        if (!(attr_devices & bit)) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            attr_devices |= bit;
+        }
     }
     hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(NW * kWave), lds, stream, a, rpw_runtime);
 }
