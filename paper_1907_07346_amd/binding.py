@@ -25,12 +25,17 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
            "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
-           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates"]
+           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient"]
 
 
 class ds_comp(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int32), ("bits", ctypes.c_int32), ("block", ctypes.c_int32),
                 ("reserved", ctypes.c_int32), ("k", ctypes.c_uint64)]
+
+
+class ds_workload(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int32), ("kind", ctypes.c_int32), ("N", ctypes.c_uint64), ("scale", ctypes.c_float),
+                ("reserved", ctypes.c_float), ("seed", ctypes.c_uint64)]
 
 
 class ds_config(ctypes.Structure):
@@ -68,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.ds_read_state.argtypes, L.ds_read_state.restype = [vp, vp, vp], i32
         L.ds_set_mixing.argtypes, L.ds_set_mixing.restype = [vp, vp, vp, vp], i32
         L.ds_set_rates.argtypes, L.ds_set_rates.restype = [vp, ctypes.c_float, ctypes.c_float], i32
+        L.ds_workload_gradient.argtypes = [ctypes.POINTER(ds_workload), u64, vp, u64, vp, u64, vp]
+        L.ds_workload_gradient.restype = i32
         L.ds_diagnostics.argtypes, L.ds_diagnostics.restype = [vp, ctypes.POINTER(ctypes.c_double)], i32
         L.ds_write_state.argtypes, L.ds_write_state.restype = [vp, vp, vp, u64], i32
         L.ds_read_messages.argtypes, L.ds_read_messages.restype = [vp, vp, u64, u64p], i32
@@ -102,6 +109,18 @@ def make_config(n: int, N: int, topo: int, kind: int, gamma: float, eta: float, 
     c.comp.kind, c.comp.bits, c.comp.block, c.comp.k = kind, bits, block, k
     c.gamma, c.eta, c.seed = gamma, eta, seed
     return c, keep
+
+
+def ds_workload_gradient(kind: str, n: int, N: int, scale: float, seed: int, t: int, g: "torch.Tensor", x_ptr: int = 0,
+                         x_ld: int = 0, stream: Optional["torch.cuda.Stream"] = None):
+    """Fills the CUDA float32 tensor g (n, >= N) with the deterministic gradients of step t (see detgen.py)."""
+    from .detgen import GRAD_KINDS
+    assert g.is_cuda and g.dtype == torch.float32 and g.dim() == 2 and g.shape[0] == n and g.stride(1) == 1
+    w = ds_workload(n, GRAD_KINDS[kind], N, scale, 0.0, seed)
+    s = stream if stream is not None else torch.cuda.current_stream()
+    st = lib().ds_workload_gradient(ctypes.byref(w), t, x_ptr, x_ld, g.data_ptr(), g.stride(0), s.cuda_stream)
+    if st != DS_OK:
+        raise RuntimeError(f"ds_workload_gradient failed with status {st}")
 
 
 def config_from_workload(w: Config):

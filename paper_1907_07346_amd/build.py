@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdsq.so")
-SOURCES = ["dsq_host.cpp", "dsq_api.hip", "dsq_tile_kernels.hip", "dsq_topk_kernels.hip", "dsq_l2norm_kernels.hip"]
+SOURCES = ["dsq_host.cpp", "dsq_api.hip", "dsq_tile_kernels.hip", "dsq_topk_kernels.hip", "dsq_l2norm_kernels.hip", "dsq_workload_kernels.hip"]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is written out as fmaf, nothing else may fuse
 #  (bit-level agreement of codes and scales depends on it).  The packed-fp32 feature is switched off because

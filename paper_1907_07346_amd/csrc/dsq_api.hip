@@ -208,6 +208,14 @@ __global__ void __launch_bounds__(256) copy_kernel(f32x4* __restrict__ dst, cons
 
 extern "C" {
 
+ds_status ds_workload_gradient(const ds_workload* w, uint64_t t, const float* x_dev, uint64_t x_ld, float* g_dev,
+                               uint64_t g_ld, void* hip_stream) {
+    if (!w || !g_dev || w->n < 1 || w->N < 1 || w->N > 0xFFFFFFF0ull || g_ld < w->N) return DS_EINVAL;
+    if (w->kind < DS_GRAD_NORMAL || w->kind > DS_GRAD_QUADRATIC || !std::isfinite(w->scale)) return DS_EINVAL;
+    if (w->kind == DS_GRAD_QUADRATIC && (!x_dev || x_ld < w->N)) return DS_EINVAL;
+    return dsq::launch_workload_gradient(*w, t, x_dev, x_ld, g_dev, g_ld, static_cast<hipStream_t>(hip_stream));
+}
+
 ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream) {
     if (!dst_dev || !src_dev || (bytes & 15) || ((reinterpret_cast<uintptr_t>(dst_dev) | reinterpret_cast<uintptr_t>(src_dev)) & 15))
         return DS_EINVAL;

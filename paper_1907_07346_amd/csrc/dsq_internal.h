@@ -133,4 +133,8 @@ ds_status l2q_step(L2State* s, const L2Args& a, hipStream_t stream);
 // l2q_flush applies them now (no-op if nothing is pending).  Call before the state is read or replaced.
 ds_status l2q_flush(L2State* s, hipStream_t stream);
 
+// Device twin of the deterministic host gradient generator (harness aid).
+ds_status launch_workload_gradient(const ds_workload& w, uint64_t t, const float* x, uint64_t x_ld, float* g, uint64_t g_ld,
+                                   hipStream_t stream);
+
 }  // namespace dsq

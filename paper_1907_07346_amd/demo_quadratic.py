@@ -1,8 +1,9 @@
 """Free run of DeepSqueeze on a synthetic quadratic, entirely on the GPU.
 
 n workers on a ring minimise  f(x) = 1/n sum_i 1/2 |x - c_i|^2  (minimiser: the mean of the c_i) from noisy
-gradients g_i = (x_i - c_i) + sigma xi.  The gradients are formed with torch from the library's own state
-buffer (borrowed through ds_state_ptrs), so nothing crosses PCIe between steps; ds_diagnostics gives the
+gradients g_i = (x_i - c_i) + sigma xi.  The gradients are drawn on the device by ds_workload_gradient from the
+library's own state buffer (borrowed through ds_state_ptrs), so nothing crosses PCIe between steps, and the
+run is reproducible bit for bit (the generator has a host twin, detgen.py); ds_diagnostics gives the
 consensus distance and the carried compression error.  This illustrates the behaviour the paper's Theorem 1
 describes (convergence under compression thanks to the error compensation); it is not the paper's experiment,
 whose data and model are not available here.
@@ -16,6 +17,7 @@ import argparse
 import torch
 
 from . import binding as b
+from . import detgen
 from . import workloads as wl
 
 
@@ -28,9 +30,7 @@ class _Borrowed:
 def run(kind, n, N, steps, gamma, eta, sigma, report, **comp):
     cfg, keep = b.make_config(n, N, wl.TOPO_RING, kind, gamma, eta, seed=1, **comp)
     ds = b.DeepSqueeze(cfg, keep)
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(7)
-    c = torch.randn((n, N), generator=gen, device="cuda")
+    c = torch.from_numpy(detgen.centres(n, N, seed=1)).cuda()
     opt = c.mean(0)
     f_opt = float(0.5 * ((opt - c) ** 2).sum(1).mean())
     xp, _, ld = ds.ds_state_ptrs()
@@ -47,8 +47,7 @@ def run(kind, n, N, steps, gamma, eta, sigma, report, **comp):
         if t == steps:
             break
         ds.ds_state_ptrs()
-        x = torch.as_tensor(_Borrowed(xp, (n, ld)), device="cuda")
-        g[:, :N] = (x[:, :N] - c) + sigma * torch.randn((n, N), generator=gen, device="cuda")
+        b.ds_workload_gradient("quadratic", n, N, sigma, 1, t, g, xp, ld)
         ds.ds_step(g)
     bytes_per_step = ds.ds_diagnostics()["message_bytes"]
     ds.ds_destroy()

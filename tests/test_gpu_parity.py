@@ -670,6 +670,53 @@ def test_rand_sparse_step_counter_set_from_outside():
     ds.ds_destroy()
 
 
+@pytest.mark.parametrize("kind", ["normal", "student_t3", "quadratic"])
+def test_device_gradient_generator_matches_the_host_one_bit_for_bit(kind):
+    from paper_1907_07346_amd import detgen as dg
+    for n, N, pitch, scale, seed, t in ((3, 1, 4, 0.5, 1, 0), (5, 1027, 1032, 0.01, (7 << 40) + 3, 17),
+                                        (8, 4 * 4099, 4 * 4099, 30.0, 99, (1 << 32) + 5)):
+        x = wl.random_state(small(wl.KIND_IDENTITY, n, N), seed=3)[0]
+        xd = upload(x, pitch)
+        g = torch.full((n, pitch), 7.0, device="cuda")
+        b.ds_workload_gradient(kind, n, N, scale, seed, t, g, xd.data_ptr(), xd.stride(0))
+        got = g.cpu().numpy()
+        want = dg.gradient(kind, n, N, scale, seed, t, x=x)
+        assert np.array_equal(got[:, :N].view(np.uint32), want.view(np.uint32)), \
+            f"{kind} n={n} N={N}: {int((got[:, :N] != want).sum())} values differ"
+        assert np.all(got[:, N:] == 0)
+
+
+def test_free_run_with_gradients_drawn_on_the_device():
+    """Config 0 at full size for its 100 steps, plus a sign and a top-k run on the same quadratic: the GPU side
+    draws its gradients on the device from its own state (no host-device traffic inside the run), the oracle side
+    gets the host twin's gradients from its own state; messages are compared every 10th step, the states at the end."""
+    from paper_1907_07346_amd import detgen as dg
+    base = wl.configs()[0]
+    for w in (base, small(wl.KIND_SIGN_MEANABS, 8, 20_000, block=256, gamma=0.1, eta=0.2),
+              small(wl.KIND_TOPK, 8, 20_000, k=200, gamma=0.1, eta=0.2),
+              small(wl.KIND_QUANT_L2NORM, 8, 20_000, bits=4, gamma=0.1, eta=0.5)):
+        steps = 100 if w is base else 30
+        say("case", w.name, "device-driven free run", steps, "steps")
+        ds = b.DeepSqueeze.from_workload(w)
+        st = oracle_state(w)
+        xp, _, ld = ds.ds_state_ptrs()
+        g = torch.zeros((w.n, ld), device="cuda")
+        for t in range(steps):
+            xp, _, ld = ds.ds_state_ptrs()                     # completes a deferred tail, if the path has one
+            b.ds_workload_gradient("quadratic", w.n, w.N, 0.1, w.seed, t, g, xp, ld)
+            ds.ds_step(g)
+            _, msg = oracle.step(st, dg.gradient("quadratic", w.n, w.N, 0.1, w.seed, t, x=st.x), want_cv=False,
+                                 want_msg=(t % 10 == 9))
+            if t % 10 == 9:
+                assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} step {t}: messages differ"
+        x, d = ds.ds_read_state()
+        assert assert_close(f"{w.name} x", x, st.x) + assert_close(f"{w.name} delta", d, st.delta) == 0
+        # the run has made progress towards consensus on the mean of the centres
+        c = dg.centres(w.n, w.N, w.seed)
+        assert np.abs(x.mean(0) - c.mean(0)).mean() < 0.2 * np.abs(c.mean(0)).mean()
+        ds.ds_destroy()
+
+
 def test_step_on_a_side_stream_and_determinism():
     w = small(wl.KIND_TOPK, 8, 50_000, k=500)
     outs = []

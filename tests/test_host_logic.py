@@ -140,3 +140,37 @@ def test_workload_generators_are_seeded_and_shaped():
         assert not np.array_equal(g1, wl.gradient(w, 4, x, c))
     w = wl.configs()[4]
     assert w.k == 255_570 and wl.configs()[1].N == 11_173_962
+
+
+def test_deterministic_generator_distributions_and_accuracy():
+    """The host half of the bit-reproducible gradient generator (its device twin is compared with it bit for bit
+    in the GPU tests): the hand-written ln / sin / cos are accurate, and the variates have the distributions
+    the workloads name."""
+    from paper_1907_07346_amd import detgen as dg
+    r = np.random.default_rng(0)
+    u = np.concatenate([r.random(100_000), 2.0 ** -r.integers(1, 33, 1000), [1.0, 0.5, 2.0 ** -33]])
+    u = u[u > 0]
+    ref = np.log(u)
+    assert np.max(np.abs(dg.det_log(u) - ref) / np.maximum(np.abs(ref), 1e-300)) < 2e-15
+    assert dg.det_log(np.array([1.0]))[0] == 0.0
+    u = np.concatenate([r.random(100_000), [0.0, 0.25, 0.5, 0.75, 1 - 2.0 ** -33]])
+    c, s = dg.det_sincos_2pi(u)
+    assert np.max(np.abs(c - np.cos(2 * np.pi * u))) < 3e-15 and np.max(np.abs(s - np.sin(2 * np.pi * u))) < 3e-15
+    assert np.max(np.abs(c * c + s * s - 1)) < 1e-15
+    # its Philox is the published one (the oracle's is pinned by known answers)
+    w = dg.philox4x32_10(np.array([7, 8]), np.array([2, 2]), np.array([3, 3]), np.array([4, 4]), 11, 12)
+    for q in range(2):
+        assert [int(w[k][q]) for k in range(4)] == list(oracle.philox4x32_10([7 + q, 2, 3, 4], [11, 12]))
+    g = dg.gradient("normal", 8, 200_001, 2.0, seed=5, t=3).astype(np.float64)
+    assert abs(g.mean()) < 5 * 2 / np.sqrt(g.size) and abs(g.std() - 2.0) < 0.01 and abs((g ** 4).mean() / 16 - 3) < 0.05
+    assert abs(np.corrcoef(g[0, :-1], g[0, 1:])[0, 1]) < 0.01 and abs(np.corrcoef(g[0], g[1])[0, 1]) < 0.01
+    assert not np.array_equal(g, dg.gradient("normal", 8, 200_001, 2.0, seed=5, t=4))
+    assert np.array_equal(g.astype(np.float32), dg.gradient("normal", 8, 200_001, 2.0, seed=5, t=3))
+    t3 = np.abs(dg.gradient("student_t3", 4, 100_000, 1.0, seed=6, t=0)).ravel()
+    med, p99 = np.percentile(t3, [50, 99])                      # Student t, 3 degrees of freedom: 0.7649, 5.841
+    assert abs(med - 0.7649) < 0.01 and abs(p99 - 5.841) < 0.25
+    x = r.standard_normal((3, 1001)).astype(np.float32)
+    gq = dg.gradient("quadratic", 3, 1001, 0.1, seed=7, t=2, x=x)
+    cen = dg.centres(3, 1001, 7)
+    resid = (gq - (x - cen)).astype(np.float64) / 0.1
+    assert abs(resid.std() - 1) < 0.05 and abs(cen.std() - 1) < 0.05
