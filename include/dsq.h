@@ -133,7 +133,8 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out);
  * g_dev: caller-owned DEVICE pointer, n rows of fp32, row pitch g_ld >= N elements, g_ld a multiple
  * of 4, base 16-byte aligned; read-only.  Work is enqueued on hip_stream (a hipStream_t, NULL = the
  * default stream) and the call returns without synchronising; g_dev must stay valid until that
- * work has finished.  Advances the step counter t by 1.  DS_ESTATE if the current HIP device is not
+ * work has finished, and the stream until the handle's next call that synchronises (those calls
+ * enqueue on, and wait for, the stream of the last ds_step).  Advances the step counter t by 1.  DS_ESTATE if the current HIP device is not
  * the one ds_init ran on.
  * The call only launches kernels: it makes no allocation, copy, memset or synchronisation, and the
  * step counter that selects the random rounding words lives in device memory and is advanced by
