@@ -182,7 +182,9 @@ ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t*
  * again after later steps before reading x. */
 ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t* ld);
 
-/* Borrows the device message buffer (ds_message_bytes bytes, layout as above). */
+/* Borrows the device buffer that holds the messages of the last ds_step (ds_message_bytes bytes, layout as
+ * above).  Some launch plans alternate between two buffers, so ask again after every step; then the call
+ * synchronises with the stream of the last ds_step. */
 ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes);
 
 /* The quantities the paper's analysis tracks, computed on the device in fp64 (off the hot path,

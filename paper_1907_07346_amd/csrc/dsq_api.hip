@@ -12,6 +12,7 @@ struct ds_handle {
     dsq::Graph graph;
     uint64_t ld = 0;                 // row pitch of x and delta, in floats
     uint64_t msg_row_bytes = 0;
+    uint64_t msg_half = 0;           // row-streaming variant: bytes of one of the two message buffers (else 0)
     uint64_t t = 0;
     bool stepped = false;
     int device = 0;
@@ -67,11 +68,17 @@ void release(ds_handle* h) {
 }
 
 
-// Two paths (top-k, norm-rescaled codes) leave the tail of a step to the next step's first pass;
+dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld);
+
+// Three paths (top-k, norm-rescaled codes, the row-streaming block kernels) leave the tail of a step to the next step's first pass;
 // this applies it now, on the stream of the last step.
 ds_status flush_deferred(ds_handle* h) {
     if (h->topk) return dsq::topk_flush(h->topk, h->last_stream);
     if (h->l2q) return dsq::l2q_flush(h->l2q, h->last_stream);
+    if (h->tile.streaming && h->stepped) {
+        h->tile.flush(tile_args(h, nullptr, 0), h->last_stream);
+        return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
+    }
     return DS_OK;
 }
 
@@ -83,6 +90,8 @@ dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     a.n = h->cfg.n; a.nnz = (int)h->graph.col.size();
     a.gamma = h->cfg.gamma; a.eta = h->cfg.eta;
     a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32); a.t_ptr = h->d_t;
+    a.msg_half = h->msg_half;
+    a.pending = reinterpret_cast<uint32_t*>(h->d_t + 3);        // cell 3: the row-streaming variant's pending flag
     if (h->cfg.comp.kind == DS_COMP_RAND_SPARSE) {
         a.keep_off = h->d_keep;
         a.keep_group_off = h->d_keep + (size_t)h->cfg.n * h->nsweeps;
@@ -250,7 +259,16 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     } else if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {
         h->plan_name = "l2norm/two-pass";
     } else {
-        if (!dsq::choose_tile_plans(h->cfg, (int)h->graph.col.size(), h->tile_candidates, err)) {
+        // DSQ_STREAM=1 asks for the row-streaming variant of the block compressors; it is also what serves a
+        // number of workers whose codes do not fit in LDS
+        const char* want_stream = std::getenv("DSQ_STREAM");
+        dsq::TilePlan sp;
+        const bool can_stream = dsq::stream_plan(h->cfg, sp);
+        const bool fits = dsq::choose_tile_plans(h->cfg, (int)h->graph.col.size(), h->tile_candidates, err);
+        if (can_stream && (!fits || (want_stream && *want_stream == '1'))) {
+            h->tile_candidates.assign(1, sp);
+            h->msg_half = (uint64_t)cfg->n * h->msg_row_bytes;
+        } else if (!fits) {
             std::fprintf(stderr, "ds_init: %s\n", err.c_str());
             return bail(DS_EINVAL);
         }
@@ -270,7 +288,7 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     if (e != hipSuccess) { std::fprintf(stderr, "ds_init: no HIP device: %s\n", hipGetErrorString(e)); return bail(DS_EHIP); }
     const size_t state_bytes = (size_t)cfg->n * h->ld * sizeof(float);
     const size_t nnz = h->graph.col.size();
-    const size_t msg_bytes = (size_t)cfg->n * h->msg_row_bytes;
+    const size_t msg_bytes = (size_t)cfg->n * h->msg_row_bytes * (h->msg_half ? 2 : 1);
     // rowptr | col | coef as one contiguous array of 32-bit words
     hipError_t errs[5] = {
         hipMalloc(&h->x, state_bytes), hipMalloc(&h->delta, state_bytes), hipMalloc(&h->msg, msg_bytes ? msg_bytes : 4),
@@ -306,7 +324,7 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     if (pin && *pin) {
         const unsigned long long v = std::strtoull(pin, nullptr, 10);
         if (v <= kMaxPitchSkew && (v & 3) == 0) skew = v;
-    } else if (tiled && (uint64_t)cfg->n * cfg->N >= (32ull << 20)) {
+    } else if (tiled && !h->tile.streaming && (uint64_t)cfg->n * cfg->N >= (32ull << 20)) {
         skew = autotune(h, base_ld, state_bytes, msg_bytes);
     }
     h->ld = base_ld + skew;
@@ -379,7 +397,7 @@ ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_
     dsq::Graph g;
     if (dsq::build_graph(&probe, g, err) != DS_OK) return fail(h, DS_EINVAL, err);
     const size_t nnz = g.col.size();
-    if (!h->topk && !h->l2q) {
+    if (!h->topk && !h->l2q && !h->tile.streaming) {
         // the launch shape was chosen for the old graph; the new CSR only has to fit in LDS next to the codes
         std::vector<dsq::TilePlan> plans;
         if (!dsq::choose_tile_plans(h->cfg, (int)nnz, plans, err)) return fail(h, DS_EINVAL, err);
@@ -444,6 +462,17 @@ ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_h
     return DS_OK;
 }
 
+// Row-streaming variant: step t writes message buffer t & 1, so the last step's messages are in half (t - 1) & 1
+// of the counter the device holds now (the caller has synchronised).
+static ds_status last_message_buffer(ds_handle* h, uint8_t** out) {
+    *out = h->msg;
+    if (!h->msg_half) return DS_OK;
+    unsigned long long t64 = 0;
+    DSQ_HIP(h, hipMemcpy(&t64, h->d_t, sizeof(t64), hipMemcpyDeviceToHost));
+    if ((t64 & 1ull) == 0) *out = h->msg + h->msg_half;      // t - 1 is odd
+    return DS_OK;
+}
+
 ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t* bytes) {
     if (!h) return DS_EINVAL;
     if (!h->stepped) return fail(h, DS_ESTATE, "no step has been taken yet");
@@ -451,7 +480,9 @@ ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t*
     if (bytes) *bytes = total;
     if (!host_buf || cap < total) return fail(h, DS_EINVAL, "message buffer too small");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
-    DSQ_HIP(h, hipMemcpy(host_buf, h->msg, total, hipMemcpyDeviceToHost));
+    uint8_t* src = nullptr;
+    if (last_message_buffer(h, &src) != DS_OK) return DS_EHIP;
+    DSQ_HIP(h, hipMemcpy(host_buf, src, total, hipMemcpyDeviceToHost));
     if (h->d_keep) {
         uint32_t overflow = 0;
         DSQ_HIP(h, hipMemcpy(&overflow, h->d_keep + (size_t)h->cfg.n * (h->nsweeps + h->ngroups) + h->cfg.n, sizeof(overflow), hipMemcpyDeviceToHost));
@@ -472,7 +503,12 @@ ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t
 
 ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes) {
     if (!h) return DS_EINVAL;
-    if (msg_dev) *msg_dev = h->msg;
+    uint8_t* src = h->msg;
+    if (h->msg_half) {                                       // which of the two buffers is the last step's: ask the device
+        DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
+        if (last_message_buffer(h, &src) != DS_OK) return DS_EHIP;
+    }
+    if (msg_dev) *msg_dev = src;
     if (bytes) *bytes = h->msg_row_bytes * (uint64_t)h->cfg.n;
     return DS_OK;
 }

@@ -47,6 +47,10 @@ struct TileArgs {
     int n, nnz;                // workers; stored entries of W - I
     float gamma, eta;
     uint32_t seed_lo, seed_hi;
+    // row-streaming variant only:
+    const uint8_t* msg_prev;           // the previous step's messages: set by the kernels themselves (msg holds two
+    uint64_t msg_half;                 // buffers of msg_half bytes; step t writes half t & 1 and reads the other)
+    uint32_t* pending;                 // 1: the previous step's gossip sum has not been added to x yet
     // random sparsifier only:
     const uint32_t* keep_off;          // n x nsweeps: kept values before each 256-column sweep inside its group of 16
     const uint32_t* keep_group_off;    // n x ngroups: values the row's message holds before each group
@@ -70,6 +74,11 @@ struct TilePlan {
     int waves = 0;             // waves per workgroup
     int rows_per_wave = 0;     // rows each wave owns (held in registers when the variant says so)
     int sweeps = 0;            // 256-column sweeps per tile
+    // Row-streaming variant (no LDS exchange, so no limit on n): a step leaves x = x - gamma g and its gossip sum
+    // to the next step's pass, which decodes the neighbours' codes from the previous messages; `flush` adds a
+    // pending sum now.
+    bool streaming = false;
+    void (*flush)(const TileArgs&, hipStream_t) = nullptr;
 };
 
 // Random sparsifier: makes sure the kept-element counts of this step's 256-column sweeps are in keep_raw (the tile
@@ -81,6 +90,9 @@ struct TilePlan {
 void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group_tot, uint32_t* prev_count, uint32_t* overflow,
                          hipStream_t stream);
 uint64_t rand_sparse_capacity(uint64_t N, uint64_t k);
+
+// The row-streaming plan of a block compressor (quantiser or sign); false if the compressor has none.
+bool stream_plan(const ds_config& cfg, TilePlan& plan);
 
 // Lists the variants that fit (n, compressor), best guess first; returns false with `err` set if none does.
 bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plans, std::string& err);

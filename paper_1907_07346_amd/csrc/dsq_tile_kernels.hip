@@ -140,9 +140,68 @@ struct Tile {
         return (size_t)n * ROW_CODE_BYTES + (size_t)n * BPT * sizeof(float) + (size_t)(n + 1 + 2 * nnz) * 4;
     }
 
+    // ---- line 9 of the PREVIOUS step for one row of a tile, decoding the neighbours' codes from that step's
+    //      messages in HBM (row-streaming variant: nothing is shared through LDS): x = xh + eta sum_j a_ij C[v_j]
+    template <bool FULL>
+    static __device__ __forceinline__ void gossip_from_messages(const TileArgs& a, int i, uint64_t col0, int lane, float4 (&x)[SW]) {
+        static_assert(KIND == DS_COMP_QUANT_MAXABS || KIND == DS_COMP_SIGN_MEANABS, "messages of this operator cannot be decoded per column");
+        float acc[SW][4];
+#pragma unroll
+        for (int s = 0; s < SW; ++s) acc[s][0] = acc[s][1] = acc[s][2] = acc[s][3] = 0.f;
+        const int e0 = a.rowptr[i], e1 = a.rowptr[i + 1];
+        for (int e = e0; e < e1; ++e) {                         // ascending neighbour index, own index included
+            const int nb = a.col[e];
+            const float w = a.coef[e];
+            const uint8_t* nrow = a.msg_prev + (uint64_t)nb * a.msg_row_bytes;
+#pragma unroll
+            for (int s = 0; s < SW; ++s) {
+                const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                if (!FULL && j >= a.N) continue;                // no message bytes exist for these columns
+                const uint64_t bcol0 = SUB ? col0 + (uint64_t)s * kSweep + (uint64_t)(lane / G) * B
+                                           : col0 + (uint64_t)(s / SPB) * B;
+                const uint8_t* blk = nrow + (bcol0 / B) * MSG_BLOCK_BYTES;
+                const float scale = *reinterpret_cast<const float*>(blk);
+                const int slot = SUB ? lane % G : (s % SPB) * kWave + lane;     // lane-slot inside the block
+                if constexpr (KIND == DS_COMP_QUANT_MAXABS) {
+                    using lane_t = typename CT::lane_t;
+                    const float unit = scale / (float)L;
+                    const uint32_t codes = reinterpret_cast<const lane_t*>(blk + 4)[slot];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int q = (int)((codes >> (BITS * c)) & (uint32_t)L);
+                        float cv = (float)(2 * q - L) * unit;
+                        if (!FULL && !(j + c < a.N)) cv = 0.f;
+                        acc[s][c] = fmaf(w, cv, acc[s][c]);
+                    }
+                } else {
+                    const uint32_t word = reinterpret_cast<const uint32_t*>(blk + 4)[slot >> 3];
+                    const uint32_t nib = word >> (4 * (lane & 7));
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        float cv = ((nib >> c) & 1u) ? -scale : scale;
+                        if (!FULL && !(j + c < a.N)) cv = 0.f;
+                        acc[s][c] = fmaf(w, cv, acc[s][c]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < SW; ++s) {
+            x[s].x = fmaf(a.eta, acc[s][0], x[s].x); x[s].y = fmaf(a.eta, acc[s][1], x[s].y);
+            x[s].z = fmaf(a.eta, acc[s][2], x[s].z); x[s].w = fmaf(a.eta, acc[s][3], x[s].w);
+            if (!FULL) {                                        // keep the pitch padding at zero
+                const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
+                if (!(j + 0 < a.N)) x[s].x = 0.f;
+                if (!(j + 1 < a.N)) x[s].y = 0.f;
+                if (!(j + 2 < a.N)) x[s].z = 0.f;
+                if (!(j + 3 < a.N)) x[s].w = 0.f;
+            }
+        }
+    }
+
     // ---- lines 6-7 for blocks of 64 or 128 columns: G = B/4 lanes hold one block of a sweep --------
     template <bool FULL>
-    static __device__ __forceinline__ void compress_sub_blocks(const TileArgs& a, int i, uint64_t col0, int lane, const float4 (&v)[SW],
+    static __device__ __forceinline__ void compress_sub_blocks(const TileArgs& a, int i, int li, uint64_t col0, int lane, const float4 (&v)[SW],
                                                                uint8_t* msg_row, uint8_t* lds_row, float* lds_units, float* dout) {
         const int grp = lane / G, in_blk = lane % G;                  // block of the sweep, lane-slot inside the block
         [[maybe_unused]] uint32_t t_lo = 0;
@@ -162,7 +221,7 @@ struct Tile {
                 const float unit = scale / (float)L;
                 const float inv = (scale > 0.f) ? hl / scale : 0.f;
                 if (in_blk == 0) {
-                    lds_units[i * BPT + s * BPS + grp] = unit;
+                    lds_units[li * BPT + s * BPS + grp] = unit;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
                 uint32_t rnd[4];
@@ -195,7 +254,7 @@ struct Tile {
                 const float sum = group_sum_tree<G>((fabsf(v[s].x) + fabsf(v[s].y)) + (fabsf(v[s].z) + fabsf(v[s].w)));
                 const float scale = block_live ? sum / (float)m : 0.f;
                 if (in_blk == 0) {
-                    lds_units[i * BPT + s * BPS + grp] = scale;
+                    lds_units[li * BPT + s * BPS + grp] = scale;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
                 uint32_t nib = 0;
@@ -224,8 +283,10 @@ struct Tile {
     }
 
     // ---- phase 1 for one row: returns xh (x - gamma g) in registers ---------------------------
-    template <bool FULL>
-    static __device__ __forceinline__ void compress_row(const TileArgs& a, int i, uint64_t col0, int lane,
+    // `li` is the slot of the row in the LDS arrays (the row itself in the fused kernel).  TAIL: x holds the
+    // previous step's x - gamma g and that step's gossip sum is still due (row-streaming variant).
+    template <bool FULL, bool TAIL = false>
+    static __device__ __forceinline__ void compress_row(const TileArgs& a, int i, int li, uint64_t col0, int lane,
                                                         uint8_t* lds_codes, float* lds_units, float4 (&xh)[SW]) {
         float4 xv[SW], gv[SW], dv[SW];
         const float* xr = a.x + (uint64_t)i * a.ld + col0 + 4 * lane;
@@ -245,6 +306,9 @@ struct Tile {
                 gv[s].w = (j + 3 < a.N) ? gr[s * kSweep + 3] : 0.f;
             }
         }
+        if constexpr (TAIL) {
+            if (*a.pending != 0u) gossip_from_messages<FULL>(a, i, col0, lane, xv);
+        }
         float4 v[SW];
 #pragma unroll
         for (int s = 0; s < SW; ++s) {                      // Algorithm 1, line 5
@@ -255,11 +319,11 @@ struct Tile {
         }
 
         uint8_t* msg_row = a.msg + (uint64_t)i * a.msg_row_bytes;
-        uint8_t* lds_row = lds_codes + (size_t)i * ROW_CODE_BYTES;
+        uint8_t* lds_row = lds_codes + (size_t)li * ROW_CODE_BYTES;
         float* dout = a.delta + (uint64_t)i * a.ld + col0 + 4 * lane;
 
         if constexpr (SUB) {
-            compress_sub_blocks<FULL>(a, i, col0, lane, v, msg_row, lds_row, lds_units, dout);
+            compress_sub_blocks<FULL>(a, i, li, col0, lane, v, msg_row, lds_row, lds_units, dout);
             return;
         }
 #pragma unroll
@@ -281,7 +345,7 @@ struct Tile {
                 const float unit = scale / (float)L;
                 const float inv = (scale > 0.f) ? hl / scale : 0.f;
                 if (lane == 0) {
-                    lds_units[i * BPT + b] = unit;
+                    lds_units[li * BPT + b] = unit;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
 #pragma unroll
@@ -330,7 +394,7 @@ struct Tile {
                     for (int s = 0; s + w < SPB; s += 2 * w) part[s] = part[s] + part[s + w];
                 const float scale = block_live ? part[0] / (float)m : 0.f;
                 if (lane == 0) {
-                    lds_units[i * BPT + b] = scale;
+                    lds_units[li * BPT + b] = scale;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
 #pragma unroll
@@ -570,7 +634,7 @@ struct Tile {
 #pragma unroll
             for (int r = 0; r < RPW; ++r) {
                 const int i = wave + r * NW;
-                if (i < a.n) compress_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh[r]);
+                if (i < a.n) compress_row<FULL>(a, i, i, col0, lane, lds_codes, lds_units, xh[r]);
             }
             park_graph();
             __syncthreads();
@@ -583,7 +647,7 @@ struct Tile {
             float4 xh[SW];
             for (int r = 0; r < rpw_runtime; ++r) {
                 const int i = wave + r * NW;
-                if (i < a.n) compress_row<FULL>(a, i, col0, lane, lds_codes, lds_units, xh);
+                if (i < a.n) compress_row<FULL>(a, i, i, col0, lane, lds_codes, lds_units, xh);
             }
             park_graph();
             __syncthreads();
@@ -727,6 +791,114 @@ __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int r
     }
 }
 
+// ---- row-streaming variant: every wave takes one (row, tile) on its own ----------------------------
+// Phase 1 of the fused kernel, preceded by the PREVIOUS step's line 9 decoded from that step's messages
+// in HBM, and followed by the store of x - gamma g.  No barrier and no LDS exchange, so any number of
+// workers fits; the price is reading (degree + 1) code streams per column (mostly cache hits) and a
+// deferred gossip sum that readers of x must flush.
+template <int KIND, int BITS, int B, int SW, int NW>
+__device__ __forceinline__ void step_counter_bump(const TileArgs& a, unsigned long long linear_block, unsigned long long blocks, bool set_pending) {
+    if (threadIdx.x == 0) {
+        const unsigned cell = (unsigned)(linear_block & 63u);
+        const unsigned long long members = (blocks >> 6) + (cell < (blocks & 63u) ? 1u : 0u);
+        unsigned long long* cnt = a.t_ptr + 32ull * (1 + cell);
+        if (__hip_atomic_fetch_add(cnt, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == members - 1ull) {
+            __hip_atomic_store(cnt, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long cells = blocks < 64u ? blocks : 64u;
+            unsigned long long* done = a.t_ptr + 1;
+            if (__hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == cells - 1ull) {
+                __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(a.t_ptr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (set_pending) __hip_atomic_store(a.pending, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+template <int KIND, int BITS, int B, int SW, int NW, bool FLUSH>
+__global__ void __launch_bounds__(NW* kWave) stream_tile_kernel(TileArgs a) {
+    using T = Tile<KIND, BITS, B, SW, NW>;
+    extern __shared__ __align__(16) uint8_t lds[];            // what phase 1 leaves for a gossip phase: unused here
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned long long t = a.t_ptr[0];
+    a.msg_prev = a.msg + ((t & 1ull) ^ 1ull) * a.msg_half;    // in a flush t has advanced: the same half
+    a.msg = a.msg + (t & 1ull) * a.msg_half;
+    const uint64_t tile = (uint64_t)blockIdx.y * gridDim.x + blockIdx.x;
+    const uint64_t col0 = tile * T::TC;
+    const int row = blockIdx.z * NW + wave;
+    if (row < a.n && col0 < a.N) {
+        const bool full = col0 + T::TC <= a.N;
+        float* xr = a.x + (uint64_t)row * a.ld + col0 + 4 * lane;
+        float4 xh[SW];
+        if constexpr (FLUSH) {
+            if (*a.pending != 0u) {
+#pragma unroll
+                for (int s = 0; s < SW; ++s) xh[s] = ld4(xr + s * kSweep);
+                if (full) T::template gossip_from_messages<true>(a, row, col0, lane, xh);
+                else      T::template gossip_from_messages<false>(a, row, col0, lane, xh);
+#pragma unroll
+                for (int s = 0; s < SW; ++s) st4(xr + s * kSweep, xh[s]);
+            }
+        } else {
+            uint8_t* lds_codes = lds;
+            float* lds_units = reinterpret_cast<float*>(lds + (size_t)NW * T::ROW_CODE_BYTES);
+            if (full) T::template compress_row<true, true>(a, row, wave, col0, lane, lds_codes, lds_units, xh);
+            else      T::template compress_row<false, true>(a, row, wave, col0, lane, lds_codes, lds_units, xh);
+#pragma unroll
+            for (int s = 0; s < SW; ++s) st4(xr + s * kSweep, xh[s]);      // x - gamma g; padding columns come out as zero
+        }
+    }
+    if constexpr (!FLUSH) {
+        __syncthreads();                                      // every wave of the workgroup has read t and pending
+        const unsigned long long blocks = (unsigned long long)gridDim.x * gridDim.y * gridDim.z;
+        step_counter_bump<KIND, BITS, B, SW, NW>(a, ((unsigned long long)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x, blocks, true);
+    }
+}
+
+__global__ void clear_pending_kernel(uint32_t* pending) { *pending = 0u; }
+
+template <int KIND, int BITS, int B, int SW, int NW, bool FLUSH>
+void launch_stream(const TileArgs& a, hipStream_t stream) {
+    using T = Tile<KIND, BITS, B, SW, NW>;
+    const uint64_t tiles = (a.N + T::TC - 1) / T::TC;
+    const uint64_t max_x = 0xFFFFFFFFull / (NW * kWave);
+    const unsigned gx = (unsigned)(tiles < max_x ? tiles : max_x);
+    const unsigned gy = (unsigned)((tiles + gx - 1) / gx);
+    const unsigned gz = (unsigned)((a.n + NW - 1) / NW);
+    const size_t lds = FLUSH ? 0 : (size_t)NW * (T::ROW_CODE_BYTES + T::BPT * sizeof(float));
+    hipLaunchKernelGGL((stream_tile_kernel<KIND, BITS, B, SW, NW, FLUSH>), dim3(gx, gy, gz), dim3(NW * kWave), lds, stream, a);
+    if (FLUSH) hipLaunchKernelGGL(clear_pending_kernel, dim3(1), dim3(1), 0, stream, a.pending);
+}
+
+template <int KIND, int BITS, int B>
+TilePlan make_stream_plan() {
+    constexpr int SW = B <= kSweep ? 1 : B / kSweep, NW = 4;
+    TilePlan p;
+    p.name = "stream/4w";
+    p.launch = [](const TileArgs& a, int, hipStream_t s) { launch_stream<KIND, BITS, B, SW, NW, false>(a, s); };
+    p.flush = [](const TileArgs& a, hipStream_t s) { launch_stream<KIND, BITS, B, SW, NW, true>(a, s); };
+    p.tile_cols = SW * kSweep;
+    p.waves = NW;
+    p.rows_per_wave = 1;
+    p.sweeps = SW;
+    p.streaming = true;
+    return p;
+}
+
+template <int KIND, int BITS>
+bool stream_plan_for_block(int block, TilePlan& plan) {
+    switch (block) {
+        case 64:   plan = make_stream_plan<KIND, BITS, 64>(); return true;
+        case 128:  plan = make_stream_plan<KIND, BITS, 128>(); return true;
+        case 256:  plan = make_stream_plan<KIND, BITS, 256>(); return true;
+        case 512:  plan = make_stream_plan<KIND, BITS, 512>(); return true;
+        case 1024: plan = make_stream_plan<KIND, BITS, 1024>(); return true;
+        case 2048: plan = make_stream_plan<KIND, BITS, 2048>(); return true;
+        default: return false;
+    }
+}
+
 template <int KIND, int BITS, int B, int SW, int NW, int RPW>
 void launch_tile(const TileArgs& a, int rpw_runtime, hipStream_t stream) {
     using T = Tile<KIND, BITS, B, SW, NW>;
@@ -845,6 +1017,13 @@ void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group
     hipLaunchKernelGGL(keep_count_if_stale_kernel, dim3((unsigned)(want < 512 ? want : 512), a.n), dim3(256), 0, stream, a);
     hipLaunchKernelGGL(keep_local_scan_kernel, dim3((unsigned)((a.nsweeps + 255) / 256), a.n), dim3(256), 0, stream, a, local_off, group_tot);
     hipLaunchKernelGGL(keep_scan_kernel, dim3(a.n), dim3(1024), 0, stream, a, group_tot, prev_count, overflow);
+}
+
+bool stream_plan(const ds_config& cfg, TilePlan& plan) {
+    if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 4) return stream_plan_for_block<DS_COMP_QUANT_MAXABS, 4>(cfg.comp.block, plan);
+    if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 2) return stream_plan_for_block<DS_COMP_QUANT_MAXABS, 2>(cfg.comp.block, plan);
+    if (cfg.comp.kind == DS_COMP_SIGN_MEANABS) return stream_plan_for_block<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, plan);
+    return false;
 }
 
 bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plan, std::string& err) {

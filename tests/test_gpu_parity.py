@@ -503,7 +503,7 @@ def test_topk_ties_take_the_lower_index():
 def test_api_errors_and_restart():
     w = small(wl.KIND_QUANT_MAXABS, 8, 512 * 4 + 3, bits=4, block=512)
     ds = b.DeepSqueeze.from_workload(w)
-    assert ds.ds_plan_name().startswith("tile/")
+    assert ds.ds_plan_name().startswith(("tile/", "stream/"))
     buf = np.empty(b.ds_message_bytes(ds.cfg), np.uint8)
     import ctypes
     assert b.lib().ds_read_messages(ds._h, buf.ctypes.data, buf.size, None) == b.DS_ESTATE
@@ -715,6 +715,49 @@ def test_free_run_with_gradients_drawn_on_the_device():
         c = dg.centres(w.n, w.N, w.seed)
         assert np.abs(x.mean(0) - c.mean(0)).mean() < 0.2 * np.abs(c.mean(0)).mean()
         ds.ds_destroy()
+
+
+STREAM_CASES = [small(wl.KIND_QUANT_MAXABS, 8, 512 * 5 + 37, bits=4, block=512),
+                small(wl.KIND_QUANT_MAXABS, 16, 64 * 70 + 9, bits=2, block=64, topo=wl.TOPO_TORUS2D, torus=(4, 4)),
+                small(wl.KIND_QUANT_MAXABS, 6, 1024 * 3 + 1000, bits=2, block=1024),
+                small(wl.KIND_SIGN_MEANABS, 12, 2048 * 2 + 5, block=2048),
+                small(wl.KIND_SIGN_MEANABS, 5, 128 * 9 + 3, block=128)]
+
+
+@pytest.mark.parametrize("w", STREAM_CASES, ids=lambda w: w.name)
+def test_row_streaming_variant(w, monkeypatch):
+    """DSQ_STREAM=1 selects the row-streaming kernels of the block compressors (no LDS exchange; the gossip sum of
+    a step is added by the next step's pass from the previous messages, which live in the other half of a double
+    buffer): lock-step, then a free run whose messages are compared after every step."""
+    monkeypatch.setenv("DSQ_STREAM", "1")
+    ds = b.DeepSqueeze.from_workload(w)
+    assert ds.ds_plan_name().startswith("stream/"), ds.ds_plan_name()
+    ds.ds_destroy()
+    lock_step(w, steps=3)
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w)
+    for t in range(7):
+        g = wl.gradient(w, t)
+        ds.ds_step(upload(g))
+        _, msg = oracle.step(st, g, want_cv=False)
+        assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name} step {t}: messages differ"
+        if t == 3:                                           # a read in the middle flushes; the run goes on
+            x, d = ds.ds_read_state()
+            assert assert_close("x mid", x, st.x) + assert_close("delta mid", d, st.delta) == 0
+    x, d = ds.ds_read_state()
+    assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+    ds.ds_destroy()
+
+
+@pytest.mark.parametrize("w", [small(wl.KIND_QUANT_MAXABS, 700, 512 * 2 + 77, bits=4, block=512),
+                               small(wl.KIND_SIGN_MEANABS, 1300, 2048 + 5, block=2048)], ids=lambda w: w.name)
+def test_more_workers_than_fit_in_lds(w):
+    """The fused tile kernel keeps the codes of all n rows of a tile in LDS; beyond that (here 700 and 1300
+    workers) ds_init falls back to the row-streaming kernels by itself."""
+    ds = b.DeepSqueeze.from_workload(w)
+    assert ds.ds_plan_name().startswith("stream/"), ds.ds_plan_name()
+    ds.ds_destroy()
+    lock_step(w, steps=2)
 
 
 def test_step_on_a_side_stream_and_determinism():
