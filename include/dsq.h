@@ -126,7 +126,12 @@ uint64_t ds_message_bytes(const ds_config* cfg);
 
 /* Creates the state on the current HIP device: x = 0, delta = 0, t = 0 (Algorithm 1, line 1;
  * Assumption 1.4).  Allocates x, delta (n rows with an internal pitch), the message buffer and
- * scratch with hipMalloc.  *out is NULL on failure. */
+ * scratch with hipMalloc.  *out is NULL on failure.
+ * For large problems (n*N >= 32 Mi) of the block compressors the call times the candidate launch
+ * shapes and row pitches of the fused kernel on the (still zero) state and keeps the fastest; the
+ * choice is reported by ds_plan_name.  Environment, read here: DSQ_TILE_PLAN=<i> pins the i-th
+ * candidate shape, DSQ_PITCH_SKEW=<floats> the pitch, DSQ_STREAM=1 selects the row-streaming variant
+ * of the block compressors (it is also what serves more workers than the fused kernel's LDS holds). */
 ds_status ds_init(const ds_config* cfg, ds_handle** out);
 
 /* One iteration of Algorithm 1 (lines 5-9) for all n workers with the gradients g_dev.
