@@ -144,7 +144,8 @@ struct Tile {
     //      messages in HBM (row-streaming variant: nothing is shared through LDS): x = xh + eta sum_j a_ij C[v_j]
     template <bool FULL>
     static __device__ __forceinline__ void gossip_from_messages(const TileArgs& a, int i, uint64_t col0, int lane, float4 (&x)[SW]) {
-        static_assert(KIND == DS_COMP_QUANT_MAXABS || KIND == DS_COMP_SIGN_MEANABS, "messages of this operator cannot be decoded per column");
+        static_assert(KIND == DS_COMP_QUANT_MAXABS || KIND == DS_COMP_SIGN_MEANABS || KIND == DS_COMP_IDENTITY,
+                      "messages of this operator cannot be decoded per column");
         float acc[SW][4];
 #pragma unroll
         for (int s = 0; s < SW; ++s) acc[s][0] = acc[s][1] = acc[s][2] = acc[s][3] = 0.f;
@@ -157,6 +158,15 @@ struct Tile {
             for (int s = 0; s < SW; ++s) {
                 const uint64_t j = col0 + (uint64_t)s * kSweep + 4 * lane;
                 if (!FULL && j >= a.N) continue;                // no message bytes exist for these columns
+                if constexpr (KIND == DS_COMP_IDENTITY) {       // the message is v itself
+                    const float* vrow = reinterpret_cast<const float*>(nrow);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const float cv = (FULL || j + c < a.N) ? vrow[j + c] : 0.f;
+                        acc[s][c] = fmaf(w, cv, acc[s][c]);
+                    }
+                    continue;
+                }
                 const uint64_t bcol0 = SUB ? col0 + (uint64_t)s * kSweep + (uint64_t)(lane / G) * B
                                            : col0 + (uint64_t)(s / SPB) * B;
                 const uint8_t* blk = nrow + (bcol0 / B) * MSG_BLOCK_BYTES;
@@ -1023,6 +1033,7 @@ bool stream_plan(const ds_config& cfg, TilePlan& plan) {
     if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 4) return stream_plan_for_block<DS_COMP_QUANT_MAXABS, 4>(cfg.comp.block, plan);
     if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 2) return stream_plan_for_block<DS_COMP_QUANT_MAXABS, 2>(cfg.comp.block, plan);
     if (cfg.comp.kind == DS_COMP_SIGN_MEANABS) return stream_plan_for_block<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, plan);
+    if (cfg.comp.kind == DS_COMP_IDENTITY) { plan = make_stream_plan<DS_COMP_IDENTITY, 32, 512>(); return true; }
     return false;
 }
 

@@ -721,7 +721,8 @@ STREAM_CASES = [small(wl.KIND_QUANT_MAXABS, 8, 512 * 5 + 37, bits=4, block=512),
                 small(wl.KIND_QUANT_MAXABS, 16, 64 * 70 + 9, bits=2, block=64, topo=wl.TOPO_TORUS2D, torus=(4, 4)),
                 small(wl.KIND_QUANT_MAXABS, 6, 1024 * 3 + 1000, bits=2, block=1024),
                 small(wl.KIND_SIGN_MEANABS, 12, 2048 * 2 + 5, block=2048),
-                small(wl.KIND_SIGN_MEANABS, 5, 128 * 9 + 3, block=128)]
+                small(wl.KIND_SIGN_MEANABS, 5, 128 * 9 + 3, block=128),
+                small(wl.KIND_IDENTITY, 7, 512 * 3 + 5)]
 
 
 @pytest.mark.parametrize("w", STREAM_CASES, ids=lambda w: w.name)
@@ -750,7 +751,8 @@ def test_row_streaming_variant(w, monkeypatch):
 
 
 @pytest.mark.parametrize("w", [small(wl.KIND_QUANT_MAXABS, 700, 512 * 2 + 77, bits=4, block=512),
-                               small(wl.KIND_SIGN_MEANABS, 1300, 2048 + 5, block=2048)], ids=lambda w: w.name)
+                               small(wl.KIND_SIGN_MEANABS, 1300, 2048 + 5, block=2048),
+                               small(wl.KIND_IDENTITY, 200, 1000)], ids=lambda w: w.name)
 def test_more_workers_than_fit_in_lds(w):
     """The fused tile kernel keeps the codes of all n rows of a tile in LDS; beyond that (here 700 and 1300
     workers) ds_init falls back to the row-streaming kernels by itself."""
