@@ -476,6 +476,37 @@ def test_all_zero_and_denormal_blocks():
         assert_close("delta", dg, st.delta)
 
 
+def test_negative_zeros():
+    # the sign compressor sends the IEEE sign bit, so -0.0 counts as negative; a zero keeps its sign through
+    # v = (x - gamma g) + delta only if delta's zero has it too
+    N = 300
+    r = np.random.default_rng(12)
+    x0 = r.standard_normal((4, N)).astype(np.float32)
+    d0 = np.zeros((4, N), np.float32)
+    x0[:, ::3] = -0.0
+    d0[:, ::6] = -0.0
+    x0[1] = -0.0
+    d0[1] = -0.0                                               # a block of negative zeros: scale 0, all bits set
+    for w in (small(wl.KIND_SIGN_MEANABS, 4, N, block=256, gamma=0.0), small(wl.KIND_SIGN_MEANABS, 4, N, block=64, gamma=0.0),
+              small(wl.KIND_QUANT_MAXABS, 4, N, bits=2, block=128, gamma=0.0), small(wl.KIND_TOPK, 4, N, k=150, gamma=0.0),
+              small(wl.KIND_QUANT_L2NORM, 4, N, bits=4, gamma=0.0), small(wl.KIND_RAND_SPARSE, 4, N, k=150, gamma=0.0)):
+        say("case", w.name)
+        ds = b.DeepSqueeze.from_workload(w)
+        st = oracle_state(w, x=x0.copy(), delta=d0.copy())
+        ds.ds_write_state(x0, d0, 0)
+        g = np.zeros((4, N), np.float32)
+        ds.ds_step(upload(g))
+        _, msg = oracle.step(st, g, want_cv=False)
+        assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name}: messages differ"
+        x, d = ds.ds_read_state()
+        if w.kind == wl.KIND_TOPK:                             # top-k writes x = xh + 0: -0 becomes +0 (documented)
+            assert np.array_equal(x, st.x) and np.array_equal(d, st.delta)
+        else:
+            assert np.array_equal(x.view(np.uint32), st.x.view(np.uint32)), f"{w.name}: x differs bitwise"
+            assert np.array_equal(d.view(np.uint32), st.delta.view(np.uint32)), f"{w.name}: delta differs bitwise"
+        ds.ds_destroy()
+
+
 def test_topk_ties_take_the_lower_index():
     w = small(wl.KIND_TOPK, 3, 20_000, k=333)
     ds = b.DeepSqueeze.from_workload(w)

@@ -470,6 +470,28 @@ def test_rand_sparse_mask_rule_message_and_residual():
     assert oracle.rand_sparse_capacity(50, 40) == 50            # never more than N
 
 
+def test_rand_sparse_threshold_is_strict():
+    # keep iff (word >> 8) < T, T = floor(k 2^24 / N): with N = 4096, T = 4096 k; find an element whose 24 bits
+    # ARE a multiple of 4096 and give it exactly that T: it must be dropped (an off-by-one T would keep it)
+    N, found = 4096, 0
+    for seed in range(60):
+        tops = np.array([oracle.keep_word(seed, 0, 0, j) >> 8 for j in range(N)])
+        hits = np.nonzero((tops % 4096 == 0) & (tops >= 4096))[0]
+        if hits.size == 0:
+            continue
+        j = int(hits[0])
+        k = int(tops[j]) // 4096
+        v = np.arange(1, N + 1, dtype=np.float32)[None, :]
+        st = OracleState(n=1, N=N, W=np.ones((1, 1)), kind=KIND_RAND_SPARSE, k=k, gamma=0.0, eta=0.5, seed=seed, x=v.copy())
+        cv, _ = oracle.step(st, np.zeros_like(v), want_msg=False)
+        assert cv[0, j] == 0 and st.delta[0, j] == v[0, j]
+        np.testing.assert_array_equal(cv[0] != 0, tops < 4096 * k)
+        found += 1
+        if found == 3:
+            break
+    assert found == 3
+
+
 def test_rand_sparse_rate_independence_and_signal_to_noise():
     # keep rate = floor(k 2^24 / N) / 2^24 within 5 sigma; masks of different workers and steps are unrelated;
     # |C[v] - v|^2 / |v|^2 averages to 1 - p: the alpha^2 of Assumption 1.6
@@ -611,6 +633,17 @@ def test_sign_scale_is_block_mean_and_contracts(N, block):
         # Assumption 1.6 holds deterministically: |v - C|^2 = |v|^2 - m s^2 <= (1 - 1/m) |v|^2
         err = ((blk - cv[0, j0:j0 + block]) ** 2).sum()
         assert err <= (1 - 1.0 / len(blk)) * (blk ** 2).sum() + 1e-12
+
+
+def test_sign_of_negative_zero_is_negative():
+    # the code is the IEEE sign bit: -0.0 is sent as "negative" and decodes to -scale
+    v = np.array([[1.0, -0.0, 0.0, -3.0]], dtype=np.float32)
+    # (v = (x - gamma g) + delta keeps the sign of a zero only if delta's zero has it too: -0 + +0 = +0)
+    d = np.array([[0.0, -0.0, 0.0, 0.0]], dtype=np.float32)
+    st = OracleState(n=1, N=4, W=np.ones((1, 1)), kind=KIND_SIGN_MEANABS, block=4, gamma=0.0, eta=0.5, x=v.copy(), delta=d)
+    cv, msg = oracle.step(st, np.zeros_like(v))
+    np.testing.assert_array_equal(cv[0], np.float32([1.0, -1.0, 1.0, -1.0]))
+    assert np.frombuffer(msg[4:8].tobytes(), np.uint32)[0] == 0b1010 and np.frombuffer(msg[:4].tobytes(), np.float32)[0] == 1.0
 
 
 def test_sign_fp32_sum_is_the_pairwise_tree():
