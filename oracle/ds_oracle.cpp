@@ -23,6 +23,11 @@
 // floating-point evaluation order used for `real = float`, are this
 // repository's readings; every one is stated next to the code that does it.
 //
+// Every function below is pinned by tests/test_oracle_pins.py against what the
+// paper and plain mathematics fix.  What nothing available can fix is the CHOICE
+// of the operators' grids, rounding and tie rules where the paper is silent
+// (against the authors' unpublished code that choice is "parity unpinned").
+//
 // Everything is templated on `real`: double is used to check the algebraic
 // identities the paper states, float (same expression order as the GPU
 // kernels, contraction off, explicit fma) is used for bit-level parity.
