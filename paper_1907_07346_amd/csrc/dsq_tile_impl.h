@@ -1,4 +1,6 @@
-// Fused compress-and-gossip tile kernels for the block compressors of libdsq (gfx950).
+// Fused compress-and-gossip tile kernels for the block compressors of libdsq (gfx950): the templates.
+// Included by the dsq_tile_*.hip translation units, which instantiate them per compressor (side by side
+// at build time).
 //
 // One workgroup owns a tile of TC consecutive parameter columns for ALL n workers.
 // Because every scale block is column-local and the mixing matrix W only couples
@@ -16,6 +18,8 @@
 // Traffic per worker-parameter: 12 B read (x, g, delta), 8 B written (x, delta) plus the
 // packed message.  The floating-point expression order below is fixed (contraction off,
 // explicit fmaf) so that codes, scales and messages are reproducible bit for bit.
+
+#pragma once
 
 #include "dsq_internal.h"
 
@@ -1018,42 +1022,4 @@ bool pick_for_kind(int block, int n, int nnz, std::vector<TilePlan>& plan, std::
 }
 
 }  // namespace
-
-static_assert(kKeepGroup == 16, "the tile kernel finds a sweep's group with a shift by 4");
-
-void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group_tot, uint32_t* prev_count, uint32_t* overflow,
-                         hipStream_t stream) {
-    const uint64_t want = (a.nsweeps + 3) / 4;
-    hipLaunchKernelGGL(keep_count_if_stale_kernel, dim3((unsigned)(want < 512 ? want : 512), a.n), dim3(256), 0, stream, a);
-    hipLaunchKernelGGL(keep_local_scan_kernel, dim3((unsigned)((a.nsweeps + 255) / 256), a.n), dim3(256), 0, stream, a, local_off, group_tot);
-    hipLaunchKernelGGL(keep_scan_kernel, dim3(a.n), dim3(1024), 0, stream, a, group_tot, prev_count, overflow);
-}
-
-bool stream_plan(const ds_config& cfg, TilePlan& plan) {
-    if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 4) return stream_plan_for_block<DS_COMP_QUANT_MAXABS, 4>(cfg.comp.block, plan);
-    if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 2) return stream_plan_for_block<DS_COMP_QUANT_MAXABS, 2>(cfg.comp.block, plan);
-    if (cfg.comp.kind == DS_COMP_SIGN_MEANABS) return stream_plan_for_block<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, plan);
-    if (cfg.comp.kind == DS_COMP_IDENTITY) { plan = make_stream_plan<DS_COMP_IDENTITY, 32, 512>(); return true; }
-    return false;
-}
-
-bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plan, std::string& err) {
-    switch (cfg.comp.kind) {
-        case DS_COMP_QUANT_MAXABS:
-            if (cfg.comp.bits == 4) return pick_for_kind<DS_COMP_QUANT_MAXABS, 4>(cfg.comp.block, cfg.n, nnz, plan, err);
-            if (cfg.comp.bits == 2) return pick_for_kind<DS_COMP_QUANT_MAXABS, 2>(cfg.comp.block, cfg.n, nnz, plan, err);
-            err = "bits must be 2 or 4";
-            return false;
-        case DS_COMP_SIGN_MEANABS:
-            return pick_for_kind<DS_COMP_SIGN_MEANABS, 1>(cfg.comp.block, cfg.n, nnz, plan, err);
-        case DS_COMP_IDENTITY:
-            return pick_for_block<DS_COMP_IDENTITY, 32, 512>(cfg.n, nnz, plan, err);
-        case DS_COMP_RAND_SPARSE:
-            return pick_for_block<DS_COMP_RAND_SPARSE, 32, 512>(cfg.n, nnz, plan, err);
-        default:
-            err = "no tile kernel for this compressor";
-            return false;
-    }
-}
-
 }  // namespace dsq
