@@ -437,14 +437,26 @@ ds_status ds_set_rates(ds_handle* h, float gamma, float eta) {
     return DS_OK;
 }
 
+// Dense host array <-> pitched device rows.  Rows of more than 1 GiB go one by one (2-D copies of such widths
+// are not something every runtime version handles).
+static hipError_t copy_rows(void* dst, size_t dst_pitch, const void* src, size_t src_pitch, size_t row_bytes, int rows, hipMemcpyKind kind) {
+    if (row_bytes <= (1ull << 30)) return hipMemcpy2D(dst, dst_pitch, src, src_pitch, row_bytes, rows, kind);
+    for (int i = 0; i < rows; ++i) {
+        const hipError_t e = hipMemcpy(static_cast<char*>(dst) + (size_t)i * dst_pitch, static_cast<const char*>(src) + (size_t)i * src_pitch,
+                                       row_bytes, kind);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host) {
     if (!h) return DS_EINVAL;
     if (!x_host && !delta_host) return fail(h, DS_EINVAL, "nothing to read");
     if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
-    if (x_host) DSQ_HIP(h, hipMemcpy2D(x_host, row, h->x, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
-    if (delta_host) DSQ_HIP(h, hipMemcpy2D(delta_host, row, h->delta, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
+    if (x_host) DSQ_HIP(h, copy_rows(x_host, row, h->x, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
+    if (delta_host) DSQ_HIP(h, copy_rows(delta_host, row, h->delta, pitch, row, h->cfg.n, hipMemcpyDeviceToHost));
     return DS_OK;
 }
 
@@ -453,8 +465,8 @@ ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_h
     if (flush_deferred(h) != DS_OK) return fail(h, DS_EHIP, "applying the deferred tail of the last step failed");
     DSQ_HIP(h, hipStreamSynchronize(h->last_stream));
     const size_t row = h->cfg.N * sizeof(float), pitch = h->ld * sizeof(float);
-    if (x_host) DSQ_HIP(h, hipMemcpy2D(h->x, pitch, x_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
-    if (delta_host) DSQ_HIP(h, hipMemcpy2D(h->delta, pitch, delta_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
+    if (x_host) DSQ_HIP(h, copy_rows(h->x, pitch, x_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
+    if (delta_host) DSQ_HIP(h, copy_rows(h->delta, pitch, delta_host, row, row, h->cfg.n, hipMemcpyHostToDevice));
     const unsigned long long t64 = t;
     DSQ_HIP(h, hipMemcpy(h->d_t, &t64, sizeof(t64), hipMemcpyHostToDevice));
     DSQ_HIP(h, hipDeviceSynchronize());

@@ -985,6 +985,12 @@ def test_vectors_longer_than_2_31_columns_block_operators(kind, bits, block, mon
         # the padding behind column N-1 stays zero
         assert float(X[:, N:].abs().max()) == 0.0 and float(D[:, N:].abs().max()) == 0.0
         del X, D, M
+        if plan == 0 and kind == wl.KIND_SIGN_MEANABS:
+            # the dense host copy of such rows (8.6 GB each) goes through ds_read_state too
+            xh, _ = ds.ds_read_state(want_delta=False)
+            for c0, c1, st, _ in windows:
+                assert assert_close(f"read_state x[{c0}:{c1}]", xh[:, c0:c1], st.x) == 0
+            del xh
         ds.ds_destroy()
     assert len(seen) >= 2, seen
 
