@@ -95,7 +95,7 @@ typedef struct {
     float    gamma;           /* learning rate                                                   */
     float    eta;             /* averaging rate; the paper's Theorem 1 wants eta <= 1/2: a larger */
                               /* value is accepted and noted in ds_last_error                    */
-    uint64_t seed;            /* key of the stochastic-rounding random stream                    */
+    uint64_t seed;            /* key of the random streams (stochastic rounding, sparsifier mask) */
 } ds_config;
 
 /* ---- host-only helpers (no GPU needed) ------------------------------------------------------ */
@@ -119,6 +119,12 @@ ds_status ds_build_topology(const ds_config* cfg, int32_t* rowptr, int32_t* col,
  *                 SIGN bit 1 means negative and decodes to -scale; unused high bits are 0.
  *   TOPK:         k pairs (u32 index, f32 value) in ascending index order.
  *   IDENTITY:     N fp32 values.
+ *   QUANT_L2NORM: [f32 norm][ceil(N*b/32) u32 words], codes packed as for QUANT; code q stands for the odd
+ *                 integer y = 2q - (2^b-1) and the receiver returns y * (norm / sqrt(sum of y^2)).
+ *   RAND_SPARSE:  [u32 count][count f32 values in ascending column order], zero-padded to the fixed capacity
+ *                 min(N, k + 8 ceil(sqrt k) + 64) values; which columns were kept follows from the seed
+ *                 (Philox4x32-10, counter (floor(j/4), i, t, 'SPAR'), word j mod 4, kept iff
+ *                 (word >> 8) < floor(k 2^24 / N)).
  * Returns 0 for an invalid configuration. */
 uint64_t ds_message_bytes(const ds_config* cfg);
 
