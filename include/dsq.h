@@ -188,8 +188,9 @@ ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t*
 
 /* Borrows the device arrays: row i of x starts at x_dev + i*ld.  Ownership stays with the
  * handle; columns >= N of each row are padding the caller must leave zero.  The contents are
- * complete once the work enqueued so far on the stream of the last ds_step has finished (with
- * DS_COMP_TOPK this call itself enqueues the last sparse update of x on that stream); call it
+ * complete once the work enqueued so far on the stream of the last ds_step has finished (top-k,
+ * the norm-rescaled codes and the row-streaming plans leave the last part of a step's update of x
+ * and delta to the next step's first pass: this call enqueues it on that stream instead); call it
  * again after later steps before reading x. */
 ds_status ds_state_ptrs(ds_handle* h, float** x_dev, float** delta_dev, uint64_t* ld);
 
