@@ -86,6 +86,8 @@ def main():
 
     import torch
 
+    from paper_1907_07346_amd.build import ensure_built
+    ensure_built()
     from paper_1907_07346_amd import binding as b
     from paper_1907_07346_amd import workloads as wl
 

@@ -40,5 +40,10 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+def ensure_built(verbose: bool = False) -> str:
+    """Builds the library only if no built one is there (tests, the smoke check and the benchmark call this)."""
+    return LIB if os.path.exists(LIB) else build(verbose=verbose)
+
+
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])
