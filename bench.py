@@ -110,10 +110,22 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     copy_gbs = 2 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del src, dst
+    # ... and the access mix of ds_step without its arithmetic: 3 streaming loads, 2 stores, in place
+    third = torch.zeros_like(src)
+    dst.zero_()
+    for _ in range(3):
+        b.ds_bench_stream(dst, third, src)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        b.ds_bench_stream(dst, third, src)
+    e1.record()
+    torch.cuda.synchronize()
+    mix_gbs = 5 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst, third
     torch.cuda.empty_cache()
     if args.copy_only:
-        print(json.dumps({"copy_GBps": copy_gbs, "bytes_per_launch": 2 * nbytes}))
+        print(json.dumps({"copy_GBps": copy_gbs, "bytes_per_launch": 2 * nbytes, "stream_3r2w_GBps": mix_gbs}))
         return
 
     ds = b.DeepSqueeze.from_workload(w)
@@ -176,7 +188,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_param": beta, "device_ms_per_step": dev_ms / K, "plain_copy_GBps": copy_gbs,
-                     "frac_of_plain_copy": achieved / copy_gbs},
+                     "frac_of_plain_copy": achieved / copy_gbs, "stream_3r2w_GBps": mix_gbs,
+                     "frac_of_3r2w_stream": achieved / mix_gbs},
     }
     ds.ds_destroy()
     del gs

@@ -252,6 +252,12 @@ ds_status ds_workload_gradient(const ds_workload* w, uint64_t t, const float* x_
  * calibrate the hardware traffic counters against a known byte count.  DS_EINVAL for bytes >= 64 GiB. */
 ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream);
 
+/* Measurement aid, not part of the method: the access mix of ds_step without its arithmetic -- per 16 bytes
+ * three streaming loads (x, delta, g) and two stores (x += g, delta += g, in place) -- over three device arrays of
+ * `bytes` each (a multiple of 16, 16-byte aligned), enqueued on hip_stream.  5 * bytes move per call.
+ * DS_EINVAL for bytes >= 64 GiB. */
+ds_status ds_bench_stream(void* x_dev, void* delta_dev, const void* g_dev, uint64_t bytes, void* hip_stream);
+
 /* Frees everything the handle owns (synchronises first).  NULL is a no-op. */
 void ds_destroy(ds_handle* h);
 

@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
            "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
-           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient"]
+           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient", "ds_bench_stream"]
 
 
 class ds_comp(ctypes.Structure):
@@ -86,6 +86,7 @@ def lib() -> ctypes.CDLL:
         L.ds_last_error.argtypes, L.ds_last_error.restype = [vp], ctypes.c_char_p
         L.ds_destroy.argtypes, L.ds_destroy.restype = [vp], None
         L.ds_bench_copy.argtypes, L.ds_bench_copy.restype = [vp, vp, u64, vp], i32
+        L.ds_bench_stream.argtypes, L.ds_bench_stream.restype = [vp, vp, vp, u64, vp], i32
         _lib = L
     return _lib
 
@@ -160,6 +161,17 @@ def ds_bench_copy(dst: "torch.Tensor", src: "torch.Tensor", stream=None):
     st = lib().ds_bench_copy(dst.data_ptr(), src.data_ptr(), nbytes, s.cuda_stream)
     if st != DS_OK:
         raise DsqError(st, "ds_bench_copy")
+
+
+def ds_bench_stream(x: "torch.Tensor", d: "torch.Tensor", g: "torch.Tensor", stream=None):
+    """x += g, d += g with the library's 3-loads / 2-stores streaming kernel (the access mix of ds_step)."""
+    nbytes = x.numel() * x.element_size()
+    assert d.numel() * d.element_size() == nbytes and g.numel() * g.element_size() == nbytes
+    assert x.is_cuda and d.is_cuda and g.is_cuda
+    s = stream if stream is not None else torch.cuda.current_stream()
+    st = lib().ds_bench_stream(x.data_ptr(), d.data_ptr(), g.data_ptr(), nbytes, s.cuda_stream)
+    if st != DS_OK:
+        raise DsqError(st, "ds_bench_stream")
 
 
 class DeepSqueeze:

@@ -217,6 +217,19 @@ __global__ void __launch_bounds__(256) copy_kernel(f32x4* __restrict__ dst, cons
     if (i < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// The access mix of ds_step without its arithmetic: three 16-byte non-temporal loads and two stores per lane,
+// in place (x += g, delta += g): what a streaming kernel of this shape reaches on the same GPU.
+__global__ void __launch_bounds__(256) stream_3r2w_kernel(f32x4* __restrict__ x, f32x4* __restrict__ d, const f32x4* __restrict__ g, uint64_t n4) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) {
+        const f32x4 gv = __builtin_nontemporal_load(g + i);
+        const f32x4 xv = __builtin_nontemporal_load(x + i);
+        const f32x4 dv = __builtin_nontemporal_load(d + i);
+        __builtin_nontemporal_store(xv + gv, x + i);
+        __builtin_nontemporal_store(dv + gv, d + i);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -227,6 +240,18 @@ ds_status ds_workload_gradient(const ds_workload* w, uint64_t t, const float* x_
     if (w->kind < DS_GRAD_NORMAL || w->kind > DS_GRAD_QUADRATIC || !std::isfinite(w->scale)) return DS_EINVAL;
     if (w->kind == DS_GRAD_QUADRATIC && (!x_dev || x_ld < w->N)) return DS_EINVAL;
     return dsq::launch_workload_gradient(*w, t, x_dev, x_ld, g_dev, g_ld, static_cast<hipStream_t>(hip_stream));
+}
+
+ds_status ds_bench_stream(void* x_dev, void* delta_dev, const void* g_dev, uint64_t bytes, void* hip_stream) {
+    if (!x_dev || !delta_dev || !g_dev || (bytes & 15) ||
+        ((reinterpret_cast<uintptr_t>(x_dev) | reinterpret_cast<uintptr_t>(delta_dev) | reinterpret_cast<uintptr_t>(g_dev)) & 15))
+        return DS_EINVAL;
+    const uint64_t n4 = bytes / 16;
+    if (n4 == 0) return DS_OK;
+    if (n4 > 0xFFFFFF00ull) return DS_EINVAL;
+    hipLaunchKernelGGL(stream_3r2w_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<f32x4*>(x_dev), static_cast<f32x4*>(delta_dev), static_cast<const f32x4*>(g_dev), n4);
+    return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
 }
 
 ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void* hip_stream) {
