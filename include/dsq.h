@@ -50,7 +50,7 @@ typedef enum {
 typedef enum {
     DS_COMP_IDENTITY = 0,     /* C[v] = v: the step is plain D-PSGD; message = v in fp32        */
     DS_COMP_QUANT_MAXABS = 1, /* stochastic `bits`-bit uniform quantisation per block of `block` */
-                              /* elements, scale = max |v| of the block; bits in {2, 4}          */
+                              /* elements, scale = max |v| of the block; bits in {2, 4, 8}       */
     DS_COMP_SIGN_MEANABS = 2, /* sign bit per element, scale = mean |v| of the block            */
     DS_COMP_TOPK = 3,         /* the k largest |v| of each worker's whole vector, ties to the   */
                               /* lower index; message = k (u32 index, f32 value) pairs          */
@@ -61,7 +61,7 @@ typedef enum {
                               /* decodes.  Grid: 2^bits levels from -max|v| to +max|v|, nearest   */
                               /* level (ties to the even code); code q stands for y = 2q - L,     */
                               /* C[v] = y * (norm / ||y||_2).  Message per worker:                */
-                              /* [f32 norm][ceil(N*bits/32) u32 words]; bits in {2, 4}            */
+                              /* [f32 norm][ceil(N*bits/32) u32 words]; bits in {2, 4, 8}         */
     DS_COMP_RAND_SPARSE = 5   /* random sparsification (named next to top-k under Assumption 1.6): */
                               /* every element is kept independently with probability k/N (floor   */
                               /* to a multiple of 2^-24) and not rescaled; the mask comes from the  */
@@ -72,7 +72,7 @@ typedef enum {
 
 typedef struct {
     int32_t  kind;    /* ds_comp_kind */
-    int32_t  bits;    /* QUANT_MAXABS, QUANT_L2NORM: 2 or 4; otherwise ignored                  */
+    int32_t  bits;    /* QUANT_MAXABS, QUANT_L2NORM: 2, 4 or 8; otherwise ignored               */
     int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 64 <= block <= 2048           */
     int32_t  reserved;
     uint64_t k;       /* TOPK: 1 <= k <= N; RAND_SPARSE: expected kept elements per worker,     */

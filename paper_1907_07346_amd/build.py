@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdsq.so")
-SOURCES = ["dsq_tile_quant4.hip", "dsq_tile_quant2.hip", "dsq_tile_sign.hip", "dsq_tile_misc.hip", "dsq_host.cpp", "dsq_api.hip",
+SOURCES = ["dsq_tile_quant4.hip", "dsq_tile_quant2.hip", "dsq_tile_quant8.hip", "dsq_tile_sign.hip", "dsq_tile_misc.hip", "dsq_host.cpp", "dsq_api.hip",
            "dsq_topk_kernels.hip", "dsq_l2norm_kernels.hip", "dsq_workload_kernels.hip"]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is written out as fmaf, nothing else may fuse

@@ -62,7 +62,7 @@ ds_status validate_config(const ds_config* cfg, std::string& err, std::string* w
     switch (c.kind) {
         case DS_COMP_IDENTITY: break;
         case DS_COMP_QUANT_MAXABS:
-            if (c.bits != 2 && c.bits != 4) { err = "bits must be 2 or 4"; return DS_EINVAL; }
+            if (c.bits != 2 && c.bits != 4 && c.bits != 8) { err = "bits must be 2, 4 or 8"; return DS_EINVAL; }
             [[fallthrough]];
         case DS_COMP_SIGN_MEANABS:
             if (c.block < kMinBlock || c.block > kMaxBlock || !is_pow2((uint64_t)c.block)) {
@@ -73,7 +73,7 @@ ds_status validate_config(const ds_config* cfg, std::string& err, std::string* w
             if (c.k < 1 || c.k > cfg->N) { err = "k must be in [1, N]"; return DS_EINVAL; }
             break;
         case DS_COMP_QUANT_L2NORM:
-            if (c.bits != 2 && c.bits != 4) { err = "bits must be 2 or 4"; return DS_EINVAL; }
+            if (c.bits != 2 && c.bits != 4 && c.bits != 8) { err = "bits must be 2, 4 or 8"; return DS_EINVAL; }
             break;
         case DS_COMP_RAND_SPARSE:
             if (c.k < 1 || c.k > cfg->N) { err = "k (expected number of kept elements) must be in [1, N]"; return DS_EINVAL; }

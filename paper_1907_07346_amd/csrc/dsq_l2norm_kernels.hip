@@ -47,7 +47,7 @@ struct L2Scratch {
     L2Row* rows;                  // n
     float* cmax;                  // n x nchunks: max |v| of the chunk
     double* csq;                  // n x nchunks: tree sum of v^2 over the chunk
-    uint32_t* csy2;               // n x nchunks: sum of y^2 over the chunk (< 2^32: 4096 * 15^2)
+    uint32_t* csy2;               // n x nchunks: sum of y^2 over the chunk (< 2^32: 4096 * 255^2)
     uint32_t* pending;            // 1: the last step's tail has not been applied to x and delta yet
     uint32_t nchunks;
 };
@@ -66,7 +66,8 @@ __device__ __forceinline__ void st4_stream(float* p, const float4& v) {
 template <int BITS>
 __device__ __forceinline__ uint32_t load_codes4(const uint8_t* msg_row, uint64_t col) {
     if constexpr (BITS == 2) return msg_row[4 + (col >> 2)];
-    else return *reinterpret_cast<const uint16_t*>(msg_row + 4 + (col >> 1));
+    else if constexpr (BITS == 4) return *reinterpret_cast<const uint16_t*>(msg_row + 4 + (col >> 1));
+    else return *reinterpret_cast<const uint32_t*>(msg_row + 4 + col);
 }
 
 // Lines 6 (second half) and 9 of Algorithm 1 for four adjacent columns of worker `row`, from the
@@ -253,7 +254,8 @@ __global__ void __launch_bounds__(LQ_THREADS) l2q_quantize(L2Args a, L2Scratch s
             }
         }
         if constexpr (BITS == 2) mrow[4 + byte] = (uint8_t)packed;
-        else *reinterpret_cast<uint16_t*>(mrow + 4 + byte) = (uint16_t)packed;
+        else if constexpr (BITS == 4) *reinterpret_cast<uint16_t*>(mrow + 4 + byte) = (uint16_t)packed;
+        else *reinterpret_cast<uint32_t*>(mrow + 4 + byte) = packed;
     }
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) sy2 += __shfl_xor(sy2, o);
@@ -363,11 +365,13 @@ ds_status l2q_step(L2State* st, const L2Args& a, hipStream_t stream) {
     // All rows go through `form` before any row's codes are replaced: the tail that `form` applies reads the
     // previous step's codes of the neighbours.  (Splitting the rows into groups that run form -> quantize
     // back to back, hoping that v is still in the memory-side cache, was measured slower at every group size.)
-    if (st->bits == 2) hipLaunchKernelGGL(l2q_form<2>, grid, block, 0, stream, a, s);
-    else               hipLaunchKernelGGL(l2q_form<4>, grid, block, 0, stream, a, s);
+    if (st->bits == 2)      hipLaunchKernelGGL(l2q_form<2>, grid, block, 0, stream, a, s);
+    else if (st->bits == 4) hipLaunchKernelGGL(l2q_form<4>, grid, block, 0, stream, a, s);
+    else                    hipLaunchKernelGGL(l2q_form<8>, grid, block, 0, stream, a, s);
     hipLaunchKernelGGL(l2q_row_scale, rows, rblock, 0, stream, s, hl);
-    if (st->bits == 2) hipLaunchKernelGGL(l2q_quantize<2>, grid, block, 0, stream, a, s);
-    else               hipLaunchKernelGGL(l2q_quantize<4>, grid, block, 0, stream, a, s);
+    if (st->bits == 2)      hipLaunchKernelGGL(l2q_quantize<2>, grid, block, 0, stream, a, s);
+    else if (st->bits == 4) hipLaunchKernelGGL(l2q_quantize<4>, grid, block, 0, stream, a, s);
+    else                    hipLaunchKernelGGL(l2q_quantize<8>, grid, block, 0, stream, a, s);
     hipLaunchKernelGGL(l2q_row_unit, rows, rblock, 0, stream, a, s);
     st->stepped = true;
     st->last = a;
@@ -380,8 +384,9 @@ ds_status l2q_flush(L2State* st, hipStream_t stream) {
     const dim3 grid(s.nchunks, st->last.n), block(LQ_THREADS);
     // the kernels look at the device's pending flag themselves: a replayed graph of ds_step sets it
     // without this code noticing
-    if (st->bits == 2) hipLaunchKernelGGL(l2q_tail<2>, grid, block, 0, stream, st->last, s);
-    else               hipLaunchKernelGGL(l2q_tail<4>, grid, block, 0, stream, st->last, s);
+    if (st->bits == 2)      hipLaunchKernelGGL(l2q_tail<2>, grid, block, 0, stream, st->last, s);
+    else if (st->bits == 4) hipLaunchKernelGGL(l2q_tail<4>, grid, block, 0, stream, st->last, s);
+    else                    hipLaunchKernelGGL(l2q_tail<8>, grid, block, 0, stream, st->last, s);
     hipLaunchKernelGGL(l2q_clear_pending, dim3(1), dim3(1), 0, stream, s);
     return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
 }

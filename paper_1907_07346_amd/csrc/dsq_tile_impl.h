@@ -116,6 +116,7 @@ __device__ __forceinline__ float group_sum_tree(float v) {
 }
 
 template <int KIND, int BITS> struct CodeTraits;
+template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 8> { using lane_t = uint32_t; static constexpr int row_bytes_per_sweep = 256; };
 template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 4> { using lane_t = uint16_t; static constexpr int row_bytes_per_sweep = 128; };
 template <> struct CodeTraits<DS_COMP_QUANT_MAXABS, 2> { using lane_t = uint8_t;  static constexpr int row_bytes_per_sweep = 64; };
 template <> struct CodeTraits<DS_COMP_SIGN_MEANABS, 1> { using lane_t = uint32_t; static constexpr int row_bytes_per_sweep = 32; };

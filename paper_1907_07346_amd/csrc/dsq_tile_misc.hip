@@ -6,9 +6,11 @@ namespace dsq {
 // identity, random sparsifier, and the dispatchers over all families
 bool tile_plans_quant4(int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
 bool tile_plans_quant2(int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
+bool tile_plans_quant8(int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
 bool tile_plans_sign(int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
 bool stream_plan_quant4(int block, TilePlan& plan);
 bool stream_plan_quant2(int block, TilePlan& plan);
+bool stream_plan_quant8(int block, TilePlan& plan);
 bool stream_plan_sign(int block, TilePlan& plan);
 
 static_assert(kKeepGroup == 16, "the tile kernel finds a sweep's group with a shift by 4");
@@ -24,6 +26,7 @@ void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group
 bool stream_plan(const ds_config& cfg, TilePlan& plan) {
     if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 4) return stream_plan_quant4(cfg.comp.block, plan);
     if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 2) return stream_plan_quant2(cfg.comp.block, plan);
+    if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 8) return stream_plan_quant8(cfg.comp.block, plan);
     if (cfg.comp.kind == DS_COMP_SIGN_MEANABS) return stream_plan_sign(cfg.comp.block, plan);
     if (cfg.comp.kind == DS_COMP_IDENTITY) { plan = make_stream_plan<DS_COMP_IDENTITY, 32, 512>(); return true; }
     return false;
@@ -34,7 +37,8 @@ bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& pla
         case DS_COMP_QUANT_MAXABS:
             if (cfg.comp.bits == 4) return tile_plans_quant4(cfg.comp.block, cfg.n, nnz, plan, err);
             if (cfg.comp.bits == 2) return tile_plans_quant2(cfg.comp.block, cfg.n, nnz, plan, err);
-            err = "bits must be 2 or 4";
+            if (cfg.comp.bits == 8) return tile_plans_quant8(cfg.comp.block, cfg.n, nnz, plan, err);
+            err = "bits must be 2, 4 or 8";
             return false;
         case DS_COMP_SIGN_MEANABS:
             return tile_plans_sign(cfg.comp.block, cfg.n, nnz, plan, err);

@@ -174,6 +174,10 @@ SMALL = [
     small(wl.KIND_SIGN_MEANABS, 8, 64 * 41 + 33, block=64),
     small(wl.KIND_SIGN_MEANABS, 33, 128 * 7 + 1, block=128),
     small(wl.KIND_SIGN_MEANABS, 3, 30, block=64),
+    small(wl.KIND_QUANT_MAXABS, 8, 512 * 5 + 37, bits=8, block=512),               # 8-bit codes
+    small(wl.KIND_QUANT_MAXABS, 16, 64 * 31 + 9, bits=8, block=64, topo=wl.TOPO_TORUS2D, torus=(4, 4)),
+    small(wl.KIND_QUANT_MAXABS, 5, 2048 * 2 + 100, bits=8, block=2048),
+    small(wl.KIND_QUANT_L2NORM, 8, 4096 * 2 + 37, bits=8),
 ]
 
 
@@ -197,7 +201,7 @@ def _random_cases(count, seed):
             topo, torus, n = wl.TOPO_RING, (0, 0), int(r.integers(3, 41))
         N = int(r.choice(edges)) + int(r.integers(0, 3)) * int(r.choice([256, 512, 4096])) if r.random() < 0.7 \
             else int(r.integers(1, 20_000))
-        bits = int(r.choice([2, 4])) if kind in (wl.KIND_QUANT_MAXABS, wl.KIND_QUANT_L2NORM) else 0
+        bits = int(r.choice([2, 4, 8])) if kind in (wl.KIND_QUANT_MAXABS, wl.KIND_QUANT_L2NORM) else 0
         block = int(r.choice([64, 128, 256, 512, 1024, 2048])) if kind in (wl.KIND_QUANT_MAXABS, wl.KIND_SIGN_MEANABS) else 0
         k = int(r.integers(1, N + 1)) if kind in (wl.KIND_TOPK, wl.KIND_RAND_SPARSE) else 0
         cases.append(wl.Config(f"rnd{c}_k{kind}_n{n}_N{N}_b{bits}_B{block}_k{k}", n=n, N=N, topo=topo, torus=torus, kind=kind,
@@ -753,7 +757,8 @@ STREAM_CASES = [small(wl.KIND_QUANT_MAXABS, 8, 512 * 5 + 37, bits=4, block=512),
                 small(wl.KIND_QUANT_MAXABS, 6, 1024 * 3 + 1000, bits=2, block=1024),
                 small(wl.KIND_SIGN_MEANABS, 12, 2048 * 2 + 5, block=2048),
                 small(wl.KIND_SIGN_MEANABS, 5, 128 * 9 + 3, block=128),
-                small(wl.KIND_IDENTITY, 7, 512 * 3 + 5)]
+                small(wl.KIND_IDENTITY, 7, 512 * 3 + 5),
+                small(wl.KIND_QUANT_MAXABS, 9, 256 * 7 + 100, bits=8, block=256)]
 
 
 @pytest.mark.parametrize("w", STREAM_CASES, ids=lambda w: w.name)

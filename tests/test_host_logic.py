@@ -40,11 +40,11 @@ def test_validate_accepts_the_five_benchmark_configs():
     (dict(n=0), "n must"), (dict(N=0), "N must"), (dict(n=2), "ring needs"),
     (dict(topo=wl.TOPO_TORUS2D, n=8, torus=(2, 4)), "torus sides"),
     (dict(topo=wl.TOPO_TORUS2D, n=10, torus=(3, 3)), "must equal n"),
-    (dict(bits=3), "bits"), (dict(block=300), "power of two"), (dict(block=32), "power of two"),
+    (dict(bits=3), "bits"), (dict(bits=1), "bits"), (dict(block=300), "power of two"), (dict(block=32), "power of two"),
     (dict(block=8192), "power of two"), (dict(kind=wl.KIND_TOPK, k=0), "k must"),
     (dict(kind=wl.KIND_TOPK, k=10 ** 9), "k must"), (dict(gamma=float("nan")), "finite"),
     (dict(eta=float("inf")), "finite"), (dict(kind=9), "unknown compressor"), (dict(topo=7), "unknown topology"),
-    (dict(kind=wl.KIND_QUANT_L2NORM, bits=3, block=0), "bits"), (dict(kind=wl.KIND_QUANT_L2NORM, bits=8, block=0), "bits"),
+    (dict(kind=wl.KIND_QUANT_L2NORM, bits=3, block=0), "bits"), (dict(kind=wl.KIND_QUANT_L2NORM, bits=16, block=0), "bits"),
 ])
 def test_validate_rejects(kw, needle):
     base = dict(n=8, N=4096, topo=wl.TOPO_RING, kind=wl.KIND_QUANT_MAXABS, gamma=0.1, eta=0.5, bits=4, block=512)

@@ -557,7 +557,7 @@ def test_quantiser_worked_example(golden_dir):
     assert seen == {"up", "down"}
 
 
-@pytest.mark.parametrize("bits,block", [(4, 512), (2, 1024)])
+@pytest.mark.parametrize("bits,block", [(4, 512), (2, 1024), (8, 256)])
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 def test_quantiser_is_unbiased_bounded_and_on_grid(bits, block, dtype):
     # every block holds the same pattern, so position e sees `reps` independent roundings of one value
@@ -572,7 +572,8 @@ def test_quantiser_is_unbiased_bounded_and_on_grid(bits, block, dtype):
     c = cv.reshape(reps, block).astype(np.float64)
     step_sz = 2.0 / L
     grid = (2 * np.arange(L + 1) - L) / L
-    assert np.all(np.min(np.abs(c[..., None] - grid), axis=-1) < 1e-6)            # on the grid
+    lvl = (c + 1.0) * (L / 2.0)                                                    # on the grid: an integer level
+    assert np.all(np.abs(lvl - np.rint(lvl)) < 1e-4) and lvl.min() > -1e-4 and lvl.max() < L + 1e-4
     assert np.all(np.abs(c - pat) <= step_sz * (1 + 1e-6))                        # error bound
     assert np.all(c[:, 0] == 1.0) and np.all(c[:, 1] == -1.0)                     # extremes exact
     sem = step_sz / 2 / np.sqrt(reps)
