@@ -128,6 +128,10 @@ ds_status ds_build_topology(const ds_config* cfg, int32_t* rowptr, int32_t* col,
  * Returns 0 for an invalid configuration. */
 uint64_t ds_message_bytes(const ds_config* cfg);
 
+/* Identifies the sources the library was built from (a hash the build script computes over the kernel and
+ * host sources, this header and the compiler flags); reports print it next to their measurements. */
+const char* ds_build_id(void);
+
 /* ---- the hot path --------------------------------------------------------------------------- */
 
 /* Creates the state on the current HIP device: x = 0, delta = 0, t = 0 (Algorithm 1, line 1;

@@ -33,12 +33,19 @@
 // kernels, contraction off, explicit fma) is used for bit-level parity.
 //
 // Build: g++ -O2 -ffp-contract=off -shared -fPIC ds_oracle.cpp -o libds_oracle.so
+// The loops over workers carry `#pragma omp parallel for`: without -fopenmp (the build every test uses) the
+// pragmas are ignored and the code is the sequential program it reads as; with -fopenmp (a second library,
+// built only for the benchmark's all-cores baseline) workers are spread over the host's cores.  No iteration
+// of those loops reads what another one writes, so both builds give the same bits.
 
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 namespace {
 
@@ -98,13 +105,12 @@ template <typename real> real fma_(real a, real b, real c);
 template <> float  fma_<float>(float a, float b, float c)    { return std::fmaf(a, b, c); }
 template <> double fma_<double>(double a, double b, double c) { return std::fma(a, b, c); }
 
-template <typename real> struct Msg {           // append-only byte sink, may be disabled
-    uint8_t* base; uint64_t cap; uint64_t used; bool overflow;
+template <typename real> struct Msg {           // append-only byte sink of one worker, may be disabled
+    std::vector<uint8_t>* bytes;
     void put(const void* p, size_t nbytes) {
-        if (!base) return;
-        if (used + nbytes > cap) { overflow = true; return; }
-        std::memcpy(base + used, p, nbytes);
-        used += nbytes;
+        if (!bytes) return;
+        const uint8_t* b = static_cast<const uint8_t*>(p);
+        bytes->insert(bytes->end(), b, b + nbytes);
     }
     void put_u32(uint32_t w) { put(&w, 4); }
     void put_f32(real s)     { float f = (float)s; put(&f, 4); }
@@ -337,11 +343,11 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
     std::vector<real> xh(total), v(total), cv_local;
     real* cv = cv_out;
     if (!cv) { cv_local.resize(total); cv = cv_local.data(); }
-    Msg<real> msg{msg_buf, msg_cap, 0, false};
     bool sparse_overflow = false;
 
     // Algorithm 1, line 5: the error-compensated variable, evaluated as
     // (x - gamma g) + delta with the product fused into the first sum.
+#pragma omp parallel for schedule(static)
     for (int i = 0; i < n; ++i)
         for (uint64_t j = 0; j < N; ++j) {
             const uint64_t p = (uint64_t)i * N + j;
@@ -349,10 +355,16 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
             v[p] = xh[p] + delta[p];
         }
 
-    // Line 6, first half, and lines 7-8: compress, and write what is sent.
+    // Line 6, first half, and lines 7-8: compress, and write what is sent.  Every worker appends to a sink of
+    // its own; the sinks are joined in worker order afterwards (so workers may be processed side by side).
+    std::vector<std::vector<uint8_t>> sent(msg_buf ? n : 0);
+    bool bad_kind = false;
+#pragma omp parallel for schedule(dynamic, 1)
     for (int i = 0; i < n; ++i) {
         const real* vi = &v[(uint64_t)i * N];
         real* ci = &cv[(uint64_t)i * N];
+        if (msg_buf) sent[i].reserve(msg_cap / n + 16);
+        Msg<real> msg{msg_buf ? &sent[i] : nullptr};
         if (kind == IDENTITY) {
             for (uint64_t j = 0; j < N; ++j) { ci[j] = vi[j]; msg.put_f32(vi[j]); }
         } else if (kind == QUANT_MAXABS || kind == SIGN_MEANABS) {
@@ -368,17 +380,31 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
         } else if (kind == QUANT_L2NORM) {
             compress_row_quant_l2norm<real>(vi, ci, N, bits, msg);
         } else if (kind == RAND_SPARSE) {
-            if (!compress_row_rand_sparse<real>(vi, ci, N, k, seed, t, (uint32_t)i, msg)) sparse_overflow = true;
+            if (!compress_row_rand_sparse<real>(vi, ci, N, k, seed, t, (uint32_t)i, msg)) {
+#pragma omp atomic write
+                sparse_overflow = true;
+            }
         } else {
-            return 1;
+#pragma omp atomic write
+            bad_kind = true;
         }
+    }
+    if (bad_kind) return 1;
+    uint64_t msg_used = 0;
+    bool msg_overflow = false;
+    for (int i = 0; msg_buf && i < n; ++i) {
+        if (msg_used + sent[i].size() > msg_cap) { msg_overflow = true; break; }
+        std::memcpy(msg_buf + msg_used, sent[i].data(), sent[i].size());
+        msg_used += sent[i].size();
     }
 
     // Line 6, second half: what compression lost is carried to the next step.
+#pragma omp parallel for schedule(static)
     for (uint64_t p = 0; p < total; ++p) delta[p] = v[p] - cv[p];
 
     // Line 9: gossip on the compressed values, neighbours in ascending index
     // order (own index included), accumulated by a chain of fused multiply-adds.
+#pragma omp parallel for schedule(static)
     for (int i = 0; i < n; ++i)
         for (uint64_t j = 0; j < N; ++j) {
             real acc = 0;
@@ -391,9 +417,9 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
             x[p] = fma_<real>(eta, acc, xh[p]);
         }
 
-    if (msg_bytes) *msg_bytes = msg.used;
+    if (msg_bytes) *msg_bytes = msg_used;
     if (sparse_overflow) return 3;
-    return msg.overflow ? 2 : 0;
+    return msg_overflow ? 2 : 0;
 }
 
 }  // namespace
@@ -411,6 +437,15 @@ uint32_t dso_rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
 uint32_t dso_keep_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) { return keep_word(seed, t, i, j); }
 
 uint64_t dso_rand_sparse_capacity(uint64_t N, uint64_t k) { return rand_sparse_capacity(N, k); }
+
+// Threads the loops over workers are spread over: 1 unless built with -fopenmp.
+int dso_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 double dso_sum_squares_tree_f32(const float* v, uint64_t N) { return sum_squares_tree<float>(v, N); }
 

@@ -24,24 +24,36 @@ KIND_RAND_SPARSE = 5   # every element kept with probability k/N, no rescaling
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ds_oracle.cpp")
 _LIB = os.path.join(_HERE, "libds_oracle.so")
+_LIB_OMP = os.path.join(_HERE, "libds_oracle_omp.so")     # same source with -fopenmp: the benchmark's all-cores baseline
 _lib = None
+_lib_omp = None
 
 
-def build_oracle(force: bool = False) -> str:
-    """Compile the oracle with g++ (contraction off, no fast-math). Returns the .so path."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+def build_oracle(force: bool = False, omp: bool = False) -> str:
+    """Compile the oracle with g++ (contraction off, no fast-math). Returns the .so path.
+
+    omp=True builds the second library, in which the loops over workers run on all host cores."""
+    out = _LIB_OMP if omp else _LIB
+    stale = (not os.path.exists(out)) or os.path.getmtime(out) < os.path.getmtime(_SRC)
     if force or stale:
         cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC",
-               _SRC, "-o", _LIB]
+               *(["-fopenmp"] if omp else []), _SRC, "-o", out]
         subprocess.run(cmd, check=True)
-    return _LIB
+    return out
 
 
-def _load():
-    global _lib
-    if _lib is not None:
+def threads(all_cores: bool = False) -> int:
+    """Threads a step runs on: 1, or what OpenMP gives the all-cores library."""
+    return int(_load(all_cores).dso_threads())
+
+
+def _load(omp: bool = False):
+    global _lib, _lib_omp
+    if omp and _lib_omp is not None:
+        return _lib_omp
+    if not omp and _lib is not None:
         return _lib
-    lib = ctypes.CDLL(build_oracle())
+    lib = ctypes.CDLL(build_oracle(omp=omp))
     u64, i32, u32 = ctypes.c_uint64, ctypes.c_int, ctypes.c_uint32
     vp = ctypes.c_void_p
     for name, real in (("dso_step_f32", ctypes.c_float), ("dso_step_f64", ctypes.c_double)):
@@ -62,7 +74,12 @@ def _load():
     lib.dso_rand_sparse_capacity.argtypes = [u64, u64]
     lib.dso_sum_squares_tree_f32.restype = ctypes.c_double
     lib.dso_sum_squares_tree_f32.argtypes = [vp, u64]
-    _lib = lib
+    lib.dso_threads.restype = ctypes.c_int
+    lib.dso_threads.argtypes = []
+    if omp:
+        _lib_omp = lib
+    else:
+        _lib = lib
     return lib
 
 
@@ -228,9 +245,11 @@ def step_window(st: OracleState, g: np.ndarray, col0: int):
     return msg
 
 
-def step(st: OracleState, g: np.ndarray, want_cv: bool = True, want_msg: bool = True):
-    """Advance `st` by one iteration with gradients g (n x N). Returns (C[v], message bytes)."""
-    lib = _load()
+def step(st: OracleState, g: np.ndarray, want_cv: bool = True, want_msg: bool = True, all_cores: bool = False):
+    """Advance `st` by one iteration with gradients g (n x N). Returns (C[v], message bytes).
+
+    all_cores=True runs the same code from the library built with -fopenmp (workers side by side)."""
+    lib = _load(all_cores)
     dt = np.dtype(st.dtype)
     assert dt in (np.dtype(np.float32), np.dtype(np.float64))
     g = np.ascontiguousarray(g, dtype=dt)

@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
            "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
-           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient", "ds_bench_stream"]
+           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient", "ds_bench_stream", "ds_build_id"]
 
 
 class ds_comp(ctypes.Structure):
@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
         L.ds_validate_config.argtypes, L.ds_validate_config.restype = [cfgp, ctypes.c_char_p, u64], i32
         L.ds_build_topology.argtypes, L.ds_build_topology.restype = [cfgp, vp, vp, vp, u64, u64p], i32
         L.ds_message_bytes.argtypes, L.ds_message_bytes.restype = [cfgp], u64
+        L.ds_build_id.argtypes, L.ds_build_id.restype = [], ctypes.c_char_p
         L.ds_init.argtypes, L.ds_init.restype = [cfgp, ctypes.POINTER(vp)], i32
         L.ds_step.argtypes, L.ds_step.restype = [vp, vp, u64, vp], i32
         L.ds_read_state.argtypes, L.ds_read_state.restype = [vp, vp, vp], i32

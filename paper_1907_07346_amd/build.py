@@ -1,6 +1,7 @@
 """Builds libdsq.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -19,12 +20,28 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
 
+ID_FILE = LIB + ".id"
+
+
+def source_id(extra_flags=()) -> str:
+    """Hash of everything the library is built from: sources, headers, flags."""
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h", ".cpp")))
+    for path in files + [os.path.join(ROOT, "include", "dsq.h")]:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join([*FLAGS, *extra_flags]).encode())
+    return h.hexdigest()[:16]
+
+
 def build(verbose: bool = True, extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    build_id = source_id(extra_flags)
     objs, procs = [], []
     for src in SOURCES:                                       # the translation units compile side by side
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
+        cmd = [hipcc, *FLAGS, *extra_flags, f'-DDSQ_BUILD_ID="{build_id}"', "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
                os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -37,12 +54,23 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    with open(ID_FILE, "w") as f:
+        f.write(build_id + "\n")
     return LIB
 
 
+def built_id() -> str:
+    """The source hash the library on disk was built from ("" if there is none, or it predates the hash)."""
+    if not (os.path.exists(LIB) and os.path.exists(ID_FILE)):
+        return ""
+    with open(ID_FILE) as f:
+        return f.read().strip()
+
+
 def ensure_built(verbose: bool = False) -> str:
-    """Builds the library only if no built one is there (tests, the smoke check and the benchmark call this)."""
-    return LIB if os.path.exists(LIB) else build(verbose=verbose)
+    """Builds the library unless the one on disk was built from exactly the present sources and flags (tests, the
+    smoke check and the benchmark call this before loading it: a stale binary must not answer for the sources)."""
+    return LIB if built_id() == source_id() else build(verbose=verbose)
 
 
 if __name__ == "__main__":

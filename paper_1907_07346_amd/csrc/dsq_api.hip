@@ -70,11 +70,32 @@ void release(ds_handle* h) {
 
 dsq::TileArgs tile_args(const ds_handle* h, const float* g_dev, uint64_t g_ld);
 
+// Kernel arguments of the top-k and the norm-rescaled paths, always from the handle's CURRENT buffers, mixing
+// matrix and rates (a flush after ds_set_mixing must not see the device addresses of the matrix it replaced).
+dsq::TopkArgs topk_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
+    dsq::TopkArgs a{};
+    a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
+    a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
+    a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.k = h->cfg.comp.k; a.n = h->cfg.n;
+    a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
+    return a;
+}
+
+dsq::L2Args l2_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
+    dsq::L2Args a{};
+    a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
+    a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
+    a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes; a.n = h->cfg.n;
+    a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
+    return a;
+}
+
 // Three paths (top-k, norm-rescaled codes, the row-streaming block kernels) leave the tail of a step to the next step's first pass;
-// this applies it now, on the stream of the last step.
+// this applies it now, on the stream of the last step.  Callers that replace W, gamma or eta call it BEFORE the
+// replacement: the tail belongs to the values the step ran with.
 ds_status flush_deferred(ds_handle* h) {
-    if (h->topk) return dsq::topk_flush(h->topk, h->last_stream);
-    if (h->l2q) return dsq::l2q_flush(h->l2q, h->last_stream);
+    if (h->topk) return dsq::topk_flush(h->topk, topk_args(h, nullptr, 0), h->last_stream);
+    if (h->l2q) return dsq::l2q_flush(h->l2q, l2_args(h, nullptr, 0), h->last_stream);
     if (h->tile.streaming && h->stepped) {
         h->tile.flush(tile_args(h, nullptr, 0), h->last_stream);
         return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
@@ -385,20 +406,10 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     if (h->cfg.comp.kind == DS_COMP_TOPK) {
-        dsq::TopkArgs a{};
-        a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
-        a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
-        a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.k = h->cfg.comp.k; a.n = h->cfg.n;
-        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
-        const ds_status st = dsq::topk_step(h->topk, a, h->graph, stream, h->err);
+        const ds_status st = dsq::topk_step(h->topk, topk_args(h, g_dev, g_ld), stream);
         if (st != DS_OK) return st;
     } else if (h->cfg.comp.kind == DS_COMP_QUANT_L2NORM) {
-        dsq::L2Args a{};
-        a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
-        a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
-        a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes; a.n = h->cfg.n;
-        a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
-        const ds_status st = dsq::l2q_step(h->l2q, a, stream);
+        const ds_status st = dsq::l2q_step(h->l2q, l2_args(h, g_dev, g_ld), stream);
         if (st != DS_OK) return fail(h, st, "launching the norm-rescaled step failed");
     } else {
         const dsq::TileArgs a = tile_args(h, g_dev, g_ld);
@@ -582,10 +593,6 @@ ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count) {
     if (!h->stepped) return fail(h, DS_ESTATE, "no step has been taken yet");
     return dsq::topk_candidate_rows(h->topk, h->last_stream, count);
 }
-
-#ifdef DSQ_DEBUG_EXPORTS
-void* dsq_debug_topk_state(ds_handle* h) { return h ? h->topk : nullptr; }
-#endif
 
 uint64_t ds_step_count(const ds_handle* h) {
     // the device counter is the authority: replays of a captured graph advance it without the host seeing them

@@ -182,6 +182,11 @@ ds_status ds_build_topology(const ds_config* cfg, int32_t* rowptr, int32_t* col,
     return DS_OK;
 }
 
+#ifndef DSQ_BUILD_ID
+#define DSQ_BUILD_ID "unknown"
+#endif
+const char* ds_build_id(void) { return DSQ_BUILD_ID; }
+
 uint64_t ds_message_bytes(const ds_config* cfg) {
     std::string err;
     if (dsq::validate_config(cfg, err, nullptr) != DS_OK) return 0;

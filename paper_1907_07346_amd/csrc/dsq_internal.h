@@ -115,10 +115,11 @@ struct TopkArgs {
 struct TopkState;              // device scratch of the radix select (histograms, per-chunk counts)
 ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::string& err);
 void topk_destroy(TopkState* s);
-ds_status topk_step(TopkState* s, const TopkArgs& a, const Graph& graph, hipStream_t stream, std::string& err);
+ds_status topk_step(TopkState* s, const TopkArgs& a, hipStream_t stream);
 // topk_step leaves the sparse part of the gossip update of x to the next step's first pass;
-// topk_flush applies it now (no-op if nothing is pending).  Call before x is read or replaced.
-ds_status topk_flush(TopkState* s, hipStream_t stream);
+// topk_flush applies it now (no-op if nothing is pending).  Call before x is read or replaced, with the
+// buffers, mixing matrix and eta the last step ran with (a.g is not used).
+ds_status topk_flush(TopkState* s, const TopkArgs& a, hipStream_t stream);
 // Number of rows whose last step selected from the candidate slots (the fast path).
 ds_status topk_candidate_rows(TopkState* s, hipStream_t stream, uint32_t* count);
 
@@ -142,8 +143,9 @@ ds_status l2q_create(const ds_config& cfg, uint64_t ld, L2State** out, std::stri
 void l2q_destroy(L2State* s);
 ds_status l2q_step(L2State* s, const L2Args& a, hipStream_t stream);
 // l2q_step leaves delta = v - C[v] and the gossip update of x to the next step's first pass;
-// l2q_flush applies them now (no-op if nothing is pending).  Call before the state is read or replaced.
-ds_status l2q_flush(L2State* s, hipStream_t stream);
+// l2q_flush applies them now (no-op if nothing is pending).  Call before the state is read or replaced, with
+// the buffers, mixing matrix and eta the last step ran with (a.g is not used).
+ds_status l2q_flush(L2State* s, const L2Args& a, hipStream_t stream);
 
 // Device twin of the deterministic host gradient generator (harness aid).
 ds_status launch_workload_gradient(const ds_workload& w, uint64_t t, const float* x, uint64_t x_ld, float* g, uint64_t g_ld,

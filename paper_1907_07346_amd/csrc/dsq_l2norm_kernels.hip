@@ -318,7 +318,6 @@ __global__ void l2q_clear_pending(L2Scratch s) { *s.pending = 0u; }
 
 struct L2State {
     L2Scratch s{};
-    L2Args last{};
     int n = 0, bits = 0;
     bool stepped = false;          // a step has been enqueued (or may have been, by a replayed graph)
 };
@@ -374,19 +373,18 @@ ds_status l2q_step(L2State* st, const L2Args& a, hipStream_t stream) {
     else                    hipLaunchKernelGGL(l2q_quantize<8>, grid, block, 0, stream, a, s);
     hipLaunchKernelGGL(l2q_row_unit, rows, rblock, 0, stream, a, s);
     st->stepped = true;
-    st->last = a;
     return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
 }
 
-ds_status l2q_flush(L2State* st, hipStream_t stream) {
+ds_status l2q_flush(L2State* st, const L2Args& a, hipStream_t stream) {
     if (!st || !st->stepped) return DS_OK;
     const L2Scratch& s = st->s;
-    const dim3 grid(s.nchunks, st->last.n), block(LQ_THREADS);
+    const dim3 grid(s.nchunks, a.n), block(LQ_THREADS);
     // the kernels look at the device's pending flag themselves: a replayed graph of ds_step sets it
     // without this code noticing
-    if (st->bits == 2)      hipLaunchKernelGGL(l2q_tail<2>, grid, block, 0, stream, st->last, s);
-    else if (st->bits == 4) hipLaunchKernelGGL(l2q_tail<4>, grid, block, 0, stream, st->last, s);
-    else                    hipLaunchKernelGGL(l2q_tail<8>, grid, block, 0, stream, st->last, s);
+    if (st->bits == 2)      hipLaunchKernelGGL(l2q_tail<2>, grid, block, 0, stream, a, s);
+    else if (st->bits == 4) hipLaunchKernelGGL(l2q_tail<4>, grid, block, 0, stream, a, s);
+    else                    hipLaunchKernelGGL(l2q_tail<8>, grid, block, 0, stream, a, s);
     hipLaunchKernelGGL(l2q_clear_pending, dim3(1), dim3(1), 0, stream, s);
     return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
 }

@@ -50,25 +50,14 @@ constexpr uint32_t kSparseStreamTag = 0x53504152u;  // ... and of the stream tha
 
 // 16-byte streaming accesses.  x, g and delta are touched exactly once per step, so they are
 // marked non-temporal: on gfx950 that keeps the streams from displacing each other in L2 / MALL.
-#ifndef DSQ_NONTEMPORAL
-#define DSQ_NONTEMPORAL 1
-#endif
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float4 ld4(const float* p) {
-#if DSQ_NONTEMPORAL
     const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-#else
-    const f32x4 v = *reinterpret_cast<const f32x4*>(p);
-#endif
     return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void st4(float* p, const float4& v) {
     const f32x4 w = {v.x, v.y, v.z, v.w};
-#if DSQ_NONTEMPORAL
     __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(p));
-#else
-    *reinterpret_cast<f32x4*>(p) = w;
-#endif
 }
 
 // ---- wave64 reductions on the DPP cross-lane path (no LDS traffic); the result is wave-uniform ----

@@ -737,6 +737,12 @@ __global__ void __launch_bounds__(TK_THREADS) topk_gossip(TopkArgs a, Scratch s)
     }
 }
 
+__global__ void __launch_bounds__(256) topk_zero_words(uint32_t* p, size_t words) {
+    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i + 3 < words) *reinterpret_cast<uint4*>(p + i) = make_uint4(0u, 0u, 0u, 0u);   // the array comes from hipMalloc: 16-byte aligned
+    else for (size_t q = i; q < words; ++q) p[q] = 0u;
+}
+
 __global__ void topk_init_rows(TopkRow* rows, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) {
@@ -754,7 +760,6 @@ struct TopkState {
     int n = 0;
     bool pending = false;          // a step has been enqueued since the last flush (or may have been, by a
                                    // replayed graph): its sparse tail may not have been applied yet
-    TopkArgs last{};               // arguments of the last step (what the pending update needs)
 };
 
 void topk_destroy(TopkState* st) {
@@ -806,25 +811,20 @@ ds_status topk_candidate_rows(TopkState* st, hipStream_t stream, uint32_t* count
     return DS_OK;
 }
 
-#ifdef DSQ_DEBUG_EXPORTS
-extern "C" int dsq_debug_topk_rows(TopkState* st, uint32_t* out) {   // 12 words per row
-    (void)hipDeviceSynchronize();
-    return (int)hipMemcpy(out, st->s.rows, (size_t)st->n * sizeof(TopkRow), hipMemcpyDeviceToHost);
-}
-#endif
-
-ds_status topk_flush(TopkState* st, hipStream_t stream) {
+ds_status topk_flush(TopkState* st, const TopkArgs& a, hipStream_t stream) {
     if (!st || !st->pending) return DS_OK;
-    const dim3 grid(st->s.nchunks, st->last.n), block(TK_THREADS);
-    hipLaunchKernelGGL(topk_gossip, grid, block, 0, stream, st->last, st->s);
-    // the tail is applied: no message offsets, nothing for the next first pass to apply again
-    const hipError_t e = hipMemsetAsync(st->s.out_off, 0, (size_t)st->n * (st->s.nchunks + 1) * sizeof(uint32_t), stream);
+    const dim3 grid(st->s.nchunks, a.n), block(TK_THREADS);
+    hipLaunchKernelGGL(topk_gossip, grid, block, 0, stream, a, st->s);
+    // the tail is applied: no message offsets, nothing for the next first pass to apply again (a kernel, not a
+    // memset: the caller may be capturing the stream)
+    const size_t words = (size_t)st->n * (st->s.nchunks + 1);
+    hipLaunchKernelGGL(topk_zero_words, dim3((unsigned)((words + 1023) / 1024)), dim3(256), 0, stream, st->s.out_off, words);
     // `pending` stays set: a captured graph of ds_step may be replayed without this code noticing, and a flush
     // with nothing to apply is a grid of workgroups that return at once
-    return (e == hipSuccess && hipGetLastError() == hipSuccess) ? DS_OK : DS_EHIP;
+    return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
 }
 
-ds_status topk_step(TopkState* st, const TopkArgs& a, const Graph& /*graph*/, hipStream_t stream, std::string& /*err*/) {
+ds_status topk_step(TopkState* st, const TopkArgs& a, hipStream_t stream) {
     const Scratch& s = st->s;
     const dim3 grid(s.nchunks, a.n), block(TK_THREADS);
     const dim3 cgrid((s.nchunks + TK_CPW - 1) / TK_CPW, a.n);
@@ -849,7 +849,6 @@ ds_status topk_step(TopkState* st, const TopkArgs& a, const Graph& /*graph*/, hi
     hipLaunchKernelGGL(topk_write_cand, grid, dim3(64), 0, stream, a, s);
     hipLaunchKernelGGL(topk_write_full, fgrid, block, 0, stream, a, s);
     st->pending = true;
-    st->last = a;
     return DS_OK;
 }
 

@@ -503,11 +503,9 @@ def test_negative_zeros():
         _, msg = oracle.step(st, g, want_cv=False)
         assert np.array_equal(ds.ds_read_messages(), msg), f"{w.name}: messages differ"
         x, d = ds.ds_read_state()
-        if w.kind == wl.KIND_TOPK:                             # top-k writes x = xh + 0: -0 becomes +0 (documented)
-            assert np.array_equal(x, st.x) and np.array_equal(d, st.delta)
-        else:
-            assert np.array_equal(x.view(np.uint32), st.x.view(np.uint32)), f"{w.name}: x differs bitwise"
-            assert np.array_equal(d.view(np.uint32), st.delta.view(np.uint32)), f"{w.name}: delta differs bitwise"
+        # (top-k writes x = xh + 0 for a column nobody sent, which is what the oracle's fma chain gives: -0 becomes +0)
+        assert np.array_equal(x.view(np.uint32), st.x.view(np.uint32)), f"{w.name}: x differs bitwise"
+        assert np.array_equal(d.view(np.uint32), st.delta.view(np.uint32)), f"{w.name}: delta differs bitwise"
         ds.ds_destroy()
 
 
@@ -883,6 +881,52 @@ def test_block_configs_full_size_one_step(idx):
     assert nb == 0
 
 
+def _full_size_free_run(w, idx, steps, t0=3):
+    """`steps` iterations at full size with no state rewrite in between (so deferred tails, double-buffered
+    messages and counts carried from one step to the next all go through their steady-state code), from a
+    seeded non-zero state; messages are compared after every step, the whole state at the end."""
+    x0, d0, g = _full_size_inputs(w, idx)
+    ds = b.DeepSqueeze.from_workload(w)
+    ds.ds_write_state(x0, d0, t0)
+    say("case", w.name, "gpu steps, plan", ds.ds_plan_name())
+    st = oracle_state(w, x=x0, delta=d0, t=t0)
+    pitch = g.shape[1]
+    for t in range(steps):
+        if t:
+            g[:, :w.N] = wl.device_gradient(w, t0 + t)
+        torch.cuda.synchronize()
+        ds.ds_step(g)
+        gm = ds.ds_read_messages()                           # does not touch x or delta: the run stays free
+        g_host = np.ascontiguousarray(g[:, :w.N].cpu().numpy())
+        say("case", w.name, "oracle step", t)
+        _, om = oracle.step(st, g_host, want_cv=False)
+        assert np.array_equal(gm, om), f"step {t}: {int((gm != om).sum())} message bytes differ"
+        del gm, om, g_host
+    assert pitch == g.shape[1]
+    x, d = ds.ds_read_state()
+    assert ds.ds_step_count() == t0 + steps
+    ds.ds_destroy()
+    nb = assert_close("x", x, st.x) + assert_close("delta", d, st.delta)
+    for name, got, want in (("x", x, st.x), ("delta", d, st.delta)):
+        num = np.linalg.norm(got.astype(np.float64) - want.astype(np.float64))
+        assert num <= 1e-5 * np.linalg.norm(want.astype(np.float64)), f"{w.name} {name}: relative L2 {num:.3e}"
+    say(w.name, f"full size, {steps} free steps: state elements differing bitwise:", nb)
+    assert nb == 0
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_block_configs_full_size_three_free_steps(idx):
+    """Configurations 1-3 at full size, three iterations in a row without touching the state in between."""
+    _full_size_free_run(wl.configs()[idx], idx, steps=3)
+
+
+def test_rand_sparse_full_size_two_free_steps():
+    """Random sparsification at the size bench.py --config 7 times (32 x 25.56 M): more than 1024 offset groups
+    per row, so the per-row scan walks several groups per thread; the second step takes its keep counts from
+    the first step's tile kernel."""
+    _full_size_free_run(wl.extra_configs()[2], 7, steps=2)
+
+
 def test_l2norm_full_size_two_steps():
     """The norm-rescaled compressor at the size bench.py --config 6 times (16 x 11.17 M, 2 bits): two steps in a
     row, so the first step's tail goes through the second step's first pass; every output is compared."""
@@ -1126,4 +1170,61 @@ def test_topk_config_full_size_sampled_rows():
         assert np.array_equal(gm[rows].ravel(), msg), f"rows {rows}: messages differ"
         nb = assert_close(f"delta rows {rows}", d[rows], sub.delta)
         nb += assert_close(f"x row {target}", x[target:target + 1], sub.x[mid:mid + 1])
+        assert nb == 0
+
+
+def test_topk_config_full_size_steady_state():
+    """Config 4 at full size on the path the benchmark times: after three free steps every row selects from its
+    candidate slots, and the sparse tail of a step is applied by the next step's first pass.  Steps 4 and 5 run
+    back to back on the GPU with nothing read in between.  The oracle follows sampled workers: a worker i with
+    two ring neighbours on each side is a 5-row problem in which rows i-1, i, i+1 keep their real neighbourhoods
+    (the outer two rows are given identity rows of W: their messages of the first step are still right, because
+    a top-k message depends on the worker's own v only).  After the two steps the messages and delta of rows
+    i-1, i, i+1 and x of row i are what the full ring gives; compared bit for bit."""
+    w = wl.configs()[4]
+    ds = b.DeepSqueeze.from_workload(w)
+    pitch = (w.N + 3) // 4 * 4
+    g = torch.zeros((w.n, pitch), dtype=torch.float32, device="cuda")
+    for t in range(3):
+        g[:, :w.N] = wl.device_gradient(w, t)
+        torch.cuda.synchronize()
+        ds.ds_step(g)
+    say("case", w.name, "3 free steps done; candidate rows", ds.ds_topk_candidate_rows())
+    x3, d3 = ds.ds_read_state()                             # applies the pending tail; the threshold guesses stay
+    targets = (0, 13)
+    # window rows in ascending worker index: the gossip sum is accumulated in ascending neighbour index, and a
+    # window that wraps around the ring must keep that order to reproduce the full ring's fp32 bits
+    windows = {i: sorted((i + o) % w.n for o in (-2, -1, 0, 1, 2)) for i in targets}
+    gs = []
+    msgs = []
+    for t in (3, 4):
+        g[:, :w.N] = wl.device_gradient(w, t)
+        torch.cuda.synchronize()
+        ds.ds_step(g)
+        assert ds.ds_topk_candidate_rows() == w.n, "a row fell back to the full-mode select"
+        msgs.append(ds.ds_read_messages().reshape(w.n, -1))
+        gs.append({i: np.ascontiguousarray(g[rows][:, :w.N].cpu().numpy()) for i, rows in windows.items()})
+    x5, d5 = ds.ds_read_state()
+    assert ds.ds_step_count() == 5
+    ds.ds_destroy()
+    third = np.float64(np.float32(1.0 / 3.0))
+    for i, rows in windows.items():
+        inner = [(i + o) % w.n for o in (-1, 0, 1)]          # workers that keep their real neighbourhood
+        W = np.eye(5)
+        for r in inner:
+            W[rows.index(r), :] = 0.0
+            for nb in ((r - 1) % w.n, r, (r + 1) % w.n):
+                W[rows.index(r), rows.index(nb)] = third
+        sub = oracle.OracleState(n=5, N=w.N, W=W, kind=w.kind, gamma=w.gamma, eta=w.eta, k=w.k,
+                                 x=x3[rows].copy(), delta=d3[rows].copy(), t=3)
+        say("case", w.name, "oracle on rows", rows)
+        _, m4 = oracle.step(sub, gs[0][i], want_cv=False)
+        assert np.array_equal(msgs[0][rows].ravel(), m4), f"rows {rows}: messages of step 4 differ"
+        _, m5 = oracle.step(sub, gs[1][i], want_cv=False)
+        m5 = m5.reshape(5, -1)
+        nb = 0
+        for r in inner:
+            assert np.array_equal(msgs[1][r], m5[rows.index(r)]), f"row {r}: message of step 5 differs"
+            nb += assert_close(f"delta row {r}", d5[r:r + 1], sub.delta[rows.index(r):rows.index(r) + 1])
+        nb += assert_close(f"x row {i}", x5[i:i + 1], sub.x[rows.index(i):rows.index(i) + 1])
         assert nb == 0

@@ -791,3 +791,29 @@ def test_diagnostics_definitions():
     oracle.step(st, np.zeros((n, N)), want_msg=False)
     d = oracle.diagnostics(st)
     assert d["consensus_sq"] < 1e-25 and d["delta_sq"] == 0.0 and d["delta_mixed_sq"] == 0.0
+
+
+def test_all_cores_build_gives_the_same_bits():
+    """The library built with -fopenmp (workers side by side, used only by the benchmark's baseline leg) and the
+    sequential one are the same program: every output equal bit for bit, for every operator."""
+    rng = np.random.default_rng(77)
+    n, N = 6, 3000
+    for kind, kw in ((oracle.KIND_QUANT_MAXABS, dict(bits=2, block=256)), (oracle.KIND_SIGN_MEANABS, dict(block=128)),
+                     (oracle.KIND_TOPK, dict(k=37)), (oracle.KIND_QUANT_L2NORM, dict(bits=4)),
+                     (oracle.KIND_RAND_SPARSE, dict(k=300)), (oracle.KIND_IDENTITY, {})):
+        outs = []
+        for all_cores in (False, True):
+            st = oracle.OracleState(n=n, N=N, W=oracle.ring_matrix(n), kind=kind, gamma=0.1, eta=0.4, seed=3, **kw)
+            r = np.random.default_rng(5)
+            msgs = []
+            for t in range(3):
+                g = r.standard_normal((n, N)).astype(np.float32)
+                cv, msg = oracle.step(st, g, all_cores=all_cores)
+                msgs.append((cv, msg))
+            outs.append((st.x, st.delta, msgs))
+        a, b_ = outs
+        assert np.array_equal(a[0].view(np.uint32), b_[0].view(np.uint32))
+        assert np.array_equal(a[1].view(np.uint32), b_[1].view(np.uint32))
+        for (cv0, m0), (cv1, m1) in zip(a[2], b_[2]):
+            assert np.array_equal(cv0.view(np.uint32), cv1.view(np.uint32)) and np.array_equal(m0, m1)
+    assert oracle.threads() == 1 and oracle.threads(all_cores=True) >= 1
