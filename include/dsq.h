@@ -159,6 +159,25 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out);
  * entries of W. */
 ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_stream);
 
+/* ds_step for callers that cannot allocate device memory or keep a handle (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): one iteration of Algorithm 1 (lines 5-9) on arrays the caller
+ * owns, with nothing allocated, copied or synchronised.  What ds_step keeps in the handle's scratch memory -- the
+ * step counter with the tile kernel's finished-workgroup counters, and W - I in CSR form, built here by a small
+ * kernel -- lives in a static device array of 61,700 bytes inside the library (one copy per GPU, held until the
+ * process ends), which bounds the problem: n <= 1024 workers, DS_TOPO_RING or DS_TOPO_TORUS2D, and the
+ * compressors of the fused tile kernel (DS_COMP_QUANT_MAXABS, DS_COMP_SIGN_MEANABS, DS_COMP_IDENTITY) with n
+ * small enough for it (the codes of all n rows of a tile must fit in LDS); anything else is DS_EINVAL.
+ *   x_dev, delta_dev: n rows of pitch ld floats, ld a multiple of 4 and at least N rounded up to a multiple of
+ *                     4096, 16-byte aligned, columns >= N zero (they stay zero); updated in place.
+ *   g_dev, g_ld:      as for ds_step.        msg_dev: ds_message_bytes(cfg) bytes, 4-byte aligned; receives the
+ *   packed messages.  t: the iteration number (selects the random rounding words, as the handle's counter does).
+ * The result is bit for bit what ds_init + ds_write_state(x, delta, t) + ds_step gives.  Work is enqueued on
+ * hip_stream.  All calls on one GPU share the one static array: calls that overlap on a GPU (two streams, two
+ * threads) race; calls on one stream are safe back to back.  errbuf (may be NULL) receives the reason of a
+ * failure, or the eta > 1/2 note. */
+ds_status ds_step_static(const ds_config* cfg, float* x_dev, float* delta_dev, uint64_t ld, const float* g_dev, uint64_t g_ld,
+                         void* msg_dev, uint64_t t, void* hip_stream, char* errbuf, uint64_t errbuf_len);
+
 /* Replaces the mixing matrix W for the following steps (time-varying communication graphs; the
  * paper's Algorithm 1 holds for any symmetric doubly stochastic W, and its related-work section
  * cites time-varying topologies).  CSR of W as for DS_TOPO_CSR (host pointers, copied): n rows, every

@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
            "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
-           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient", "ds_bench_stream", "ds_build_id"]
+           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient", "ds_bench_stream", "ds_build_id", "ds_step_static"]
 
 
 class ds_comp(ctypes.Structure):
@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.ds_build_topology.argtypes, L.ds_build_topology.restype = [cfgp, vp, vp, vp, u64, u64p], i32
         L.ds_message_bytes.argtypes, L.ds_message_bytes.restype = [cfgp], u64
         L.ds_build_id.argtypes, L.ds_build_id.restype = [], ctypes.c_char_p
+        L.ds_step_static.argtypes = [cfgp, vp, vp, u64, vp, u64, vp, u64, vp, ctypes.c_char_p, u64]
+        L.ds_step_static.restype = i32
         L.ds_init.argtypes, L.ds_init.restype = [cfgp, ctypes.POINTER(vp)], i32
         L.ds_step.argtypes, L.ds_step.restype = [vp, vp, u64, vp], i32
         L.ds_read_state.argtypes, L.ds_read_state.restype = [vp, vp, vp], i32
@@ -173,6 +175,21 @@ def ds_bench_stream(x: "torch.Tensor", d: "torch.Tensor", g: "torch.Tensor", str
     st = lib().ds_bench_stream(x.data_ptr(), d.data_ptr(), g.data_ptr(), nbytes, s.cuda_stream)
     if st != DS_OK:
         raise DsqError(st, "ds_bench_stream")
+
+
+def ds_step_static(cfg: ds_config, x: "torch.Tensor", delta: "torch.Tensor", g: "torch.Tensor", msg: "torch.Tensor", t: int,
+                   stream: Optional["torch.cuda.Stream"] = None):
+    """One step on caller-owned CUDA tensors (x, delta: float32 (n, ld); g: float32 (n, >= N); msg: uint8), nothing allocated."""
+    for a in (x, delta, g):
+        assert a.is_cuda and a.dtype == torch.float32 and a.dim() == 2 and a.stride(1) == 1
+    assert msg.is_cuda and msg.dtype == torch.uint8 and msg.is_contiguous() and msg.numel() >= ds_message_bytes(cfg)
+    assert x.stride(0) == delta.stride(0)
+    s = stream if stream is not None else torch.cuda.current_stream()
+    buf = ctypes.create_string_buffer(256)
+    st = lib().ds_step_static(ctypes.byref(cfg), x.data_ptr(), delta.data_ptr(), x.stride(0), g.data_ptr(), g.stride(0),
+                              msg.data_ptr(), t, s.cuda_stream, buf, 256)
+    if st != DS_OK:
+        raise DsqError(st, "ds_step_static", buf.value.decode())
 
 
 class DeepSqueeze:

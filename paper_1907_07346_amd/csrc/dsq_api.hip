@@ -251,9 +251,122 @@ __global__ void __launch_bounds__(256) stream_3r2w_kernel(f32x4* __restrict__ x,
     }
 }
 
+// ---- ds_step_static: one step with no handle and no allocation ------------------------------------------------
+// Everything the fused tile kernel needs beyond the caller's arrays -- the step-counter cells with its
+// finished-workgroup counters, and W - I in CSR form -- lives in this file-scope device array.  Every GPU the
+// library runs on holds its own copy until the process ends.  In host code the array's name is only a stand-in:
+// its device address is asked for once per device (static_scratch) and that pointer is what kernels get.
+constexpr int kStaticMaxWorkers = 1024;
+constexpr int kStaticMaxDegree = 5;                                           // ring 3, torus 5 (diagonal included)
+constexpr size_t kStaticGraphWords = (size_t)kStaticMaxWorkers + 1 + 2 * (size_t)kStaticMaxDegree * kStaticMaxWorkers;
+constexpr size_t kStaticCellBytes = dsq::kStepCells * sizeof(unsigned long long);
+constexpr size_t kStaticBytes = kStaticCellBytes + kStaticGraphWords * sizeof(int32_t);   // 16,640 + 45,060 bytes
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (asked for on the first call per device); nullptr on failure.
+unsigned char* static_scratch(int device, std::string& err) {
+    if (device < 0 || device >= kMaxDevices) { err = "device index beyond the 64 this entry point keeps an address for"; return nullptr; }
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e); return nullptr; }
+        g_scratch_ptr[device] = static_cast<unsigned char*>(p);
+    }
+    return g_scratch_ptr[device];
+}
+
+// One workgroup: the step-counter cells (t, everything else zero, no keep counts) and the CSR of W - I of a
+// ring or a 2-D torus, rows in ascending neighbour index as ds_init builds them.
+__global__ void __launch_bounds__(256) static_setup_kernel(unsigned char* base, int n, int topo, int torus_rows, int torus_cols,
+                                                           float w, float w_diag, unsigned long long t) {
+    unsigned long long* cells = reinterpret_cast<unsigned long long*>(base);
+    for (size_t q = threadIdx.x; q < dsq::kStepCells; q += 256) cells[q] = (q == 0) ? t : (q == 2) ? ~0ull : 0ull;
+    const int deg = (topo == DS_TOPO_RING) ? 3 : 5;
+    int32_t* rowptr = reinterpret_cast<int32_t*>(base + kStaticCellBytes);
+    int32_t* col = rowptr + n + 1;
+    float* coef = reinterpret_cast<float*>(col + (size_t)deg * n);
+    for (int i = threadIdx.x; i <= n; i += 256) rowptr[i] = deg * i;
+    for (int i = threadIdx.x; i < n; i += 256) {
+        int nb[5];
+        if (topo == DS_TOPO_RING) {
+            nb[0] = (i + n - 1) % n; nb[1] = i; nb[2] = (i + 1) % n;
+        } else {
+            const int r = i / torus_cols, c = i % torus_cols;
+            nb[0] = i;
+            nb[1] = ((r + 1) % torus_rows) * torus_cols + c;
+            nb[2] = ((r + torus_rows - 1) % torus_rows) * torus_cols + c;
+            nb[3] = r * torus_cols + (c + 1) % torus_cols;
+            nb[4] = r * torus_cols + (c + torus_cols - 1) % torus_cols;
+        }
+        for (int a = 1; a < deg; ++a)                                          // ascending neighbour index
+            for (int b = a; b > 0 && nb[b - 1] > nb[b]; --b) { const int tmp = nb[b]; nb[b] = nb[b - 1]; nb[b - 1] = tmp; }
+        for (int e = 0; e < deg; ++e) {
+            col[(size_t)deg * i + e] = nb[e];
+            coef[(size_t)deg * i + e] = (nb[e] == i) ? w_diag : w;
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" {
+
+ds_status ds_step_static(const ds_config* cfg, float* x_dev, float* delta_dev, uint64_t ld, const float* g_dev, uint64_t g_ld,
+                         void* msg_dev, uint64_t t, void* hip_stream, char* errbuf, uint64_t errbuf_len) {
+    std::string err, warn;
+    auto fail_with = [&](ds_status st, const std::string& m) {
+        if (errbuf && errbuf_len) std::snprintf(errbuf, (size_t)errbuf_len, "%s", m.c_str());
+        return st;
+    };
+    if (dsq::validate_config(cfg, err, &warn) != DS_OK) return fail_with(DS_EINVAL, err);
+    const int kind = cfg->comp.kind;
+    if (kind != DS_COMP_QUANT_MAXABS && kind != DS_COMP_SIGN_MEANABS && kind != DS_COMP_IDENTITY)
+        return fail_with(DS_EINVAL, "ds_step_static serves the block quantiser, the sign compressor and the identity only "
+                                    "(the other compressors need scratch memory in proportion to N)");
+    if (cfg->topo != DS_TOPO_RING && cfg->topo != DS_TOPO_TORUS2D)
+        return fail_with(DS_EINVAL, "ds_step_static builds W on the device: DS_TOPO_RING or DS_TOPO_TORUS2D only");
+    if (cfg->n > kStaticMaxWorkers)
+        return fail_with(DS_EINVAL, "ds_step_static: n exceeds the 1024 workers its static scratch array has room for");
+    if (!x_dev || !delta_dev || !g_dev || !msg_dev) return fail_with(DS_EINVAL, "a device pointer is NULL");
+    if ((ld & 3) || ld < (cfg->N + dsq::kPitchAlign - 1) / dsq::kPitchAlign * dsq::kPitchAlign)
+        return fail_with(DS_EINVAL, "ld must be a multiple of 4 and at least N rounded up to a multiple of 4096");
+    if (g_ld < cfg->N || (g_ld & 3)) return fail_with(DS_EINVAL, "g_ld must be >= N and a multiple of 4");
+    if ((reinterpret_cast<uintptr_t>(x_dev) | reinterpret_cast<uintptr_t>(delta_dev) | reinterpret_cast<uintptr_t>(g_dev)) & 15)
+        return fail_with(DS_EINVAL, "x_dev, delta_dev and g_dev must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(msg_dev) & 3) return fail_with(DS_EINVAL, "msg_dev must be 4-byte aligned");
+    const int deg = cfg->topo == DS_TOPO_RING ? 3 : 5;
+    const int nnz = deg * cfg->n;
+    std::vector<dsq::TilePlan> plans;
+    if (!dsq::choose_tile_plans(*cfg, nnz, plans, err)) return fail_with(DS_EINVAL, err);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return fail_with(DS_EHIP, "no current HIP device");
+    unsigned char* base = static_scratch(dev, err);
+    if (!base) return fail_with(DS_EHIP, err);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const float w = (cfg->topo == DS_TOPO_RING) ? 1.0f / 3.0f : 1.0f / 5.0f;
+    hipLaunchKernelGGL(static_setup_kernel, dim3(1), dim3(256), 0, stream, base, cfg->n, cfg->topo, cfg->torus_rows,
+                       cfg->torus_cols, w, w - 1.0f, (unsigned long long)t);
+    dsq::TileArgs a{};
+    a.x = x_dev; a.delta = delta_dev; a.g = g_dev; a.msg = static_cast<uint8_t*>(msg_dev);
+    a.rowptr = reinterpret_cast<const int32_t*>(base + kStaticCellBytes);
+    a.col = a.rowptr + cfg->n + 1;
+    a.coef = reinterpret_cast<const float*>(a.col + nnz);
+    a.ld = ld; a.g_ld = g_ld; a.N = cfg->N; a.msg_row_bytes = dsq::message_row_bytes(cfg);
+    a.n = cfg->n; a.nnz = nnz;
+    a.gamma = cfg->gamma; a.eta = cfg->eta;
+    a.seed_lo = (uint32_t)cfg->seed; a.seed_hi = (uint32_t)(cfg->seed >> 32);
+    a.t_ptr = reinterpret_cast<unsigned long long*>(base);
+    a.pending = reinterpret_cast<uint32_t*>(a.t_ptr + 3);
+    const dsq::TilePlan& plan = plans.front();
+    plan.launch(a, plan.rows_per_wave, stream);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_with(DS_EHIP, std::string("launching the step failed: ") + hipGetErrorString(e));
+    if (errbuf && errbuf_len) std::snprintf(errbuf, (size_t)errbuf_len, "%s", warn.c_str());
+    return DS_OK;
+}
 
 ds_status ds_workload_gradient(const ds_workload* w, uint64_t t, const float* x_dev, uint64_t x_ld, float* g_dev,
                                uint64_t g_ld, void* hip_stream) {
