@@ -6,21 +6,28 @@
 // leaves everything else in delta, lines 7-8 "send" the k pairs, line 9 mixes the neighbours'
 // sparse vectors into x.
 //
-// The select is an MSB-first radix select on key = bits(v) & 0x7fffffff (order preserving for
-// finite |v|): 11 + 11 + 9 bits, workgroup histograms in LDS, three tiny per-row select kernels
-// that end with the exact threshold key tau and the number r_tie of elements equal to tau that
-// still belong to the set.  Ordered output (ascending index: the tie rule and a canonical
-// message need it) comes from per-chunk counts, a per-row scan over chunks and an ordered
-// compaction inside each chunk.
+// Keys: key = bits(v) & 0x7fffffff (order preserving for finite |v|).  The select ends with the exact
+// threshold key tau and the number r_tie of elements equal to tau that still belong to the set.  Ordered
+// output (ascending index: the tie rule and a canonical message need it) comes from per-chunk counts, a
+// per-row scan over chunks and an ordered compaction inside each chunk.
 //
 // Two sources feed the select, chosen per row on the device with no host round trip:
-//   * candidate mode (the fast path): the pass that forms v also appends every element whose key
-//     reaches a per-row guess `tlo` (extrapolated from the previous steps' thresholds, aimed at
-//     about 3 k elements) to a small per-chunk slot.  If at least k candidates were collected
-//     and no slot overflowed, the whole select runs on the slots (a few % of N) and v is never
-//     read again.
-//   * full mode (always exact, used on the first step and whenever the guess fails): the same
-//     select with histogram passes over v itself.
+//   * candidate mode (the fast path): the pass that forms v also appends every element whose key reaches a
+//     per-row guess `tlo` (aimed at about 1.6 k elements from the previous step's catch and the drift of the
+//     threshold) to a small per-chunk slot, with a level-1 histogram (bins of 2^20 keys) of those keys.  If
+//     at least k candidates were collected and no slot overflowed, small kernels finish the step without
+//     reading v again:
+//       topk_decide_select  per row: the level-1 bin that holds the threshold, and how many to take inside
+//       topk_hist_cand2     the slots' level-2 histogram (bins of 512 keys) inside that bin
+//       topk_select2_cand   per row: the level-2 bin of the threshold
+//       topk_bin_collect    per chunk: candidates above that bin counted; the few inside it listed per row
+//       topk_finish         per row: exact tau and r_tie from the list, per-chunk counts, scan over chunks
+//       topk_write_cand     per chunk: the ordered message from the slot
+//   * full mode (always exact, used on the first step and whenever the guess fails): an MSB-first radix
+//     select over v itself, 11 + 11 + 9 bits, workgroup histograms in LDS, every workgroup of a pass
+//     working out the previous level's bin for itself.  Its kernels run on a small grid-stride grid and
+//     return at once for rows in candidate mode, so a step that needs none of them pays a few microseconds
+//     for their launches.
 // Both end in the same tau, r_tie, per-chunk counts and message, so results never depend on the
 // guess; only speed does.
 //
@@ -42,18 +49,22 @@ constexpr int TK_ITERS = 4;
 constexpr int TK_CHUNK = TK_VEC * TK_ITERS;  // columns per chunk (one workgroup of the streaming passes)
 constexpr int TK_CAP = 512;                  // candidate slots per chunk (12.5 % of the chunk)
 constexpr int TK_H1 = 256;                   // level-1 bins the first pass tracks, counted from tlo's bin upwards
-constexpr int TK_CPW = 8;                    // chunks per workgroup in topk_fix_cand
-constexpr int TK_FPW = 8;                    // chunks per workgroup in the full-mode kernels (few, cheap-to-skip workgroups)
-constexpr int TK_HWG = 16;                   // workgroups per row in the candidate-mode histogram passes
+constexpr int TK_HWG = 16;                   // workgroups per row in topk_hist_cand2 and topk_bin_collect
 constexpr int TK_HTHREADS = 1024;            // threads of those workgroups
-constexpr int BINS1 = 2048, SHIFT1 = 20;     // key bits 30..20
-constexpr int BINS2 = 2048, SHIFT2 = 9;      // key bits 19..9
-constexpr int BINS3 = 512;                   // key bits 8..0
+constexpr int TK_FWG = 64;                   // full-mode workgroups per row (grid-stride over the row's chunks)
+constexpr int TK_WPW = 8;                    // chunks per wave (= workgroup) in topk_write_cand
+constexpr int TK_RTHREADS = 1024;            // threads of the per-row kernels
+constexpr int BINS1 = 2048, SHIFT1 = 20;     // level 1: key bits 30..20
+constexpr int BINS2 = 2048, SHIFT2 = 9;      // level 2: key bits 19..9
+constexpr int BINS3 = 512;                   // level 3: key bits 8..0
 constexpr int HIST_BINS = 2048;
+constexpr uint32_t FINE_SPAN = 1u << SHIFT2; // keys in a level-2 bin
+constexpr uint32_t TK_LIST_CAP = 8192;       // candidates inside the threshold's level-2 bin a row can list
+constexpr float TK_TARGET = 1.6f;            // candidates aimed at, in units of k
 
 struct TopkRow {
-    uint32_t prefix1, need1;   // level-1 bin holding the threshold; how many to take inside it
-    uint32_t prefix2, need2;   // 22-bit prefix of the threshold key; how many to take among its matches
+    uint32_t prefix1, need1;   // full mode: level-1 bin holding the threshold; how many to take inside it
+    uint32_t prefix2, need2;   // full mode: 22-bit prefix of the threshold key; how many to take among its matches
     uint32_t tau, r_tie;       // threshold key; number of elements with key == tau to take (lowest indices)
     uint32_t total;            // number of selected elements found by the scan (must equal k)
     uint32_t tlo;              // candidate threshold key for the next first pass (0xffffffff: collect nothing)
@@ -62,7 +73,10 @@ struct TopkRow {
     uint32_t cand_total;       // candidates collected in this step
     uint32_t tlo_used;         // the threshold this step's first pass collected with
     uint32_t tau_prev;         // threshold key of the previous step (0xffffffff: none yet)
-    uint32_t pad;
+    uint32_t bin_lo;           // candidate mode: first key of the histogram bin that holds the threshold
+    uint32_t bin_need;         //                 how many elements to take inside that bin
+    uint32_t list_count;       //                 elements of that bin listed so far by topk_bin_collect
+    float drift_prev;          // last step's movement of |tau| as a float (for the forecast of the next threshold)
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -107,7 +121,9 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_sums) {
 }
 
 struct Scratch {               // device pointers of the select's scratch (all owned by TopkState)
-    uint32_t* hist;            // n x 2048
+    uint32_t* hist;            // n x 2048: level-1 histogram (candidates of the first pass, or all keys in full mode)
+    uint32_t* hist2;           // n x 2048: level 2
+    uint32_t* hist3;           // n x 512:  level 3 (full mode)
     TopkRow* rows;             // n
     uint32_t* cnt_gt;          // n x nchunks: keys above the threshold (prefix) in the chunk
     uint32_t* cnt_eq;          // n x nchunks: keys equal to the threshold (prefix) in the chunk
@@ -117,8 +133,32 @@ struct Scratch {               // device pointers of the select's scratch (all o
     uint32_t* slot_val;        // n x nchunks x TK_CAP candidate values (fp32 bits), unordered inside a slot; the select
                                // passes read only these
     uint16_t* slot_idx;        // same shape: the candidates' columns, relative to the start of the chunk
+    uint2* list;               // n x TK_LIST_CAP: (key, chunk) of the candidates inside the threshold's histogram bin
     uint32_t nchunks;
 };
+
+// Scans over the TK_RTHREADS threads of a per-row workgroup.
+__device__ __forceinline__ uint32_t row_exclusive_scan(uint32_t v, uint32_t* wave_sums /*[16]*/, uint32_t* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(inc, o);
+        if (lane >= o) inc += up;
+    }
+    __syncthreads();                       // wave_sums may still be read from a previous call
+    if (lane == 63) wave_sums[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < TK_RTHREADS / 64; ++w) {
+        const uint32_t sm = wave_sums[w];
+        if (w < wave) base += sm;
+        tot += sm;
+    }
+    *total = tot;
+    return base + inc - v;
+}
 
 // ---- pass 1: pending gossip of the previous step, Algorithm 1 line 5, candidate collection ------
 __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scratch s) {
@@ -136,22 +176,28 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     float* xr = a.x + (uint64_t)row * a.ld;
     float* dr = a.delta + (uint64_t)row * a.ld;
     const float* gr = a.g + (uint64_t)row * a.g_ld;
+    // x and delta rows are padded to whole chunks (the pitch is a multiple of the chunk plus a skew), so only g
+    // needs care, and only in the row's last chunk: everywhere else the twelve loads go out back to back with
+    // nothing between them that could make one wait for another.
     float4 xin[TK_ITERS], din[TK_ITERS], gin[TK_ITERS];
+    if (c0 + TK_CHUNK <= a.N) {                                // uniform
 #pragma unroll
-    for (int it = 0; it < TK_ITERS; ++it) {
-        const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
-        xin[it] = din[it] = gin[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (j < a.ld) {
+        for (int it = 0; it < TK_ITERS; ++it) {
+            const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
             xin[it] = ld4_stream(xr + j);
             din[it] = ld4_stream(dr + j);
-            if (j + 3 < a.N) {
-                gin[it] = ld4_stream(gr + j);
-            } else {
-                gin[it].x = (j + 0 < a.N) ? gr[j + 0] : 0.f;
-                gin[it].y = (j + 1 < a.N) ? gr[j + 1] : 0.f;
-                gin[it].z = (j + 2 < a.N) ? gr[j + 2] : 0.f;
-                gin[it].w = (j + 3 < a.N) ? gr[j + 3] : 0.f;
-            }
+            gin[it] = ld4_stream(gr + j);
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < TK_ITERS; ++it) {
+            const uint64_t j = c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x;
+            xin[it] = ld4_stream(xr + j);
+            din[it] = ld4_stream(dr + j);
+            gin[it].x = (j + 0 < a.N) ? gr[j + 0] : 0.f;
+            gin[it].y = (j + 1 < a.N) ? gr[j + 1] : 0.f;
+            gin[it].z = (j + 2 < a.N) ? gr[j + 2] : 0.f;
+            gin[it].w = (j + 3 < a.N) ? gr[j + 3] : 0.f;
         }
     }
     bool patch = false;
@@ -194,7 +240,6 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     for (int it = 0; it < TK_ITERS; ++it) {
         const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
         const uint64_t j = c0 + q0;
-        if (j >= a.ld) break;
         float4 xv = xin[it], dv = din[it];
         const float4 gv = gin[it];
         if (patch) {                                // lines 6 and 9 of the previous step
@@ -226,8 +271,8 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
             }
     }
     __syncthreads();
-    // the row histogram is used if the row ends up in candidate mode and wiped by topk_decide otherwise;
-    // a candidate beyond the tracked bins (256 bins = 2^32 in magnitude above tlo) sends the row there too
+    // the row histogram is used if the row ends up in candidate mode and wiped by topk_decide_select either way;
+    // a candidate beyond the tracked bins (256 bins = 2^32 in magnitude above tlo) sends the row the exact way
     uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
     for (int b = threadIdx.x; b < TK_H1; b += TK_THREADS)
         if (h[b]) atomicAdd(&hrow[bin0 + b], h[b]);
@@ -239,28 +284,117 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     }
 }
 
-// ---- per row: did the guess work?  (candidates >= k and no slot overflow) ----------------------
-__global__ void __launch_bounds__(TK_THREADS) topk_decide(Scratch s, uint32_t k) {
-    __shared__ uint32_t wave_sums[TK_THREADS / 64];
-    const int row = blockIdx.x;
-    uint32_t sum = 0;
-    for (uint32_t c = threadIdx.x; c < s.nchunks; c += TK_THREADS) sum += s.cand_cnt[(size_t)row * s.nchunks + c];
-    const uint32_t total = block_sum(sum, wave_sums);
-    const bool cand = total >= k && s.rows[row].overflow == 0;
-    if (!cand)                                             // full mode builds its own level-1 histogram
-        for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS) s.hist[(size_t)row * HIST_BINS + b] = 0;
+// ---- digit select on a row histogram: the bin where the count from the top crosses `need` ----------
+// 256 threads, 8 consecutive bins each, largest keys first.  res (LDS): [0] bin, [1] how many to take inside
+// it, [2] elements in it, [3] all elements counted.  A crossing exists whenever need <= the total count.
+__device__ __forceinline__ void select_digit(const uint32_t* hrow, int bins, uint32_t need, uint32_t* wave_sums, uint32_t* res) {
+    constexpr int PER = HIST_BINS / TK_THREADS;
+    uint32_t mine[PER], sum = 0;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int b = HIST_BINS - 1 - (threadIdx.x * PER + q);
+        mine[q] = (b < bins) ? hrow[b] : 0u;
+        sum += mine[q];
+    }
+    uint32_t total;
+    uint32_t above = block_exclusive_scan(sum, wave_sums, &total);     // keys in strictly higher bins
+    if (threadIdx.x == 0) { res[0] = 0; res[1] = 0; res[2] = 0; res[3] = total; }
     __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int b = HIST_BINS - 1 - (threadIdx.x * PER + q);
+        if (above < need && need <= above + mine[q]) { res[0] = (uint32_t)b; res[1] = need - above; res[2] = mine[q]; }
+        above += mine[q];
+    }
+    __syncthreads();
+}
+
+// ---- candidate mode, per row: did the guess work, and which level-1 bin holds the threshold? -----
+// The row is in candidate mode if at least k candidates were collected and no slot overflowed.  Leaves all
+// three histograms of the row clean.
+__global__ void __launch_bounds__(TK_THREADS) topk_decide_select(Scratch s, uint32_t k) {
+    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    __shared__ uint32_t res[4];
+    const int row = blockIdx.x;
+    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
+    TopkRow& r = s.rows[row];
+    select_digit(hrow, BINS1, k, wave_sums, res);
+    for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS) { hrow[b] = 0; s.hist2[(size_t)row * HIST_BINS + b] = 0; }
+    for (int b = threadIdx.x; b < BINS3; b += TK_THREADS) s.hist3[(size_t)row * BINS3 + b] = 0;
     if (threadIdx.x == 0) {
-        TopkRow& r = s.rows[row];
-        r.cand_total = total;
+        const uint32_t total = res[3];
+        const bool cand = total >= k && r.overflow == 0 && r.tlo != 0xFFFFFFFFu;
+        if (cand) { r.prefix1 = res[0]; r.need1 = res[1]; }
         r.cand_mode = cand ? 1u : 0u;
+        r.cand_total = total;
         r.overflow = 0;
         r.tlo_used = r.tlo;
+        r.list_count = 0;
     }
 }
 
-// ---- digit histograms.  LEVEL 1: all keys; 2: keys matching prefix1; 3: keys matching prefix2,
-//      plus per-chunk counts of keys above / inside the 22-bit prefix. -------------------------------
+// ---- candidate mode: level-2 histogram of the slots' keys inside the threshold's level-1 bin --------
+// TK_HWG workgroups of 1024 threads per row, each walking a contiguous range of chunks with 16 lanes per
+// chunk (64 chunks side by side) and 8 slot loads in flight per lane.  Few, large workgroups keep the number
+// of global histogram atomics down (one flush of <= 2048 bins each).
+__global__ void __launch_bounds__(TK_HTHREADS) topk_hist_cand2(Scratch s) {
+    __shared__ uint32_t h[HIST_BINS];
+    const int row = blockIdx.y;
+    if (!s.rows[row].cand_mode) return;                        // uniform
+    for (int b = threadIdx.x; b < HIST_BINS; b += TK_HTHREADS) h[b] = 0;
+    __syncthreads();
+    const uint32_t prefix = s.rows[row].prefix1;
+    constexpr int TPC = 16, SIDE = TK_HTHREADS / TPC;          // lanes per chunk, chunks side by side
+    const int sub = threadIdx.x % TPC;
+    const uint32_t per_wg = (s.nchunks + TK_HWG - 1) / TK_HWG;
+    const uint32_t first = blockIdx.x * per_wg;
+    const uint32_t last = (first + per_wg < s.nchunks) ? first + per_wg : s.nchunks;
+    const uint32_t* cand_cnt = s.cand_cnt + (size_t)row * s.nchunks;
+    uint32_t chunk = first + threadIdx.x / TPC;
+    uint32_t cnt = chunk < last ? cand_cnt[chunk] : 0u;        // the next chunk's count is asked for one turn ahead
+    for (; chunk < last; chunk += SIDE) {
+        const uint32_t cnt_next = (chunk + SIDE < last) ? cand_cnt[chunk + SIDE] : 0u;
+        const uint32_t* slot = s.slot_val + ((size_t)row * s.nchunks + chunk) * TK_CAP;
+        for (uint32_t p0 = sub; p0 < cnt; p0 += 8 * TPC) {
+            uint32_t key[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC] & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (key[u] != 0xFFFFFFFFu && (key[u] >> SHIFT1) == prefix) atomicAdd(&h[(key[u] >> SHIFT2) & (BINS2 - 1)], 1u);
+        }
+        cnt = cnt_next;
+    }
+    __syncthreads();
+    uint32_t* hrow = s.hist2 + (size_t)row * HIST_BINS;
+    for (int b = threadIdx.x; b < HIST_BINS; b += TK_HTHREADS)
+        if (h[b]) atomicAdd(&hrow[b], h[b]);
+}
+
+// ---- candidate mode, per row: the level-2 bin of the threshold ------------------------------------
+// A bin with more elements than a row can list (many equal or nearly equal keys) sends the row the exact way.
+__global__ void __launch_bounds__(TK_THREADS) topk_select2_cand(Scratch s) {
+    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    __shared__ uint32_t res[4];
+    const int row = blockIdx.x;
+    TopkRow& r = s.rows[row];
+    if (!r.cand_mode) return;                                  // uniform
+    uint32_t* hrow = s.hist2 + (size_t)row * HIST_BINS;
+    select_digit(hrow, BINS2, r.need1, wave_sums, res);
+    for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS) hrow[b] = 0;     // full mode may need it clean
+    if (threadIdx.x == 0) {
+        if (res[1] == 0 || res[2] > TK_LIST_CAP) {
+            r.cand_mode = 0;
+        } else {
+            r.bin_lo = ((r.prefix1 << (SHIFT1 - SHIFT2)) | res[0]) << SHIFT2;
+            r.bin_need = res[1];
+        }
+    }
+}
+
+// ---- full mode: digit histograms over v.  LEVEL 1: all keys; 2: keys matching prefix1; 3: keys matching
+//      prefix2, plus per-chunk counts of keys above / inside the 22-bit prefix.  From level 2 on every
+//      workgroup first works out the previous level's bin from that level's (complete) histogram. ---------
 template <int LEVEL>
 __device__ __forceinline__ void hist_key(uint32_t key, uint32_t prefix, uint32_t* h, uint32_t& gt, uint32_t& eq) {
     if (LEVEL == 1) {
@@ -275,17 +409,28 @@ __device__ __forceinline__ void hist_key(uint32_t key, uint32_t prefix, uint32_t
 }
 
 template <int LEVEL>
-__global__ void __launch_bounds__(TK_THREADS) topk_hist_full(const float* __restrict__ delta, uint64_t ld, uint64_t N, Scratch s) {
+__global__ void __launch_bounds__(TK_THREADS) topk_hist_full(const float* __restrict__ delta, uint64_t ld, uint64_t N, Scratch s, uint32_t k) {
     __shared__ uint32_t h[HIST_BINS];
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    __shared__ uint32_t res[4];
     const int row = blockIdx.y;
-    if (s.rows[row].cand_mode) return;                         // uniform
+    TopkRow& r = s.rows[row];
+    if (r.cand_mode) return;                                   // uniform
     constexpr int BINS = (LEVEL == 3) ? BINS3 : HIST_BINS;
     for (int b = threadIdx.x; b < BINS; b += TK_THREADS) h[b] = 0;
+    uint32_t prefix = 0;
+    if (LEVEL == 2) {
+        select_digit(s.hist + (size_t)row * HIST_BINS, BINS1, k, wave_sums, res);
+        prefix = res[0];
+        if (blockIdx.x == 0 && threadIdx.x == 0) { r.prefix1 = res[0]; r.need1 = res[1]; }
+    } else if (LEVEL == 3) {
+        select_digit(s.hist2 + (size_t)row * HIST_BINS, BINS2, r.need1, wave_sums, res);
+        prefix = (r.prefix1 << (SHIFT1 - SHIFT2)) | res[0];
+        if (blockIdx.x == 0 && threadIdx.x == 0) { r.prefix2 = prefix; r.need2 = res[1]; }
+    }
     __syncthreads();
-    const uint32_t prefix = (LEVEL == 2) ? s.rows[row].prefix1 : (LEVEL == 3) ? s.rows[row].prefix2 : 0u;
     const float* dr = delta + (uint64_t)row * ld;
-    for (uint32_t chunk = blockIdx.x * TK_FPW; chunk < (blockIdx.x + 1) * TK_FPW && chunk < s.nchunks; ++chunk) {
+    for (uint32_t chunk = blockIdx.x; chunk < s.nchunks; chunk += gridDim.x) {
         const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
         uint32_t gt = 0, eq = 0;
 #pragma unroll 2
@@ -308,128 +453,25 @@ __global__ void __launch_bounds__(TK_THREADS) topk_hist_full(const float* __rest
         }
     }
     __syncthreads();
-    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
+    uint32_t* hrow = (LEVEL == 1) ? s.hist + (size_t)row * HIST_BINS : (LEVEL == 2) ? s.hist2 + (size_t)row * HIST_BINS
+                                                                                     : s.hist3 + (size_t)row * BINS3;
     for (int b = threadIdx.x; b < BINS; b += TK_THREADS)
         if (h[b]) atomicAdd(&hrow[b], h[b]);
 }
 
-// Candidate mode: TK_HWG workgroups of 1024 threads per row, each walking a contiguous range of chunks
-// with 32 lanes per chunk (32 chunks side by side) and 8 slot loads in flight per lane.  Few, large
-// workgroups keep the number of global histogram atomics down (one flush of <= 2048 bins each).
-template <int LEVEL>
-__global__ void __launch_bounds__(TK_HTHREADS) topk_hist_cand(Scratch s) {
-    __shared__ uint32_t h[HIST_BINS];
-    const int row = blockIdx.y;
-    if (!s.rows[row].cand_mode) return;                        // uniform
-    constexpr int BINS = (LEVEL == 3) ? BINS3 : HIST_BINS;
-    for (int b = threadIdx.x; b < BINS; b += TK_HTHREADS) h[b] = 0;
-    __syncthreads();
-    const uint32_t prefix = (LEVEL == 2) ? s.rows[row].prefix1 : s.rows[row].prefix2;
-    constexpr int TPC = 32, SIDE = TK_HTHREADS / TPC;          // lanes per chunk, chunks side by side
-    const int sub = threadIdx.x % TPC;
-    const uint32_t per_wg = (s.nchunks + TK_HWG - 1) / TK_HWG;
-    const uint32_t first = blockIdx.x * per_wg;
-    const uint32_t last = (first + per_wg < s.nchunks) ? first + per_wg : s.nchunks;
-    for (uint32_t chunk = first + threadIdx.x / TPC; chunk < last; chunk += SIDE) {
-        const size_t cidx = (size_t)row * s.nchunks + chunk;
-        const uint32_t cnt = s.cand_cnt[cidx];
-        const uint32_t* slot = s.slot_val + cidx * TK_CAP;
-        uint32_t gt = 0, eq = 0;
-        for (uint32_t p0 = sub; p0 < cnt; p0 += 8 * TPC) {
-            uint32_t key[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC] & 0x7FFFFFFFu) : 0xFFFFFFFFu;
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (key[u] != 0xFFFFFFFFu) hist_key<LEVEL>(key[u], prefix, h, gt, eq);
-        }
-        if (LEVEL == 3) {
-            // the 32 lanes of a chunk are half a wave: fold with shuffles inside the half
-#pragma unroll
-            for (int o = 1; o < TPC; o <<= 1) { gt += __shfl_xor(gt, o); eq += __shfl_xor(eq, o); }
-            if (sub == 0) { s.cnt_gt[cidx] = gt; s.cnt_eq[cidx] = eq; }
-        }
-    }
-    __syncthreads();
-    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
-    for (int b = threadIdx.x; b < BINS; b += TK_HTHREADS)
-        if (h[b]) atomicAdd(&hrow[b], h[b]);
-}
-
-// ---- where to collect candidates in the next step ------------------------------------------------
-// Keys are (piecewise) logarithmic in |v|, and near the threshold the number of keys above a level
-// falls roughly exponentially with the level.  With d = tau - tlo the distance that caught
-// ratio * k candidates this step, the distance that would catch 3 k is d* = d ln 3 / ln ratio.  The
-// threshold itself moves from step to step (delta keeps growing early in a run), so the next level
-// is aimed at tau + 3/4 drift - d*.  Without usable candidates (full mode) a fixed distance of two
-// level-1 bins is taken.  Only speed depends on this guess; a bad one sends the row through the exact full path.
-__device__ __forceinline__ uint32_t next_candidate_threshold(const TopkRow& r, uint32_t tau, uint32_t k) {
-    const float d0 = 2.f * (float)(1u << SHIFT1);
-    float dstar = d0;
-    if (r.cand_mode && r.cand_total > k && tau > r.tlo_used) {
-        const float ratio = (float)r.cand_total / (float)k;
-        const float d = (float)(tau - r.tlo_used);
-        dstar = d * (1.0986123f / logf(ratio));
-        dstar = fminf(fmaxf(dstar, 1024.f), 4.f * d0);
-    }
-    float drift = 0.f;
-    if (r.tau_prev != 0xFFFFFFFFu && tau > r.tau_prev) drift = fminf((float)(tau - r.tau_prev), 8.f * d0);
-    // the drift decays as a run settles: three quarters of the last one is the forecast
-    const float t = (float)tau + 0.75f * drift - dstar;
-    return t > 0.f ? (uint32_t)t : 0u;
-}
-
-// ---- per-row digit select: the bin where the count from the top crosses `need` -----------------
-// Level 3 ends with the threshold key and also aims the candidate collection of the next step.
-template <int LEVEL>
-__global__ void __launch_bounds__(TK_THREADS) topk_select(Scratch s, uint32_t k) {
-    __shared__ uint32_t wave_sums[TK_THREADS / 64];
-    const int row = blockIdx.x;
-    constexpr int BINS = (LEVEL == 1) ? BINS1 : (LEVEL == 2) ? BINS2 : BINS3;
-    constexpr int PER = HIST_BINS / TK_THREADS;           // 8 consecutive bins per thread
-    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
-    TopkRow& r = s.rows[row];
-    const uint32_t need = (LEVEL == 1) ? k : (LEVEL == 2) ? r.need1 : r.need2;
-    // thread t owns bins [top - 8t - 7, top - 8t], i.e. threads are ordered from the largest keys down
-    uint32_t mine[PER];
-    uint32_t sum = 0;
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-        const int b = HIST_BINS - 1 - (threadIdx.x * PER + q);
-        mine[q] = (b < BINS) ? hrow[b] : 0u;
-        sum += mine[q];
-    }
-    uint32_t total;
-    uint32_t above = block_exclusive_scan(sum, wave_sums, &total);   // keys in strictly higher bins
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-        const int b = HIST_BINS - 1 - (threadIdx.x * PER + q);
-        if (above < need && need <= above + mine[q]) {
-            const uint32_t rem = need - above;
-            if (LEVEL == 1)      { r.prefix1 = (uint32_t)b; r.need1 = rem; }
-            else if (LEVEL == 2) { r.prefix2 = (r.prefix1 << (SHIFT1 - SHIFT2)) | (uint32_t)b; r.need2 = rem; }
-            else {
-                const uint32_t tau = (r.prefix2 << SHIFT2) | (uint32_t)b;
-                r.tlo = next_candidate_threshold(r, tau, k);
-                r.tau_prev = tau;
-                r.tau = tau;
-                r.r_tie = rem;
-            }
-        }
-        above += mine[q];
-        hrow[b] = 0;                                      // leave the histogram clean for the next pass
-    }
-}
-
-// ---- exact per-chunk counts: only chunks that hold a key with the threshold's 22-bit prefix -----
+// ---- full mode: the threshold key from the level-3 histogram, then exact per-chunk counts for the chunks
+//      that hold a key with the threshold's 22-bit prefix ---------------------------------------------------
 __global__ void __launch_bounds__(TK_THREADS) topk_fix_full(const float* __restrict__ delta, uint64_t ld, uint64_t N, Scratch s) {
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    __shared__ uint32_t res[4];
     const int row = blockIdx.y;
-    if (s.rows[row].cand_mode) return;
-    const uint32_t tau = s.rows[row].tau;
+    TopkRow& r = s.rows[row];
+    if (r.cand_mode) return;
+    select_digit(s.hist3 + (size_t)row * BINS3, BINS3, r.need2, wave_sums, res);
+    const uint32_t tau = (r.prefix2 << SHIFT2) | res[0];
+    if (blockIdx.x == 0 && threadIdx.x == 0) { r.tau = tau; r.r_tie = res[1]; }
     const float* dr = delta + (uint64_t)row * ld;
-    for (uint32_t chunk = blockIdx.x * TK_FPW; chunk < (blockIdx.x + 1) * TK_FPW && chunk < s.nchunks; ++chunk) {
+    for (uint32_t chunk = blockIdx.x; chunk < s.nchunks; chunk += gridDim.x) {
         const size_t ci = (size_t)row * s.nchunks + chunk;
         if (s.cnt_eq[ci] == 0) continue;                  // uniform: nothing in this chunk can tie or straddle
         const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
@@ -453,76 +495,197 @@ __global__ void __launch_bounds__(TK_THREADS) topk_fix_full(const float* __restr
     }
 }
 
-__global__ void __launch_bounds__(TK_THREADS) topk_fix_cand(Scratch s) {
-    __shared__ uint32_t c_gt[TK_CPW], c_eq[TK_CPW];
+// ---- candidate mode, per chunk: candidates above the threshold's bin counted, those inside it listed ----
+// The walk of topk_hist_cand2 (16 lanes per chunk, counts asked for one turn ahead).  The bin holds a few
+// hundred elements of a whole row (it is 512 keys wide), so the list is short and its appends (one returning
+// atomic each) are rare.
+__global__ void __launch_bounds__(TK_HTHREADS) topk_bin_collect(Scratch s) {
     const int row = blockIdx.y;
-    if (!s.rows[row].cand_mode) return;
-    if (threadIdx.x < TK_CPW) { c_gt[threadIdx.x] = 0; c_eq[threadIdx.x] = 0; }
-    __syncthreads();
-    const uint32_t tau = s.rows[row].tau;
-    constexpr int TPC = TK_THREADS / TK_CPW;
-    const int ci = threadIdx.x / TPC, sub = threadIdx.x % TPC;
-    const uint32_t chunk = blockIdx.x * TK_CPW + ci;
-    if (chunk < s.nchunks) {
+    if (!s.rows[row].cand_mode) return;                   // uniform
+    const uint32_t lo = s.rows[row].bin_lo;
+    constexpr int TPC = 16, SIDE = TK_HTHREADS / TPC;
+    const int sub = threadIdx.x % TPC;
+    const uint32_t per_wg = (s.nchunks + TK_HWG - 1) / TK_HWG;
+    const uint32_t first = blockIdx.x * per_wg;
+    const uint32_t last = (first + per_wg < s.nchunks) ? first + per_wg : s.nchunks;
+    const uint32_t* cand_cnt = s.cand_cnt + (size_t)row * s.nchunks;
+    uint2* list = s.list + (size_t)row * TK_LIST_CAP;
+    uint32_t chunk = first + threadIdx.x / TPC;
+    uint32_t cnt = chunk < last ? cand_cnt[chunk] : 0u;
+    for (; chunk < last; chunk += SIDE) {                 // the 16 lanes of a chunk leave the loop together
+        const uint32_t cnt_next = (chunk + SIDE < last) ? cand_cnt[chunk + SIDE] : 0u;
         const size_t cidx = (size_t)row * s.nchunks + chunk;
-        if (s.cnt_eq[cidx] != 0) {
-            const uint32_t cnt = s.cand_cnt[cidx];
-            const uint32_t* slot = s.slot_val + cidx * TK_CAP;
-            uint32_t gt = 0, eq = 0;
-            for (uint32_t p = sub; p < cnt; p += TPC) {
-                const uint32_t key = slot[p] & 0x7FFFFFFFu;
-                gt += key > tau;
-                eq += key == tau;
+        const uint32_t* slot = s.slot_val + cidx * TK_CAP;
+        uint32_t gt = 0;
+        for (uint32_t p0 = sub; p0 < cnt; p0 += 8 * TPC) {
+            uint32_t key[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) key[u] = (p0 + u * TPC < cnt) ? (slot[p0 + u * TPC] & 0x7FFFFFFFu) : 0u;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t rel = key[u] - lo;          // wraps to a huge number below the bin
+                if (key[u] >= lo && rel >= FINE_SPAN) ++gt;
+                else if (rel < FINE_SPAN && p0 + u * TPC < cnt) {
+                    const uint32_t at = atomicAdd(&s.rows[row].list_count, 1u);
+                    if (at < TK_LIST_CAP) list[at] = make_uint2(key[u], chunk);
+                }
             }
-            if (gt) atomicAdd(&c_gt[ci], gt);
-            if (eq) atomicAdd(&c_eq[ci], eq);
         }
-    }
-    __syncthreads();
-    const uint32_t chunk0 = blockIdx.x * TK_CPW;
-    if (threadIdx.x < TK_CPW && chunk0 + threadIdx.x < s.nchunks) {
-        const size_t cidx = (size_t)row * s.nchunks + chunk0 + threadIdx.x;
-        if (s.cnt_eq[cidx] != 0) { s.cnt_gt[cidx] = c_gt[threadIdx.x]; s.cnt_eq[cidx] = c_eq[threadIdx.x]; }
+#pragma unroll
+        for (int o = 1; o < TPC; o <<= 1) gt += __shfl_xor(gt, o);
+        if (sub == 0) { s.cnt_gt[cidx] = gt; s.cnt_eq[cidx] = 0; }
+        cnt = cnt_next;
     }
 }
 
-// ---- per-row scan over chunks: tie quota and output offset of every chunk -----------------------
-__global__ void __launch_bounds__(TK_THREADS) topk_scan_chunks(Scratch s, unsigned long long* t_ptr) {
+// ---- where to collect candidates in the next step ------------------------------------------------
+// Near the threshold the number of keys above a level falls roughly exponentially with the level.  With
+// d = tau - tlo the distance that caught ratio * k candidates this step, d* = d ln(target) / ln(ratio) would
+// have caught target * k; the next level is (forecast of the next tau) - d*.  The forecast is made on |tau|
+// as a float (keys are only piecewise linear in the magnitude: the slope halves at every power of two): the
+// last movement repeated, or three quarters of it while the movement still changes by more than a quarter
+// from step to step (early in a run delta grows fast and then settles).  Without usable candidates (full
+// mode) a fixed distance of two million keys (a quarter of a binade) is taken.  Only speed depends on this
+// guess; a bad one sends the row through the exact full path.
+__device__ __forceinline__ uint32_t next_candidate_threshold(TopkRow& r, uint32_t tau, uint32_t k) {
+    const float d0 = 2.f * (float)(1u << SHIFT1);
+    float dist = d0;
+    if (r.cand_mode && r.cand_total > k && tau > r.tlo_used) {
+        const float ratio = (float)r.cand_total / (float)k;
+        dist = (float)(tau - r.tlo_used) * (logf(TK_TARGET) / logf(ratio));
+        dist = fminf(fmaxf(dist, 65536.f), 4.f * d0);
+    }
+    const float mag = __uint_as_float(tau);
+    float move = 0.f, next = mag;
+    if (r.tau_prev != 0xFFFFFFFFu) {
+        move = mag - __uint_as_float(r.tau_prev);
+        const bool steady = fabsf(move - r.drift_prev) <= 0.25f * fabsf(move);
+        next = mag + (steady ? move : 0.75f * move);
+        if (!(next > 0.f) || !(next < 3.0e38f)) next = mag;
+    }
+    r.drift_prev = move;
+    const float t = (float)__float_as_uint(next) - dist;
+    return t > 0.f ? (uint32_t)t : 0u;
+}
+
+// ---- per row: exact threshold (candidate mode), per-chunk counts, scan over chunks -----------------
+// Candidate mode: the listed keys of the threshold's bin (512 possible values) are counted in LDS, the
+// count from the top gives tau and the tie quota, and the chunks of the listed keys above / equal to tau
+// get their counts corrected.  Both modes: the scan over the row's chunks (tie quota and message offset of
+// every chunk), the guess for the next step, and the step counter.
+__global__ void __launch_bounds__(TK_RTHREADS) topk_finish(Scratch s, uint32_t k, unsigned long long* t_ptr) {
+    __shared__ uint32_t wave_sums[TK_RTHREADS / 64];
+    __shared__ uint32_t h[FINE_SPAN];
+    __shared__ uint32_t sel[2];
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(t_ptr, 1ull);   // one step taken
-    __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.x;
     const uint32_t nchunks = s.nchunks;
-    const uint32_t r_tie = s.rows[row].r_tie;
-    const uint32_t* gt = s.cnt_gt + (size_t)row * nchunks;
-    const uint32_t* eq = s.cnt_eq + (size_t)row * nchunks;
+    TopkRow& r = s.rows[row];
+    uint32_t* gtw = s.cnt_gt + (size_t)row * nchunks;
+    uint32_t* eqw = s.cnt_eq + (size_t)row * nchunks;
+    if (r.cand_mode) {                                              // uniform
+        const uint32_t lo = r.bin_lo, need = r.bin_need;
+        const uint32_t nlist = r.list_count < TK_LIST_CAP ? r.list_count : TK_LIST_CAP;
+        const uint2* list = s.list + (size_t)row * TK_LIST_CAP;
+        for (uint32_t b = threadIdx.x; b < FINE_SPAN; b += TK_RTHREADS) h[b] = 0;
+        if (threadIdx.x == 0) { sel[0] = lo; sel[1] = 0; }
+        __syncthreads();
+        for (uint32_t e = threadIdx.x; e < nlist; e += TK_RTHREADS) atomicAdd(&h[list[e].x - lo], 1u);
+        __syncthreads();
+        // one value per thread (the first 512 threads), largest first
+        const uint32_t b = (threadIdx.x < FINE_SPAN) ? FINE_SPAN - 1 - threadIdx.x : 0u;
+        const uint32_t mine = (threadIdx.x < FINE_SPAN) ? h[b] : 0u;
+        uint32_t total;
+        const uint32_t above = row_exclusive_scan(mine, wave_sums, &total);
+        if (threadIdx.x < FINE_SPAN && above < need && need <= above + mine) { sel[0] = lo + b; sel[1] = need - above; }
+        __syncthreads();
+        const uint32_t tau = sel[0];
+        for (uint32_t e = threadIdx.x; e < nlist; e += TK_RTHREADS) {
+            const uint2 en = list[e];
+            if (en.x > tau) atomicAdd(&gtw[en.y], 1u);
+            else if (en.x == tau) atomicAdd(&eqw[en.y], 1u);
+        }
+        if (threadIdx.x == 0) { r.tau = tau; r.r_tie = sel[1]; }
+        __threadfence();                                            // the corrected counts, before the scan reads them
+        __syncthreads();
+    } else {
+        // full mode: topk_fix_full left tau and the tie quota; the level-1 histogram of all keys must not meet the
+        // next first pass's candidates
+        for (int b = threadIdx.x; b < HIST_BINS; b += TK_RTHREADS) s.hist[(size_t)row * HIST_BINS + b] = 0;
+        if (threadIdx.x == 0) { sel[0] = r.tau; sel[1] = r.r_tie; }
+    }
+    __syncthreads();
+    const uint32_t tau_row = sel[0], r_tie = sel[1];
     uint32_t* eqb = s.eq_before + (size_t)row * nchunks;
     uint32_t* off = s.out_off + (size_t)row * (nchunks + 1);
-    // each thread owns a run of consecutive chunks, so that two workgroup scans serve the whole row
-    const uint32_t per = (nchunks + TK_THREADS - 1) / TK_THREADS;
-    const uint32_t lo = (threadIdx.x * per < nchunks) ? threadIdx.x * per : nchunks;
-    const uint32_t hi = (lo + per < nchunks) ? lo + per : nchunks;
+    // each thread owns a run of consecutive chunks, so that two workgroup scans serve the whole row; the counts
+    // are read past the vector cache (atomics above updated them in L2)
+    const uint32_t per = (nchunks + TK_RTHREADS - 1) / TK_RTHREADS;
+    const uint32_t lo_c = (threadIdx.x * per < nchunks) ? threadIdx.x * per : nchunks;
+    const uint32_t hi_c = (lo_c + per < nchunks) ? lo_c + per : nchunks;
+    auto load = [](const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    constexpr uint32_t REG = 8;                              // a thread's run fits in registers up to 8192 chunks a row
+    uint32_t e_r[REG], g_r[REG];
+#pragma unroll
+    for (uint32_t q = 0; q < REG; ++q) {
+        const bool in = per <= REG && lo_c + q < hi_c;
+        e_r[q] = in ? load(eqw + lo_c + q) : 0u;
+        g_r[q] = in ? load(gtw + lo_c + q) : 0u;
+    }
     uint32_t sum_e = 0;
-    for (uint32_t c = lo; c < hi; ++c) sum_e += eq[c];
+    if (per <= REG) {
+#pragma unroll
+        for (uint32_t q = 0; q < REG; ++q) sum_e += e_r[q];
+    } else {
+        for (uint32_t c = lo_c; c < hi_c; ++c) sum_e += load(eqw + c);
+    }
     uint32_t tot_e, tot_o;
-    const uint32_t before0 = block_exclusive_scan(sum_e, wave_sums, &tot_e);   // ties in earlier chunks of the row
+    const uint32_t before0 = row_exclusive_scan(sum_e, wave_sums, &tot_e);     // ties in earlier chunks of the row
     uint32_t before = before0, sum_take = 0;
-    for (uint32_t c = lo; c < hi; ++c) {
-        const uint32_t e = eq[c];
-        const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
-        sum_take += gt[c] + (e < quota ? e : quota);
-        before += e;
+    if (per <= REG) {
+#pragma unroll
+        for (uint32_t q = 0; q < REG; ++q) {
+            const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
+            sum_take += g_r[q] + (e_r[q] < quota ? e_r[q] : quota);
+            before += e_r[q];
+        }
+    } else {
+        for (uint32_t c = lo_c; c < hi_c; ++c) {
+            const uint32_t e = load(eqw + c);
+            const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
+            sum_take += load(gtw + c) + (e < quota ? e : quota);
+            before += e;
+        }
     }
-    uint32_t o = block_exclusive_scan(sum_take, wave_sums, &tot_o);
+    uint32_t o = row_exclusive_scan(sum_take, wave_sums, &tot_o);
     before = before0;
-    for (uint32_t c = lo; c < hi; ++c) {
-        const uint32_t e = eq[c];
-        const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
-        eqb[c] = before;
-        off[c] = o;
-        o += gt[c] + (e < quota ? e : quota);
-        before += e;
+    if (per <= REG) {
+#pragma unroll
+        for (uint32_t q = 0; q < REG; ++q) {
+            if (lo_c + q < hi_c) {
+                const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
+                eqb[lo_c + q] = before;
+                off[lo_c + q] = o;
+                o += g_r[q] + (e_r[q] < quota ? e_r[q] : quota);
+                before += e_r[q];
+            }
+        }
+    } else {
+        for (uint32_t c = lo_c; c < hi_c; ++c) {
+            const uint32_t e = load(eqw + c);
+            const uint32_t quota = (before < r_tie) ? (r_tie - before) : 0u;
+            eqb[c] = before;
+            off[c] = o;
+            o += load(gtw + c) + (e < quota ? e : quota);
+            before += e;
+        }
     }
-    if (threadIdx.x == 0) { off[nchunks] = tot_o; s.rows[row].total = tot_o; }
+    if (threadIdx.x == 0) {
+        off[nchunks] = tot_o;
+        r.total = tot_o;
+        r.tlo = next_candidate_threshold(r, tau_row, k);
+        r.tau_prev = tau_row;
+    }
 }
 
 // ---- ordered compaction: message pairs, delta <- 0 on the selected set (Algorithm 1, line 6) ----
@@ -582,16 +745,16 @@ __global__ void __launch_bounds__(TK_THREADS) topk_write_full(TopkArgs a, Scratc
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
     if (s.rows[row].cand_mode) return;
-    for (uint32_t chunk = blockIdx.x * TK_FPW; chunk < (blockIdx.x + 1) * TK_FPW && chunk < s.nchunks; ++chunk)
+    for (uint32_t chunk = blockIdx.x; chunk < s.nchunks; chunk += gridDim.x)
         write_full_chunk(a, s, row, chunk, wave_sums);
 }
 
-// Candidate mode, one wave per chunk.  A slot is unordered, so order comes from two bitmaps over the
-// chunk's columns (selected, tied): the place of a pair in the message is the number of selected
-// columns below it, and the ties that belong to the set are the `quota` lowest tied columns.
+// Candidate mode, one wave per workgroup, TK_WPW chunks per wave.  A slot is unordered, so order comes from
+// two bitmaps over the chunk's columns (selected, tied): the place of a pair in the message is the number of
+// selected columns below it, and the ties that belong to the set are the `quota` lowest tied columns.
 constexpr int TK_WORDS = TK_CHUNK / 32;                        // bitmap words per chunk
 __device__ __forceinline__ void bitmap_prefix(const uint32_t* bits, uint32_t* prefix, int lane) {
-    // prefix[w] = number of set bits in words [0, w); 4 consecutive words per lane
+    // prefix[w] = number of set bits in words [0, w); 2 consecutive words per lane
     uint32_t c[TK_WORDS / 64], sum = 0;
 #pragma unroll
     for (int q = 0; q < TK_WORDS / 64; ++q) { c[q] = __popc(bits[lane * (TK_WORDS / 64) + q]); sum += c[q]; }
@@ -610,79 +773,87 @@ __device__ __forceinline__ uint32_t bitmap_rank(const uint32_t* bits, const uint
 }
 
 __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
-    __shared__ uint32_t sel_bits[TK_WORDS], eq_bits[TK_WORDS], prefix[TK_WORDS];
+    __shared__ uint32_t sel_bits[TK_WORDS], eq_bits[TK_WORDS], prefix[TK_WORDS];      // of the chunk being written
     const int row = blockIdx.y;
+    if (!s.rows[row].cand_mode) return;                     // uniform
     const int lane = threadIdx.x;
-    const uint32_t nchunks = s.nchunks, chunk = blockIdx.x;
-    const size_t cidx = (size_t)row * nchunks + chunk;
-    const uint32_t* slot_val = s.slot_val + cidx * TK_CAP;
-    const uint16_t* slot_idx = s.slot_idx + cidx * TK_CAP;
-    // The slot goes into registers, 8 pairs per lane.  The first half is loaded before anything is known
-    // about the chunk (the slot's memory exists whatever its fill; what lies behind `cnt` is discarded
-    // below), so that these loads do not queue behind the chunk's counters.
-    constexpr int EPL = TK_CAP / 64, SPEC = EPL / 2;
-    uint2 ent[EPL];
-#pragma unroll
-    for (int u = 0; u < SPEC; ++u) {
-        const uint32_t p = (uint32_t)u * 64 + lane;
-        ent[u] = make_uint2(slot_idx[p], slot_val[p]);     // .x: column in the chunk
-    }
-    const uint32_t cand_mode = s.rows[row].cand_mode;
+    const uint32_t nchunks = s.nchunks, chunk0 = blockIdx.x * TK_WPW;
     const uint32_t tau = s.rows[row].tau, r_tie = s.rows[row].r_tie;
-    const uint32_t off0 = s.out_off[(size_t)row * (nchunks + 1) + chunk];
-    const uint32_t off1 = s.out_off[(size_t)row * (nchunks + 1) + chunk + 1];
-    const uint32_t cnt = s.cand_cnt[cidx];
-    const uint32_t eqb = s.eq_before[cidx];
-    const uint32_t cnt_eq = s.cnt_eq[cidx];
-    if (!cand_mode || off0 == off1) return;                 // uniform
-    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
-    const uint32_t quota = (eqb < r_tie) ? (r_tie - eqb) : 0u;   // ties of this chunk that belong to the set
-    const bool ties = cnt_eq != 0 && quota != 0;
+    // The slots go into registers.  The first two pairs per lane of every chunk (what a slot normally holds) are
+    // loaded before anything is known about the chunk (the slot's memory exists whatever its fill; what lies
+    // behind `cnt` is discarded below), together with the chunks' counters: one round trip to memory for the
+    // wave's TK_WPW chunks.
+    constexpr int SPEC = 2;
+    uint2 ent[TK_WPW][SPEC];
+    uint32_t cnt[TK_WPW], off0[TK_WPW], off1[TK_WPW], eqb[TK_WPW], ceq[TK_WPW];
 #pragma unroll
-    for (int u = 0; u < EPL; ++u) {
-        const uint32_t p = (uint32_t)u * 64 + lane;
-        if (u < SPEC) { if (p >= cnt) ent[u] = make_uint2(0xFFFFFFFFu, 0u); }
-        else ent[u] = (p < cnt) ? make_uint2(slot_idx[p], slot_val[p]) : make_uint2(0xFFFFFFFFu, 0u);
-    }
-    for (int w = lane; w < TK_WORDS; w += 64) { sel_bits[w] = 0; eq_bits[w] = 0; }
-    __syncthreads();
+    for (int c = 0; c < TK_WPW; ++c) {
+        const uint32_t chunk = (chunk0 + c < nchunks) ? chunk0 + c : nchunks - 1;     // a clamped chunk is skipped below
+        const size_t cidx = (size_t)row * nchunks + chunk;
 #pragma unroll
-    for (int u = 0; u < EPL; ++u) {
-        const uint32_t key = ent[u].y & 0x7FFFFFFFu;
-        const uint32_t q = ent[u].x;
-        if (q >= (uint32_t)TK_CHUNK) continue;              // the padding pairs
-        if (key > tau) atomicOr(&sel_bits[q >> 5], 1u << (q & 31));
-        else if (key == tau && ties) atomicOr(&eq_bits[q >> 5], 1u << (q & 31));
-    }
-    __syncthreads();
-    if (ties) {                                             // uniform
-        bitmap_prefix(eq_bits, prefix, lane);
-        __syncthreads();
-        for (int w = lane; w < TK_WORDS; w += 64) {
-            // keep the tied columns whose rank among the ties is below the quota
-            uint32_t word = eq_bits[w], keep = 0;
-            uint32_t rank = prefix[w];
-            while (word) {
-                const uint32_t bit = word & (0u - word);
-                if (rank < quota) keep |= bit;
-                ++rank;
-                word ^= bit;
-            }
-            sel_bits[w] |= keep;
+        for (int u = 0; u < SPEC; ++u) {
+            const uint32_t p = (uint32_t)u * 64 + lane;
+            ent[c][u] = make_uint2(s.slot_idx[cidx * TK_CAP + p], s.slot_val[cidx * TK_CAP + p]);   // .x: column in the chunk
         }
-        __syncthreads();
+        cnt[c] = s.cand_cnt[cidx];
+        off0[c] = s.out_off[(size_t)row * (nchunks + 1) + chunk];
+        off1[c] = s.out_off[(size_t)row * (nchunks + 1) + chunk + 1];
+        eqb[c] = s.eq_before[cidx];
+        ceq[c] = s.cnt_eq[cidx];
     }
-    bitmap_prefix(sel_bits, prefix, lane);
-    __syncthreads();
     uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
 #pragma unroll
-    for (int u = 0; u < EPL; ++u) {
-        const uint32_t q = ent[u].x;
-        if (q >= (uint32_t)TK_CHUNK) continue;
-        if (sel_bits[q >> 5] & (1u << (q & 31))) {
-            const uint32_t pos = off0 + bitmap_rank(sel_bits, prefix, q);
-            if (pos < a.k && pos < off1) out[pos] = make_uint2((uint32_t)(c0 + q), ent[u].y);
+    for (int c = 0; c < TK_WPW; ++c) {
+        const uint32_t chunk = chunk0 + c;
+        if (chunk >= nchunks || off0[c] == off1[c]) continue;                         // uniform
+        const size_t cidx = (size_t)row * nchunks + chunk;
+        const uint32_t* slot_val = s.slot_val + cidx * TK_CAP;
+        const uint16_t* slot_idx = s.slot_idx + cidx * TK_CAP;
+        const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+        const uint32_t quota = (eqb[c] < r_tie) ? (r_tie - eqb[c]) : 0u;          // ties of this chunk that belong to the set
+        const bool ties = ceq[c] != 0 && quota != 0;
+        for (int w = lane; w < TK_WORDS; w += 64) { sel_bits[w] = 0; eq_bits[w] = 0; }
+        __syncthreads();                                    // (one wave: orders its LDS accesses)
+        auto mark = [&](uint32_t q, uint32_t bits) {
+            const uint32_t key = bits & 0x7FFFFFFFu;
+            if (key > tau) atomicOr(&sel_bits[q >> 5], 1u << (q & 31));
+            else if (key == tau && ties) atomicOr(&eq_bits[q >> 5], 1u << (q & 31));
+        };
+#pragma unroll
+        for (int u = 0; u < SPEC; ++u)
+            if ((uint32_t)u * 64 + lane < cnt[c]) mark(ent[c][u].x, ent[c][u].y);
+        for (uint32_t p = SPEC * 64 + lane; p < cnt[c]; p += 64) mark(slot_idx[p], slot_val[p]);   // a fuller slot than usual
+        __syncthreads();
+        if (ties) {                                         // uniform
+            bitmap_prefix(eq_bits, prefix, lane);
+            __syncthreads();
+            for (int w = lane; w < TK_WORDS; w += 64) {
+                // keep the tied columns whose rank among the ties is below the quota
+                uint32_t word = eq_bits[w], keep = 0;
+                uint32_t rank = prefix[w];
+                while (word) {
+                    const uint32_t bit = word & (0u - word);
+                    if (rank < quota) keep |= bit;
+                    ++rank;
+                    word ^= bit;
+                }
+                sel_bits[w] |= keep;
+            }
+            __syncthreads();
         }
+        bitmap_prefix(sel_bits, prefix, lane);
+        __syncthreads();
+        auto emit = [&](uint32_t q, uint32_t bits) {
+            if (sel_bits[q >> 5] & (1u << (q & 31))) {
+                const uint32_t pos = off0[c] + bitmap_rank(sel_bits, prefix, q);
+                if (pos < a.k && pos < off1[c]) out[pos] = make_uint2((uint32_t)(c0 + q), bits);
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < SPEC; ++u)
+            if ((uint32_t)u * 64 + lane < cnt[c]) emit(ent[c][u].x, ent[c][u].y);
+        for (uint32_t p = SPEC * 64 + lane; p < cnt[c]; p += 64) emit(slot_idx[p], slot_val[p]);
+        __syncthreads();                                    // the bitmaps are reused by the next chunk
     }
 }
 
@@ -764,19 +935,24 @@ struct TopkState {
 
 void topk_destroy(TopkState* st) {
     if (!st) return;
-    void* ptrs[] = {st->s.hist, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slot_val, st->s.slot_idx};
+    void* ptrs[] = {st->s.hist, st->s.hist2, st->s.hist3, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slot_val, st->s.slot_idx,
+                    st->s.list};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     delete st;
 }
 
-ds_status topk_create(const ds_config& cfg, uint64_t /*ld*/, TopkState** out, std::string& err) {
+ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::string& err) {
     TopkState* st = new TopkState();
     st->n = cfg.n;
     Scratch& s = st->s;
     s.nchunks = (uint32_t)((cfg.N + TK_CHUNK - 1) / TK_CHUNK);
+    // the first pass reads and writes whole chunks of x and delta
+    if ((uint64_t)s.nchunks * TK_CHUNK > ld) { err = "internal: row pitch smaller than the chunked row"; delete st; return DS_EINVAL; }
     const size_t n = (size_t)cfg.n, nc = s.nchunks;
     bool ok = hipMalloc(&s.hist, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.hist2, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.hist3, n * BINS3 * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.rows, n * sizeof(TopkRow)) == hipSuccess &&
               hipMalloc(&s.cnt_gt, n * nc * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.cnt_eq, n * nc * sizeof(uint32_t)) == hipSuccess &&
@@ -784,8 +960,11 @@ ds_status topk_create(const ds_config& cfg, uint64_t /*ld*/, TopkState** out, st
               hipMalloc(&s.out_off, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.cand_cnt, n * nc * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.slot_val, n * nc * TK_CAP * sizeof(uint32_t)) == hipSuccess &&
-              hipMalloc(&s.slot_idx, n * nc * TK_CAP * sizeof(uint16_t)) == hipSuccess;
+              hipMalloc(&s.slot_idx, n * nc * TK_CAP * sizeof(uint16_t)) == hipSuccess &&
+              hipMalloc(&s.list, n * TK_LIST_CAP * sizeof(uint2)) == hipSuccess;
     ok = ok && hipMemset(s.hist, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+         hipMemset(s.hist2, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+         hipMemset(s.hist3, 0, n * BINS3 * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.out_off, 0, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.cand_cnt, 0, n * nc * sizeof(uint32_t)) == hipSuccess;
     if (ok) {
@@ -826,27 +1005,26 @@ ds_status topk_flush(TopkState* st, const TopkArgs& a, hipStream_t stream) {
 
 ds_status topk_step(TopkState* st, const TopkArgs& a, hipStream_t stream) {
     const Scratch& s = st->s;
-    const dim3 grid(s.nchunks, a.n), block(TK_THREADS);
-    const dim3 cgrid((s.nchunks + TK_CPW - 1) / TK_CPW, a.n);
-    const dim3 fgrid((s.nchunks + TK_FPW - 1) / TK_FPW, a.n);
+    const dim3 grid(s.nchunks, a.n), block(TK_THREADS), rblock(TK_RTHREADS);
+    const dim3 wgrid((s.nchunks + TK_WPW - 1) / TK_WPW, a.n);
+    // full mode walks a row's chunks with a fixed number of workgroups, so that a step in which no row needs it
+    // pays little for the launches
+    const dim3 fgrid(s.nchunks < (uint32_t)TK_FWG ? s.nchunks : (uint32_t)TK_FWG, a.n);
     const dim3 hgrid(TK_HWG, a.n), hblock(TK_HTHREADS);
     const dim3 rows(a.n);
     const uint32_t k = (uint32_t)a.k;
     // after a flush (and at the start) all message offsets are zero, so the first pass finds no tail to apply
     hipLaunchKernelGGL(topk_form_collect, grid, block, 0, stream, a, s);
-    hipLaunchKernelGGL(topk_decide, rows, block, 0, stream, s, k);
-    hipLaunchKernelGGL(topk_hist_full<1>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
-    hipLaunchKernelGGL(topk_select<1>, rows, block, 0, stream, s, k);
-    hipLaunchKernelGGL(topk_hist_cand<2>, hgrid, hblock, 0, stream, s);
-    hipLaunchKernelGGL(topk_hist_full<2>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
-    hipLaunchKernelGGL(topk_select<2>, rows, block, 0, stream, s, k);
-    hipLaunchKernelGGL(topk_hist_cand<3>, hgrid, hblock, 0, stream, s);
-    hipLaunchKernelGGL(topk_hist_full<3>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
-    hipLaunchKernelGGL(topk_select<3>, rows, block, 0, stream, s, k);
-    hipLaunchKernelGGL(topk_fix_cand, cgrid, block, 0, stream, s);
+    hipLaunchKernelGGL(topk_decide_select, rows, block, 0, stream, s, k);
+    hipLaunchKernelGGL(topk_hist_cand2, hgrid, hblock, 0, stream, s);
+    hipLaunchKernelGGL(topk_select2_cand, rows, block, 0, stream, s);
+    hipLaunchKernelGGL(topk_bin_collect, hgrid, hblock, 0, stream, s);
+    hipLaunchKernelGGL(topk_hist_full<1>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s, k);
+    hipLaunchKernelGGL(topk_hist_full<2>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s, k);
+    hipLaunchKernelGGL(topk_hist_full<3>, fgrid, block, 0, stream, a.delta, a.ld, a.N, s, k);
     hipLaunchKernelGGL(topk_fix_full, fgrid, block, 0, stream, a.delta, a.ld, a.N, s);
-    hipLaunchKernelGGL(topk_scan_chunks, rows, block, 0, stream, s, a.t_ptr);
-    hipLaunchKernelGGL(topk_write_cand, grid, dim3(64), 0, stream, a, s);
+    hipLaunchKernelGGL(topk_finish, rows, rblock, 0, stream, s, k, a.t_ptr);
+    hipLaunchKernelGGL(topk_write_cand, wgrid, dim3(64), 0, stream, a, s);
     hipLaunchKernelGGL(topk_write_full, fgrid, block, 0, stream, a, s);
     st->pending = true;
     return DS_OK;
