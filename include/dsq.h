@@ -73,7 +73,8 @@ typedef enum {
 typedef struct {
     int32_t  kind;    /* ds_comp_kind */
     int32_t  bits;    /* QUANT_MAXABS, QUANT_L2NORM: 2, 4 or 8; otherwise ignored               */
-    int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 64 <= block <= 2048           */
+    int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 64 <= block <= 2048 (the fused  */
+                      /* kernel holds a whole block in one wave's registers)                    */
     int32_t  reserved;
     uint64_t k;       /* TOPK: 1 <= k <= N; RAND_SPARSE: expected kept elements per worker,     */
                       /* 1 <= k <= N; otherwise ignored                                         */
@@ -136,13 +137,28 @@ const char* ds_build_id(void);
 
 /* Creates the state on the current HIP device: x = 0, delta = 0, t = 0 (Algorithm 1, line 1;
  * Assumption 1.4).  Allocates x, delta (n rows with an internal pitch), the message buffer and
- * scratch with hipMalloc.  *out is NULL on failure.
+ * scratch with hipMalloc.  *out is NULL on failure; ds_init_ex also says why.
  * For large problems (n*N >= 32 Mi) of the block compressors the call times the candidate launch
  * shapes and row pitches of the fused kernel on the (still zero) state and keeps the fastest; the
- * choice is reported by ds_plan_name.  Environment, read here: DSQ_TILE_PLAN=<i> pins the i-th
- * candidate shape, DSQ_PITCH_SKEW=<floats> the pitch, DSQ_STREAM=1 selects the row-streaming variant
- * of the block compressors (it is also what serves more workers than the fused kernel's LDS holds). */
+ * choice is reported by ds_plan_name and can be pinned through ds_init_ex. */
 ds_status ds_init(const ds_config* cfg, ds_handle** out);
+
+/* ds_init with a say in the kernel plan and with the reason of a failure.  `plan` may be NULL (everything
+ * automatic, what ds_init does).  errbuf (may be NULL) receives the reason of a failure, or the note ds_init
+ * leaves in ds_last_error (eta > 1/2). */
+typedef struct {
+    int32_t variant;      /* 0: automatic; 1: the row-streaming variant of the block compressors (every wave   */
+                          /*    takes one row of a tile, no LDS exchange; what serves more workers than the     */
+                          /*    fused kernel's LDS holds is chosen automatically anyway)                        */
+    int32_t tile_plan;    /* -1: automatic; i >= 0 pins the i-th candidate launch shape of the fused kernel      */
+                          /*    (an index past the last candidate leaves the choice automatic)                   */
+    int64_t pitch_skew;   /* -1: automatic; else floats added to the padded row length of x and delta:          */
+                          /*    a multiple of 4, at most 12288                                                   */
+    int32_t autotune;     /* 1: time the candidates at init (large problems only); 0: first candidate, default   */
+                          /*    pitch (reproducible launches, a few per cent slower)                             */
+    int32_t reserved;
+} ds_plan_request;
+ds_status ds_init_ex(const ds_config* cfg, const ds_plan_request* plan, char* errbuf, uint64_t errbuf_len, ds_handle** out);
 
 /* One iteration of Algorithm 1 (lines 5-9) for all n workers with the gradients g_dev.
  * g_dev: caller-owned DEVICE pointer, n rows of fp32, row pitch g_ld >= N elements, g_ld a multiple
@@ -195,21 +211,25 @@ ds_status ds_set_mixing(ds_handle* h, const int32_t* W_rowptr, const int32_t* W_
  * graph captured from ds_step keeps the values it was captured with.  Synchronises nothing. */
 ds_status ds_set_rates(ds_handle* h, float gamma, float eta);
 
-/* Copies the state to dense host arrays of n*N fp32 each (delta_host may be NULL).  Synchronises
- * with the stream of the last ds_step. */
+/* Copies the state -- the workers' models x_i and carried compression errors delta_i of Algorithm 1 (rows of
+ * X and Delta in the paper's matrix notation, section "Mathematical formulation") -- to dense host arrays of
+ * n*N fp32 each (delta_host may be NULL).  Synchronises with the stream of the last ds_step. */
 ds_status ds_read_state(ds_handle* h, float* x_host, float* delta_host);
 
-/* Overwrites the state from dense host arrays (n*N fp32 each; NULL leaves that array unchanged)
- * and sets the step counter.  With the counter-based random stream this makes a run restartable:
- * read_state at step t, write_state into a fresh handle, and the continuation is bit-identical. */
+/* Overwrites x and delta (Algorithm 1's per-worker state; line 1 starts them at zero) from dense host
+ * arrays (n*N fp32 each; NULL leaves that array unchanged) and sets the step counter.  With the
+ * counter-based random stream this makes a run restartable: read_state at step t, write_state into a
+ * fresh handle, and the continuation is bit-identical. */
 ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_host, uint64_t t);
 
-/* Copies the packed messages of the last ds_step (layout: ds_message_bytes) into host_buf of
+/* Copies the packed messages of the last ds_step -- what Algorithm 1's lines 7-8 send and receive,
+ * C_omega[v_i] of every worker in its wire format (layout: ds_message_bytes) -- into host_buf of
  * capacity cap; *bytes receives the size.  DS_ESTATE before the first step, DS_EINVAL if cap is
  * too small.  Synchronises like ds_read_state. */
 ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t* bytes);
 
-/* Borrows the device arrays: row i of x starts at x_dev + i*ld.  Ownership stays with the
+/* Borrows the device arrays of x and delta (Algorithm 1's state, as for ds_read_state): row i of x starts
+ * at x_dev + i*ld.  Ownership stays with the
  * handle; columns >= N of each row are padding the caller must leave zero.  The contents are
  * complete once the work enqueued so far on the stream of the last ds_step has finished (top-k,
  * the norm-rescaled codes and the row-streaming plans leave the last part of a step's update of x

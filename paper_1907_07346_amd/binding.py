@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdsq.so")
 EXPORTS = ["ds_validate_config", "ds_build_topology", "ds_message_bytes", "ds_init", "ds_step",
            "ds_read_state", "ds_write_state", "ds_read_messages", "ds_state_ptrs", "ds_message_ptr",
            "ds_step_count", "ds_plan_name", "ds_last_error", "ds_destroy", "ds_bench_copy",
-           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient", "ds_bench_stream", "ds_build_id", "ds_step_static"]
+           "ds_topk_candidate_rows", "ds_set_mixing", "ds_diagnostics", "ds_set_rates", "ds_workload_gradient", "ds_bench_stream", "ds_build_id", "ds_step_static", "ds_init_ex"]
 
 
 class ds_comp(ctypes.Structure):
@@ -36,6 +36,11 @@ class ds_comp(ctypes.Structure):
 class ds_workload(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int32), ("kind", ctypes.c_int32), ("N", ctypes.c_uint64), ("scale", ctypes.c_float),
                 ("reserved", ctypes.c_float), ("seed", ctypes.c_uint64)]
+
+
+class ds_plan_request(ctypes.Structure):
+    _fields_ = [("variant", ctypes.c_int32), ("tile_plan", ctypes.c_int32), ("pitch_skew", ctypes.c_int64),
+                ("autotune", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class ds_config(ctypes.Structure):
@@ -72,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.ds_step_static.argtypes = [cfgp, vp, vp, u64, vp, u64, vp, u64, vp, ctypes.c_char_p, u64]
         L.ds_step_static.restype = i32
         L.ds_init.argtypes, L.ds_init.restype = [cfgp, ctypes.POINTER(vp)], i32
+        L.ds_init_ex.argtypes = [cfgp, ctypes.POINTER(ds_plan_request), ctypes.c_char_p, u64, ctypes.POINTER(vp)]
+        L.ds_init_ex.restype = i32
         L.ds_step.argtypes, L.ds_step.restype = [vp, vp, u64, vp], i32
         L.ds_read_state.argtypes, L.ds_read_state.restype = [vp, vp, vp], i32
         L.ds_set_mixing.argtypes, L.ds_set_mixing.restype = [vp, vp, vp, vp], i32
@@ -195,19 +202,26 @@ def ds_step_static(cfg: ds_config, x: "torch.Tensor", delta: "torch.Tensor", g: 
 class DeepSqueeze:
     """Owner of one ds_handle. Methods are the C calls with the same names."""
 
-    def __init__(self, cfg: ds_config, keepalive=None):
+    def __init__(self, cfg: ds_config, keepalive=None, plan: Optional[dict] = None):
+        """plan: None (ds_init) or a dict with any of variant, tile_plan, pitch_skew, autotune (ds_init_ex)."""
         self._h = ctypes.c_void_p()
         self.cfg = cfg
         self._keep = keepalive
-        st = lib().ds_init(ctypes.byref(cfg), ctypes.byref(self._h))
+        buf = ctypes.create_string_buffer(256)
+        if plan is None:
+            st = lib().ds_init_ex(ctypes.byref(cfg), None, buf, 256, ctypes.byref(self._h))
+        else:
+            req = ds_plan_request(plan.get("variant", 0), plan.get("tile_plan", -1), plan.get("pitch_skew", -1),
+                                  plan.get("autotune", 1), 0)
+            st = lib().ds_init_ex(ctypes.byref(cfg), ctypes.byref(req), buf, 256, ctypes.byref(self._h))
         if st != DS_OK:
-            raise DsqError(st, "ds_init", ds_validate_config(cfg)[1])
+            raise DsqError(st, "ds_init", buf.value.decode())
         self.n, self.N = int(cfg.n), int(cfg.N)
 
     @classmethod
-    def from_workload(cls, w: Config) -> "DeepSqueeze":
+    def from_workload(cls, w: Config, plan: Optional[dict] = None) -> "DeepSqueeze":
         cfg, keep = config_from_workload(w)
-        return cls(cfg, keep)
+        return cls(cfg, keep, plan)
 
     def _check(self, st: int, where: str):
         if st != DS_OK:

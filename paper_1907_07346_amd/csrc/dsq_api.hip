@@ -400,17 +400,32 @@ ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void
     return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
 }
 
-ds_status ds_init(const ds_config* cfg, ds_handle** out) {
+ds_status ds_init(const ds_config* cfg, ds_handle** out) { return ds_init_ex(cfg, nullptr, nullptr, 0, out); }
+
+ds_status ds_init_ex(const ds_config* cfg, const ds_plan_request* plan, char* errbuf, uint64_t errbuf_len, ds_handle** out) {
+    if (errbuf && errbuf_len) errbuf[0] = 0;
     if (!out) return DS_EINVAL;
     *out = nullptr;
     ds_handle* h = new (std::nothrow) ds_handle();
     if (!h) return DS_ENOMEM;
-    auto bail = [&](ds_status st) { release(h); return st; };
+    auto bail = [&](ds_status st, const std::string& why) {
+        if (errbuf && errbuf_len) std::snprintf(errbuf, (size_t)errbuf_len, "%s", why.c_str());
+        release(h);
+        return st;
+    };
+    ds_plan_request want{};                                 // all automatic
+    want.tile_plan = -1; want.pitch_skew = -1; want.autotune = 1;
+    if (plan) {
+        want = *plan;
+        if (want.variant < 0 || want.variant > 1) return bail(DS_EINVAL, "plan: variant must be 0 (automatic) or 1 (row-streaming)");
+        if (want.pitch_skew < -1 || want.pitch_skew > (int64_t)kMaxPitchSkew || (want.pitch_skew > 0 && (want.pitch_skew & 3)))
+            return bail(DS_EINVAL, "plan: pitch_skew must be -1 (automatic) or a multiple of 4 up to 12288");
+    }
 
     std::string err, warn;
-    if (dsq::validate_config(cfg, err, &warn) != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(DS_EINVAL); }
+    if (dsq::validate_config(cfg, err, &warn) != DS_OK) return bail(DS_EINVAL, err);
     h->cfg = *cfg;
-    if (dsq::build_graph(cfg, h->graph, err) != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(DS_EINVAL); }
+    if (dsq::build_graph(cfg, h->graph, err) != DS_OK) return bail(DS_EINVAL, err);
     h->cfg.W_rowptr = nullptr; h->cfg.W_col = nullptr; h->cfg.W_val = nullptr;   // the copy lives in graph
     const uint64_t base_ld = (cfg->N + dsq::kPitchAlign - 1) / dsq::kPitchAlign * dsq::kPitchAlign;
     h->ld = base_ld + kMaxPitchSkew;                       // allocation pitch; the working pitch is fixed below
@@ -422,33 +437,27 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
     } else if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {
         h->plan_name = "l2norm/two-pass";
     } else {
-        // DSQ_STREAM=1 asks for the row-streaming variant of the block compressors; it is also what serves a
-        // number of workers whose codes do not fit in LDS
-        const char* want_stream = std::getenv("DSQ_STREAM");
+        // the row-streaming variant of the block compressors on request; it is also what serves a number of
+        // workers whose codes do not fit in LDS
         dsq::TilePlan sp;
         const bool can_stream = dsq::stream_plan(h->cfg, sp);
         const bool fits = dsq::choose_tile_plans(h->cfg, (int)h->graph.col.size(), h->tile_candidates, err);
-        if (can_stream && (!fits || (want_stream && *want_stream == '1'))) {
+        if (can_stream && (!fits || want.variant == 1)) {
             h->tile_candidates.assign(1, sp);
             h->msg_half = (uint64_t)cfg->n * h->msg_row_bytes;
         } else if (!fits) {
-            std::fprintf(stderr, "ds_init: %s\n", err.c_str());
-            return bail(DS_EINVAL);
+            return bail(DS_EINVAL, err);
         }
         h->tile = h->tile_candidates.front();
-        // DSQ_TILE_PLAN=<i> pins the i-th candidate launch shape (tests walk through all of them)
-        const char* pinned = std::getenv("DSQ_TILE_PLAN");
-        if (pinned && *pinned) {
-            const size_t i = (size_t)std::strtoull(pinned, nullptr, 10);
-            if (i < h->tile_candidates.size()) {
-                h->tile = h->tile_candidates[i];
-                h->tile_candidates.assign(1, h->tile);
-            }
+        // a pinned candidate launch shape (tests walk through all of them; an index past the end leaves the choice automatic)
+        if (want.tile_plan >= 0 && (size_t)want.tile_plan < h->tile_candidates.size()) {
+            h->tile = h->tile_candidates[(size_t)want.tile_plan];
+            h->tile_candidates.assign(1, h->tile);
         }
     }
 
     hipError_t e = hipGetDevice(&h->device);
-    if (e != hipSuccess) { std::fprintf(stderr, "ds_init: no HIP device: %s\n", hipGetErrorString(e)); return bail(DS_EHIP); }
+    if (e != hipSuccess) return bail(DS_EHIP, std::string("no HIP device: ") + hipGetErrorString(e));
     const size_t state_bytes = (size_t)cfg->n * h->ld * sizeof(float);
     const size_t nnz = h->graph.col.size();
     const size_t msg_bytes = (size_t)cfg->n * h->msg_row_bytes * (h->msg_half ? 2 : 1);
@@ -457,7 +466,7 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
         hipMalloc(&h->x, state_bytes), hipMalloc(&h->delta, state_bytes), hipMalloc(&h->msg, msg_bytes ? msg_bytes : 4),
         hipMalloc(&h->d_rowptr, (cfg->n + 1 + 2 * nnz) * sizeof(int32_t)), hipMalloc(&h->d_t, dsq::kStepCells * sizeof(unsigned long long))};
     for (hipError_t ee : errs)
-        if (ee != hipSuccess) { std::fprintf(stderr, "ds_init: hipMalloc: %s\n", hipGetErrorString(ee)); return bail(ee == hipErrorOutOfMemory ? DS_ENOMEM : DS_EHIP); }
+        if (ee != hipSuccess) { (void)hipGetLastError(); return bail(ee == hipErrorOutOfMemory ? DS_ENOMEM : DS_EHIP, std::string("hipMalloc: ") + hipGetErrorString(ee)); }
     h->d_col = h->d_rowptr + cfg->n + 1;
     h->d_coef = reinterpret_cast<float*>(h->d_col + nnz);
     bool ok = hipMemset(h->x, 0, state_bytes) == hipSuccess && hipMemset(h->delta, 0, state_bytes) == hipSuccess &&
@@ -468,26 +477,23 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
               hipMemcpy(h->d_col, h->graph.col.data(), nnz * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipMemcpy(h->d_coef, h->graph.coef.data(), nnz * sizeof(float), hipMemcpyHostToDevice) == hipSuccess &&
               hipDeviceSynchronize() == hipSuccess;
-    if (!ok) { std::fprintf(stderr, "ds_init: device initialisation failed\n"); return bail(DS_EHIP); }
+    if (!ok) return bail(DS_EHIP, "device initialisation failed");
     if (cfg->comp.kind == DS_COMP_RAND_SPARSE) {
         h->nsweeps = (cfg->N + dsq::kSweep - 1) / dsq::kSweep;
         h->ngroups = (h->nsweeps + 15) / 16;
         const size_t words = (size_t)cfg->n * (3 * h->nsweeps + h->ngroups) + (size_t)cfg->n + 1;
         if (hipMalloc(&h->d_keep, words * sizeof(uint32_t)) != hipSuccess || hipMemset(h->d_keep, 0, words * sizeof(uint32_t)) != hipSuccess ||
             hipDeviceSynchronize() != hipSuccess) {
-            std::fprintf(stderr, "ds_init: allocating the random sparsifier's offsets failed\n");
-            return bail(DS_ENOMEM);
+            return bail(DS_ENOMEM, "allocating the random sparsifier's offsets failed");
         }
     }
 
-    // working row pitch: DSQ_PITCH_SKEW=<floats, multiple of 4, <= 12288> pins it; otherwise large tile-kernel
-    // problems are timed per candidate, everything else takes the default
+    // working row pitch: pinned by the caller, or timed per candidate for large tile-kernel problems; everything
+    // else takes the default
     uint64_t skew = dsq::kPitchSkew;
-    const char* pin = std::getenv("DSQ_PITCH_SKEW");
-    if (pin && *pin) {
-        const unsigned long long v = std::strtoull(pin, nullptr, 10);
-        if (v <= kMaxPitchSkew && (v & 3) == 0) skew = v;
-    } else if (tiled && !h->tile.streaming && (uint64_t)cfg->n * cfg->N >= (32ull << 20)) {
+    if (want.pitch_skew >= 0) {
+        skew = (uint64_t)want.pitch_skew;
+    } else if (want.autotune && tiled && !h->tile.streaming && (uint64_t)cfg->n * cfg->N >= (32ull << 20)) {
         skew = autotune(h, base_ld, state_bytes, msg_bytes);
     }
     h->ld = base_ld + skew;
@@ -497,13 +503,14 @@ ds_status ds_init(const ds_config* cfg, ds_handle** out) {
 
     if (cfg->comp.kind == DS_COMP_TOPK) {
         const ds_status st = dsq::topk_create(h->cfg, h->ld, &h->topk, err);
-        if (st != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(st); }
+        if (st != DS_OK) return bail(st, err);
     }
     if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {
         const ds_status st = dsq::l2q_create(h->cfg, h->ld, &h->l2q, err);
-        if (st != DS_OK) { std::fprintf(stderr, "ds_init: %s\n", err.c_str()); return bail(st); }
+        if (st != DS_OK) return bail(st, err);
     }
     h->err = warn;
+    if (errbuf && errbuf_len) std::snprintf(errbuf, (size_t)errbuf_len, "%s", warn.c_str());
     *out = h;
     return DS_OK;
 }
@@ -627,14 +634,14 @@ ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_h
     return DS_OK;
 }
 
-// Row-streaming variant: step t writes message buffer t & 1, so the last step's messages are in half (t - 1) & 1
-// of the counter the device holds now (the caller has synchronised).
+// Row-streaming variant: step t writes message buffer t & 1 and leaves that number in cell 4 of the step cells
+// (the counter itself may have been set from outside since).  The caller has synchronised.
 static ds_status last_message_buffer(ds_handle* h, uint8_t** out) {
     *out = h->msg;
     if (!h->msg_half) return DS_OK;
-    unsigned long long t64 = 0;
-    DSQ_HIP(h, hipMemcpy(&t64, h->d_t, sizeof(t64), hipMemcpyDeviceToHost));
-    if ((t64 & 1ull) == 0) *out = h->msg + h->msg_half;      // t - 1 is odd
+    unsigned long long half = 0;
+    DSQ_HIP(h, hipMemcpy(&half, h->d_t + 4, sizeof(half), hipMemcpyDeviceToHost));
+    if (half & 1ull) *out = h->msg + h->msg_half;
     return DS_OK;
 }
 

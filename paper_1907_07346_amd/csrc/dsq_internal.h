@@ -62,8 +62,10 @@ struct TileArgs {
                                        // the kernel and advanced by its last workgroup to finish, so that a captured
                                        // HIP graph of ds_step keeps moving along the random stream on replay.
                                        // [1]: finished first-level cells; [2]: random sparsifier: the step whose keep
-                                       // counts are in keep_raw (~0 if none); [32 (1+c)], c < 64: finished workgroups
-                                       // with blockIdx % 64 == c.  All but [0] and [2] are zero between launches.
+                                       // counts are in keep_raw (~0 if none); [3]: row-streaming variant: a gossip sum is
+                                       // pending; [4]: row-streaming variant: the message buffer (0 / 1) the last step
+                                       // wrote; [32 (1+c)], c < 64: finished workgroups with blockIdx % 64 == c.
+                                       // Cells [1] and [32 (1+c)] are zero between launches.
 };
 
 // A compiled variant of the fused tile kernel, chosen once at init.

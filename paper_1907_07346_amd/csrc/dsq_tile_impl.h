@@ -812,8 +812,13 @@ __device__ __forceinline__ void step_counter_bump(const TileArgs& a, unsigned lo
             unsigned long long* done = a.t_ptr + 1;
             if (__hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == cells - 1ull) {
                 __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_fetch_add(a.t_ptr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (set_pending) __hip_atomic_store(a.pending, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const unsigned long long t = __hip_atomic_fetch_add(a.t_ptr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (set_pending) {
+                    __hip_atomic_store(a.pending, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    // which of the two message buffers this step wrote (readers must not infer it from t: the
+                    // counter can be set from outside)
+                    __hip_atomic_store(a.t_ptr + 4, t & 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
     }

@@ -61,14 +61,14 @@ def upload(g: np.ndarray, pitch=None):
     return t
 
 
-def lock_step(w: wl.Config, steps, W=None, start="random", pitch=None, bitwise=True, csr=None):
+def lock_step(w: wl.Config, steps, W=None, start="random", pitch=None, bitwise=True, csr=None, plan=None):
     """Each step: both sides start from the oracle's state, take one step, everything is compared."""
     if csr is not None:
         cfg, keep = b.make_config(w.n, w.N, wl.TOPO_CSR, w.kind, w.gamma, w.eta, bits=w.bits, block=w.block,
                                   k=w.k, seed=w.seed, W_csr=csr)
-        ds = b.DeepSqueeze(cfg, keep)
+        ds = b.DeepSqueeze(cfg, keep, plan)
     else:
-        ds = b.DeepSqueeze.from_workload(w)
+        ds = b.DeepSqueeze.from_workload(w, plan)
     st = oracle_state(w, W)
     if start == "random":
         st.x, st.delta = wl.random_state(w, seed=17)
@@ -257,20 +257,18 @@ def test_gradient_pitch_larger_than_N(w):
 
 @pytest.mark.parametrize("w", [SMALL[1], SMALL[4], SMALL[5], SMALL[10], SMALL[13], SMALL[-7], SMALL[-6], SMALL[-2]],
                          ids=lambda w: w.name)
-def test_every_candidate_launch_shape(w, monkeypatch):
-    # ds_init picks the launch shape by timing; here each candidate is pinned in turn and checked
+def test_every_candidate_launch_shape(w):
+    # ds_init picks the launch shape by timing; here each candidate is pinned in turn (ds_init_ex) and checked
     seen = []
     for i in range(12):
-        monkeypatch.setenv("DSQ_TILE_PLAN", str(i))
-        ds = b.DeepSqueeze.from_workload(w)
+        ds = b.DeepSqueeze.from_workload(w, {"tile_plan": i})
         name = ds.ds_plan_name()
         ds.ds_destroy()
         if name in seen:                                   # index past the end: the default came back
             break
         seen.append(name)
         say("case", w.name, "plan", name)
-        lock_step(w, steps=2)
-    monkeypatch.delenv("DSQ_TILE_PLAN")
+        lock_step(w, steps=2, plan={"tile_plan": i})
     assert len(seen) >= 2, seen
 
 
@@ -565,6 +563,14 @@ def test_api_errors_and_restart():
     cfg, _ = b.make_config(8, 1024, wl.TOPO_RING, wl.KIND_SIGN_MEANABS, 0.1, 0.9, block=256)
     big_eta = b.DeepSqueeze(cfg)
     assert "eta" in big_eta.ds_last_error()
+    # a failed ds_init says why (ds_init_ex), and an out-of-range plan request is refused
+    bad, _ = b.make_config(2, 1024, wl.TOPO_RING, wl.KIND_SIGN_MEANABS, 0.1, 0.4, block=256)
+    with pytest.raises(b.DsqError, match="ring needs n >= 3"):
+        b.DeepSqueeze(bad)
+    with pytest.raises(b.DsqError, match="pitch_skew"):
+        b.DeepSqueeze(cfg, plan={"pitch_skew": 6})
+    pinned = b.DeepSqueeze(cfg, plan={"autotune": 0, "pitch_skew": 4096})
+    assert pinned.ds_plan_name().endswith("pitch+4096")
 
 
 def test_two_handles_interleaved():
@@ -760,16 +766,16 @@ STREAM_CASES = [small(wl.KIND_QUANT_MAXABS, 8, 512 * 5 + 37, bits=4, block=512),
 
 
 @pytest.mark.parametrize("w", STREAM_CASES, ids=lambda w: w.name)
-def test_row_streaming_variant(w, monkeypatch):
-    """DSQ_STREAM=1 selects the row-streaming kernels of the block compressors (no LDS exchange; the gossip sum of
+def test_row_streaming_variant(w):
+    """variant = 1 in ds_init_ex's plan selects the row-streaming kernels of the block compressors (no LDS exchange; the gossip sum of
     a step is added by the next step's pass from the previous messages, which live in the other half of a double
     buffer): lock-step, then a free run whose messages are compared after every step."""
-    monkeypatch.setenv("DSQ_STREAM", "1")
-    ds = b.DeepSqueeze.from_workload(w)
+    stream = {"variant": 1}
+    ds = b.DeepSqueeze.from_workload(w, stream)
     assert ds.ds_plan_name().startswith("stream/"), ds.ds_plan_name()
     ds.ds_destroy()
-    lock_step(w, steps=3)
-    ds = b.DeepSqueeze.from_workload(w)
+    lock_step(w, steps=3, plan=stream)
+    ds = b.DeepSqueeze.from_workload(w, stream)
     st = oracle_state(w)
     for t in range(7):
         g = wl.gradient(w, t)
@@ -781,6 +787,10 @@ def test_row_streaming_variant(w, monkeypatch):
             assert assert_close("x mid", x, st.x) + assert_close("delta mid", d, st.delta) == 0
     x, d = ds.ds_read_state()
     assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+    # the last step's messages stay readable after the step counter has been set from outside to the other parity
+    before = ds.ds_read_messages()
+    ds.ds_write_state(None, None, ds.ds_step_count() + 1)
+    assert np.array_equal(ds.ds_read_messages(), before)
     ds.ds_destroy()
 
 
@@ -986,7 +996,7 @@ LONG_N = (1 << 31) + 4096 * 3 + 517          # columns beyond 2^31, byte offsets
 
 @pytest.mark.parametrize("kind,bits,block", [(wl.KIND_QUANT_MAXABS, 4, 512), (wl.KIND_SIGN_MEANABS, 0, 256)],
                          ids=["quant4b512", "sign256"])
-def test_vectors_longer_than_2_31_columns_block_operators(kind, bits, block, monkeypatch):
+def test_vectors_longer_than_2_31_columns_block_operators(kind, bits, block):
     """Three workers with 2^31 + 12,805 parameters each (77 GB of state and gradients): two steps on the GPU in
     every launch shape (the widest ones need more than 2^32 work-items and a second grid row), then windows of
     columns -- the start, the 2^31 crossing, the ragged end -- are compared with the oracle's windowed step
@@ -1006,11 +1016,9 @@ def test_vectors_longer_than_2_31_columns_block_operators(kind, bits, block, mon
         gw = g[:, c0:c1].cpu().numpy()
         oracle.step_window(st, gw, c0)
         windows.append((c0, c1, st, oracle.step_window(st, gw, c0)))
-    monkeypatch.setenv("DSQ_PITCH_SKEW", "2560")            # no timing runs: every shape is pinned in turn
     seen = []
     for plan in range(12):
-        monkeypatch.setenv("DSQ_TILE_PLAN", str(plan))
-        ds = b.DeepSqueeze.from_workload(w)
+        ds = b.DeepSqueeze.from_workload(w, {"tile_plan": plan, "pitch_skew": 2560})   # no timing runs: every shape is pinned in turn
         name = ds.ds_plan_name()
         if name in seen:                                    # index past the end: the default came back
             ds.ds_destroy()
