@@ -1,0 +1,190 @@
+// Cases for the sanitizer build (g++ -fsanitize=address,undefined) of the library's host-only code
+// (paper_1907_07346_amd/csrc/dsq_host.cpp: configuration checks, mixing matrices of the built-in topologies,
+// message sizes) and of the CPU oracle (oracle/ds_oracle.cpp).  Built and run by tests/test_sanitizers.py; any
+// report of the sanitizers aborts the run, any failed check returns non-zero.  No GPU call anywhere.
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "dsq.h"
+
+extern "C" {
+void dso_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out);
+uint64_t dso_rand_sparse_capacity(uint64_t N, uint64_t k);
+int dso_step_f32(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const float* wval, int kind, int bits, uint64_t block,
+                 uint64_t k, float gamma, float eta, uint64_t seed, uint64_t t, float* x, float* delta, const float* g, float* cv,
+                 uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes);
+int dso_step_f64(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const double* wval, int kind, int bits, uint64_t block,
+                 uint64_t k, double gamma, double eta, uint64_t seed, uint64_t t, double* x, double* delta, const double* g, double* cv,
+                 uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes);
+int dso_step_window_f32(int n, uint64_t N, uint64_t col0, const int32_t* rowptr, const int32_t* col, const float* wval, int kind, int bits,
+                        uint64_t block, float gamma, float eta, uint64_t seed, uint64_t t, float* x, float* delta, const float* g,
+                        uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes);
+}
+
+static int failures = 0;
+#define CHECK(cond)                                                              \
+    do {                                                                         \
+        if (!(cond)) { std::printf("FAILED %s:%d: %s\n", __FILE__, __LINE__, #cond); ++failures; } \
+    } while (0)
+
+static ds_config base_config(int n, uint64_t N, int topo, int kind) {
+    ds_config c;
+    std::memset(&c, 0, sizeof c);
+    c.n = n; c.N = N; c.topo = topo; c.comp.kind = kind; c.gamma = 0.1f; c.eta = 0.4f; c.seed = 7;
+    return c;
+}
+
+static void host_cases() {
+    char err[128];
+    // validation: accepted and refused configurations, with and without an error buffer, with a tiny one
+    ds_config c = base_config(8, 1000, DS_TOPO_RING, DS_COMP_QUANT_MAXABS);
+    c.comp.bits = 4; c.comp.block = 512;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_OK);
+    CHECK(ds_validate_config(&c, nullptr, 0) == DS_OK);
+    CHECK(ds_validate_config(nullptr, err, sizeof err) == DS_EINVAL);
+    c.n = 2;
+    CHECK(ds_validate_config(&c, err, 4) == DS_EINVAL && std::strlen(err) <= 3);
+    c.n = 8; c.comp.block = 48;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_EINVAL);
+    c.comp.block = 4096;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_EINVAL);
+    c.comp.block = 512; c.comp.bits = 3;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_EINVAL);
+    c.comp.bits = 4; c.gamma = NAN;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_EINVAL);
+    c.gamma = 0.1f; c.N = 0;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_EINVAL);
+    c = base_config(9, 77, DS_TOPO_TORUS2D, DS_COMP_TOPK);
+    c.torus_rows = 3; c.torus_cols = 3; c.comp.k = 7;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_OK);
+    c.comp.k = 78;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_EINVAL);
+    c.comp.k = 7; c.torus_cols = 2;
+    CHECK(ds_validate_config(&c, err, sizeof err) == DS_EINVAL);
+    // topologies: every row sums to one, is sorted, holds its diagonal
+    for (int pass = 0; pass < 2; ++pass) {
+        ds_config t = pass == 0 ? base_config(7, 10, DS_TOPO_RING, DS_COMP_IDENTITY) : base_config(12, 10, DS_TOPO_TORUS2D, DS_COMP_IDENTITY);
+        if (pass) { t.torus_rows = 3; t.torus_cols = 4; }
+        std::vector<int32_t> rowptr(t.n + 1), col(5 * t.n);
+        std::vector<float> val(5 * t.n);
+        uint64_t nnz = 0;
+        CHECK(ds_build_topology(&t, rowptr.data(), col.data(), val.data(), col.size(), &nnz) == DS_OK);
+        CHECK(nnz == (uint64_t)(pass ? 5 : 3) * t.n);
+        for (int i = 0; i < t.n; ++i) {
+            double sum = 0;
+            bool diag = false;
+            for (int e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                sum += val[e];
+                diag |= col[e] == i;
+                CHECK(e == rowptr[i] || col[e] > col[e - 1]);
+            }
+            CHECK(diag && std::fabs(sum - 1.0) < 1e-6);
+        }
+        CHECK(ds_build_topology(&t, rowptr.data(), col.data(), val.data(), 2, &nnz) == DS_EINVAL);   // capacity too small
+    }
+    // a matrix given in CSR form: accepted, then made asymmetric, then given a row that does not sum to one
+    {
+        const int n = 4;
+        int32_t rowptr[] = {0, 3, 6, 9, 12};
+        int32_t col[] = {0, 1, 3, 0, 1, 2, 1, 2, 3, 0, 2, 3};
+        float val[12];
+        for (float& v : val) v = 1.0f / 3.0f;
+        ds_config g = base_config(n, 64, DS_TOPO_CSR, DS_COMP_SIGN_MEANABS);
+        g.comp.block = 64; g.W_rowptr = rowptr; g.W_col = col; g.W_val = val;
+        CHECK(ds_validate_config(&g, err, sizeof err) == DS_OK);
+        val[1] = 0.5f; val[0] = 1.0f / 6.0f;
+        CHECK(ds_validate_config(&g, err, sizeof err) == DS_EINVAL);
+        val[1] = 1.0f / 3.0f;
+        CHECK(ds_validate_config(&g, err, sizeof err) == DS_EINVAL);
+        val[0] = 1.0f / 3.0f; col[2] = 9;
+        CHECK(ds_validate_config(&g, err, sizeof err) == DS_EINVAL);
+    }
+    // message sizes (the volume figures of the paper's section "Convergence Efficiency" up to the scale words)
+    c = base_config(8, 65536, DS_TOPO_RING, DS_COMP_QUANT_MAXABS);
+    c.comp.bits = 4; c.comp.block = 512;
+    CHECK(ds_message_bytes(&c) == 8ull * 128 * 260);
+    c.N = 11173962; c.comp.bits = 2; c.comp.block = 1024;
+    CHECK(ds_message_bytes(&c) == 8ull * (10912ull * 260 + 4 + 4 * ((74 * 2 + 31) / 32)));
+    c.comp.kind = DS_COMP_TOPK; c.comp.k = 111739;
+    CHECK(ds_message_bytes(&c) == 8ull * 111739 * 8);
+    c.comp.kind = DS_COMP_RAND_SPARSE;
+    CHECK(ds_message_bytes(&c) == 8ull * (4 + 4 * dso_rand_sparse_capacity(c.N, c.comp.k)));
+    c.comp.k = 0;
+    CHECK(ds_message_bytes(&c) == 0);
+    CHECK(std::strlen(ds_build_id()) > 0);
+}
+
+template <typename real, typename Step>
+static void oracle_case(Step step, int kind, int bits, uint64_t block, uint64_t k, int n, uint64_t N) {
+    // ring of n workers; ragged sizes; three steps; delta + C[v] == v after each (Algorithm 1, line 6)
+    std::vector<int32_t> rowptr(n + 1), col;
+    std::vector<real> w;
+    for (int i = 0; i < n; ++i) {
+        int nb[3] = {(i + n - 1) % n, i, (i + 1) % n};
+        for (int a = 0; a < 3; ++a)
+            for (int b = a + 1; b < 3; ++b)
+                if (nb[b] < nb[a]) std::swap(nb[a], nb[b]);
+        for (int e = 0; e < 3; ++e) { col.push_back(nb[e]); w.push_back((real)(1.0 / 3.0)); }
+        rowptr[i + 1] = (int32_t)col.size();
+    }
+    std::vector<real> x(n * N, 0), d(n * N, 0), g(n * N), cv(n * N), xh(n * N);
+    std::vector<uint8_t> msg(n * N * 8 + 64);
+    uint32_t ctr[4] = {1, 2, 3, 4}, key[2] = {5, 6}, out[4];
+    for (int t = 0; t < 3; ++t) {
+        for (size_t p = 0; p < g.size(); ++p) {
+            if (p % 4 == 0) { ctr[0] = (uint32_t)p; ctr[1] = (uint32_t)t; dso_philox4x32_10(ctr, key, out); }
+            g[p] = (real)((double)out[p % 4] / 4294967296.0 - 0.5);
+            xh[p] = x[p] - (real)0.1 * g[p] + d[p];             // v, up to rounding order
+        }
+        uint64_t used = 0;
+        const int rc = step(n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, (uint64_t)t,
+                            x.data(), d.data(), g.data(), cv.data(), msg.data(), msg.size(), &used);
+        CHECK(rc == 0 && used > 0 && used <= msg.size());
+        for (size_t p = 0; p < g.size(); ++p) CHECK(std::fabs((double)(d[p] + cv[p]) - (double)xh[p]) <= 1e-5 * (1.0 + std::fabs((double)xh[p])));
+    }
+    // no message buffer, no C[v] array
+    CHECK(step(n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, 3, x.data(), d.data(), g.data(),
+               nullptr, nullptr, 0, nullptr) == 0);
+    // a message buffer one byte too small is reported, not overrun
+    uint64_t used = 0;
+    std::vector<uint8_t> exact(msg.size());
+    CHECK(step(n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, 4, x.data(), d.data(), g.data(),
+               nullptr, exact.data(), exact.size(), &used) == 0);
+    std::vector<uint8_t> tight(used - 1);
+    CHECK(step(n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, 5, x.data(), d.data(), g.data(),
+               nullptr, tight.data(), tight.size(), &used) == 2);
+}
+
+static void oracle_cases() {
+    struct K { int kind, bits; uint64_t block, k; };
+    const K kinds[] = {{DS_COMP_IDENTITY, 0, 0, 0}, {DS_COMP_QUANT_MAXABS, 2, 64, 0}, {DS_COMP_QUANT_MAXABS, 4, 512, 0}, {DS_COMP_QUANT_MAXABS, 8, 128, 0},
+                       {DS_COMP_SIGN_MEANABS, 0, 256, 0}, {DS_COMP_TOPK, 0, 0, 13}, {DS_COMP_QUANT_L2NORM, 2, 0, 0}, {DS_COMP_QUANT_L2NORM, 4, 0, 0},
+                       {DS_COMP_RAND_SPARSE, 0, 0, 40}};
+    for (const K& kd : kinds)
+        for (uint64_t N : {(uint64_t)1, (uint64_t)63, (uint64_t)513, (uint64_t)1100}) {
+            const uint64_t k = kd.k ? (kd.k < N ? kd.k : N) : 0;
+            oracle_case<float>(dso_step_f32, kd.kind, kd.bits, kd.block, k, 3, N);
+            oracle_case<double>(dso_step_f64, kd.kind, kd.bits, kd.block, k, 5, N);
+        }
+    // refused arguments
+    int32_t rowptr[] = {0, 1}, col[] = {0};
+    float w[] = {1.f}, x[4] = {0}, d[4] = {0}, g[4] = {0};
+    CHECK(dso_step_f32(1, 4, rowptr, col, w, DS_COMP_QUANT_MAXABS, 3, 64, 0, 0.1f, 0.4f, 0, 0, x, d, g, nullptr, nullptr, 0, nullptr) == 1);
+    CHECK(dso_step_f32(1, 4, rowptr, col, w, DS_COMP_QUANT_MAXABS, 4, 48, 0, 0.1f, 0.4f, 0, 0, x, d, g, nullptr, nullptr, 0, nullptr) == 1);
+    CHECK(dso_step_f32(1, 4, rowptr, col, w, DS_COMP_TOPK, 0, 0, 5, 0.1f, 0.4f, 0, 0, x, d, g, nullptr, nullptr, 0, nullptr) == 1);
+    CHECK(dso_step_f32(1, 4, nullptr, col, w, DS_COMP_IDENTITY, 0, 0, 0, 0.1f, 0.4f, 0, 0, x, d, g, nullptr, nullptr, 0, nullptr) == 1);
+    CHECK(dso_step_window_f32(1, 4, 0, rowptr, col, w, DS_COMP_TOPK, 0, 0, 0.1f, 0.4f, 0, 0, x, d, g, nullptr, 0, nullptr) == 1);
+    CHECK(dso_step_window_f32(1, 4, 64, rowptr, col, w, DS_COMP_SIGN_MEANABS, 0, 64, 0.1f, 0.4f, 0, 0, x, d, g, nullptr, 0, nullptr) == 0);
+}
+
+int main() {
+    host_cases();
+    oracle_cases();
+    if (failures) { std::printf("%d checks failed\n", failures); return 1; }
+    std::printf("sanitizer cases ok\n");
+    return 0;
+}
