@@ -749,71 +749,82 @@ __global__ void __launch_bounds__(TK_THREADS) topk_write_full(TopkArgs a, Scratc
         write_full_chunk(a, s, row, chunk, wave_sums);
 }
 
-// Candidate mode, one wave per workgroup, TK_WPW chunks per wave.  A slot is unordered, so order comes from
-// two bitmaps over the chunk's columns (selected, tied): the place of a pair in the message is the number of
-// selected columns below it, and the ties that belong to the set are the `quota` lowest tied columns.
+// Candidate mode: 16 lanes per chunk, so a wave (= a workgroup) writes four chunks side by side, TK_WPW / 4
+// times in a row.  A slot is unordered, so order comes from two bitmaps over the chunk's columns (selected,
+// tied): the place of a pair in the message is the number of selected columns below it, and the ties that
+// belong to the set are the `quota` lowest tied columns.
 constexpr int TK_WORDS = TK_CHUNK / 32;                        // bitmap words per chunk
-__device__ __forceinline__ void bitmap_prefix(const uint32_t* bits, uint32_t* prefix, int lane) {
-    // prefix[w] = number of set bits in words [0, w); 2 consecutive words per lane
-    uint32_t c[TK_WORDS / 64], sum = 0;
+constexpr int TK_GL = 16;                                      // lanes per chunk
+constexpr int TK_WPL = TK_WORDS / TK_GL;                       // bitmap words per lane (consecutive)
+// prefix[w] = number of set bits in words [0, w) of one chunk's bitmap; the TK_GL lanes of the chunk call together
+__device__ __forceinline__ void bitmap_prefix(const uint32_t* bits, uint32_t* prefix, int sub) {
+    uint32_t c[TK_WPL], sum = 0;
 #pragma unroll
-    for (int q = 0; q < TK_WORDS / 64; ++q) { c[q] = __popc(bits[lane * (TK_WORDS / 64) + q]); sum += c[q]; }
+    for (int q = 0; q < TK_WPL; ++q) { c[q] = __popc(bits[sub * TK_WPL + q]); sum += c[q]; }
     uint32_t inc = sum;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(inc, o);
-        if (lane >= o) inc += up;
+    for (int o = 1; o < TK_GL; o <<= 1) {
+        const uint32_t up = __shfl_up(inc, o, TK_GL);
+        if (sub >= o) inc += up;
     }
     uint32_t run = inc - sum;
 #pragma unroll
-    for (int q = 0; q < TK_WORDS / 64; ++q) { prefix[lane * (TK_WORDS / 64) + q] = run; run += c[q]; }
+    for (int q = 0; q < TK_WPL; ++q) { prefix[sub * TK_WPL + q] = run; run += c[q]; }
 }
 __device__ __forceinline__ uint32_t bitmap_rank(const uint32_t* bits, const uint32_t* prefix, uint32_t q) {
     return prefix[q >> 5] + __popc(bits[q >> 5] & ((1u << (q & 31)) - 1u));
 }
 
 __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
-    __shared__ uint32_t sel_bits[TK_WORDS], eq_bits[TK_WORDS], prefix[TK_WORDS];      // of the chunk being written
+    constexpr int GROUPS = 64 / TK_GL;                         // chunks side by side in the wave
+    constexpr int TURNS = TK_WPW / GROUPS;
+    constexpr int SPEC = 8;                                    // slot entries per lane held in registers: 128 per chunk
+    __shared__ uint32_t sel_all[GROUPS][TK_WORDS], eq_all[GROUPS][TK_WORDS], prefix_all[GROUPS][TK_WORDS];
     const int row = blockIdx.y;
     if (!s.rows[row].cand_mode) return;                     // uniform
-    const int lane = threadIdx.x;
-    const uint32_t nchunks = s.nchunks, chunk0 = blockIdx.x * TK_WPW;
+    const int lane = threadIdx.x, grp = lane / TK_GL, sub = lane % TK_GL;
+    uint32_t* sel_bits = sel_all[grp];
+    uint32_t* eq_bits = eq_all[grp];
+    uint32_t* prefix = prefix_all[grp];
+    const uint32_t nchunks = s.nchunks;
     const uint32_t tau = s.rows[row].tau, r_tie = s.rows[row].r_tie;
-    // The slots go into registers.  The first two pairs per lane of every chunk (what a slot normally holds) are
-    // loaded before anything is known about the chunk (the slot's memory exists whatever its fill; what lies
-    // behind `cnt` is discarded below), together with the chunks' counters: one round trip to memory for the
-    // wave's TK_WPW chunks.
-    constexpr int SPEC = 2;
-    uint2 ent[TK_WPW][SPEC];
-    uint32_t cnt[TK_WPW], off0[TK_WPW], off1[TK_WPW], eqb[TK_WPW], ceq[TK_WPW];
+    uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
+    // All loads of the wave's chunks go out first: the slots' first 128 entries (what a slot normally holds; the
+    // slot's memory exists whatever its fill, what lies behind `cnt` is discarded below) and the chunks' counters.
+    uint2 ent[TURNS][SPEC];
+    uint32_t cnt[TURNS], off0[TURNS], off1[TURNS], eqb[TURNS], ceq[TURNS];
 #pragma unroll
-    for (int c = 0; c < TK_WPW; ++c) {
-        const uint32_t chunk = (chunk0 + c < nchunks) ? chunk0 + c : nchunks - 1;     // a clamped chunk is skipped below
+    for (int tn = 0; tn < TURNS; ++tn) {
+        const uint32_t want = blockIdx.x * TK_WPW + tn * GROUPS + grp;
+        const uint32_t chunk = want < nchunks ? want : nchunks - 1;              // a clamped chunk is skipped below
         const size_t cidx = (size_t)row * nchunks + chunk;
 #pragma unroll
         for (int u = 0; u < SPEC; ++u) {
-            const uint32_t p = (uint32_t)u * 64 + lane;
-            ent[c][u] = make_uint2(s.slot_idx[cidx * TK_CAP + p], s.slot_val[cidx * TK_CAP + p]);   // .x: column in the chunk
+            const uint32_t p = (uint32_t)u * TK_GL + sub;
+            ent[tn][u] = make_uint2(s.slot_idx[cidx * TK_CAP + p], s.slot_val[cidx * TK_CAP + p]);   // .x: column in the chunk
         }
-        cnt[c] = s.cand_cnt[cidx];
-        off0[c] = s.out_off[(size_t)row * (nchunks + 1) + chunk];
-        off1[c] = s.out_off[(size_t)row * (nchunks + 1) + chunk + 1];
-        eqb[c] = s.eq_before[cidx];
-        ceq[c] = s.cnt_eq[cidx];
+        cnt[tn] = s.cand_cnt[cidx];
+        off0[tn] = s.out_off[(size_t)row * (nchunks + 1) + chunk];
+        off1[tn] = s.out_off[(size_t)row * (nchunks + 1) + chunk + 1];
+        eqb[tn] = s.eq_before[cidx];
+        ceq[tn] = s.cnt_eq[cidx];
     }
-    uint2* out = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
 #pragma unroll
-    for (int c = 0; c < TK_WPW; ++c) {
-        const uint32_t chunk = chunk0 + c;
-        if (chunk >= nchunks || off0[c] == off1[c]) continue;                         // uniform
-        const size_t cidx = (size_t)row * nchunks + chunk;
+    for (int tn = 0; tn < TURNS; ++tn) {
+        // every lane walks through all barriers of a turn (one wave: they only order its LDS accesses); a group
+        // with nothing to write idles through them
+        const uint32_t chunk = blockIdx.x * TK_WPW + tn * GROUPS + grp;
+        const bool active = chunk < nchunks && off0[tn] != off1[tn];
+        const size_t cidx = (size_t)row * nchunks + (chunk < nchunks ? chunk : 0u);
         const uint32_t* slot_val = s.slot_val + cidx * TK_CAP;
         const uint16_t* slot_idx = s.slot_idx + cidx * TK_CAP;
         const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
-        const uint32_t quota = (eqb[c] < r_tie) ? (r_tie - eqb[c]) : 0u;          // ties of this chunk that belong to the set
-        const bool ties = ceq[c] != 0 && quota != 0;
-        for (int w = lane; w < TK_WORDS; w += 64) { sel_bits[w] = 0; eq_bits[w] = 0; }
-        __syncthreads();                                    // (one wave: orders its LDS accesses)
+        const uint32_t quota = (eqb[tn] < r_tie) ? (r_tie - eqb[tn]) : 0u;        // ties of this chunk that belong to the set
+        const bool ties = active && ceq[tn] != 0 && quota != 0;
+        const uint32_t n_ent = active ? cnt[tn] : 0u;
+#pragma unroll
+        for (int q = 0; q < TK_WPL; ++q) { sel_bits[sub * TK_WPL + q] = 0; eq_bits[sub * TK_WPL + q] = 0; }
+        __syncthreads();
         auto mark = [&](uint32_t q, uint32_t bits) {
             const uint32_t key = bits & 0x7FFFFFFFu;
             if (key > tau) atomicOr(&sel_bits[q >> 5], 1u << (q & 31));
@@ -821,14 +832,16 @@ __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
         };
 #pragma unroll
         for (int u = 0; u < SPEC; ++u)
-            if ((uint32_t)u * 64 + lane < cnt[c]) mark(ent[c][u].x, ent[c][u].y);
-        for (uint32_t p = SPEC * 64 + lane; p < cnt[c]; p += 64) mark(slot_idx[p], slot_val[p]);   // a fuller slot than usual
+            if ((uint32_t)u * TK_GL + sub < n_ent) mark(ent[tn][u].x, ent[tn][u].y);
+        for (uint32_t p = SPEC * TK_GL + sub; p < n_ent; p += TK_GL) mark(slot_idx[p], slot_val[p]);   // a fuller slot than usual
         __syncthreads();
-        if (ties) {                                         // uniform
-            bitmap_prefix(eq_bits, prefix, lane);
-            __syncthreads();
-            for (int w = lane; w < TK_WORDS; w += 64) {
+        if (ties) bitmap_prefix(eq_bits, prefix, sub);          // all lanes of the group together
+        __syncthreads();
+        if (ties) {
+#pragma unroll
+            for (int q = 0; q < TK_WPL; ++q) {
                 // keep the tied columns whose rank among the ties is below the quota
+                const int w = sub * TK_WPL + q;
                 uint32_t word = eq_bits[w], keep = 0;
                 uint32_t rank = prefix[w];
                 while (word) {
@@ -839,21 +852,21 @@ __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
                 }
                 sel_bits[w] |= keep;
             }
-            __syncthreads();
         }
-        bitmap_prefix(sel_bits, prefix, lane);
+        __syncthreads();
+        bitmap_prefix(sel_bits, prefix, sub);
         __syncthreads();
         auto emit = [&](uint32_t q, uint32_t bits) {
             if (sel_bits[q >> 5] & (1u << (q & 31))) {
-                const uint32_t pos = off0[c] + bitmap_rank(sel_bits, prefix, q);
-                if (pos < a.k && pos < off1[c]) out[pos] = make_uint2((uint32_t)(c0 + q), bits);
+                const uint32_t pos = off0[tn] + bitmap_rank(sel_bits, prefix, q);
+                if (pos < a.k && pos < off1[tn]) out[pos] = make_uint2((uint32_t)(c0 + q), bits);
             }
         };
 #pragma unroll
         for (int u = 0; u < SPEC; ++u)
-            if ((uint32_t)u * 64 + lane < cnt[c]) emit(ent[c][u].x, ent[c][u].y);
-        for (uint32_t p = SPEC * 64 + lane; p < cnt[c]; p += 64) emit(slot_idx[p], slot_val[p]);
-        __syncthreads();                                    // the bitmaps are reused by the next chunk
+            if ((uint32_t)u * TK_GL + sub < n_ent) emit(ent[tn][u].x, ent[tn][u].y);
+        for (uint32_t p = SPEC * TK_GL + sub; p < n_ent; p += TK_GL) emit(slot_idx[p], slot_val[p]);
+        __syncthreads();                                    // the bitmaps are reused by the next turn
     }
 }
 
