@@ -23,6 +23,10 @@
 // floating-point evaluation order used for `real = float`, are this
 // repository's readings; every one is stated next to the code that does it.
 //
+// After the DeepSqueeze step come the two compressed decentralized methods the
+// paper compares it with (DCD-PSGD, CHOCO-SGD), as this repository reads them
+// from the paper's unrolled forms; see the note above step_dcd.
+//
 // Every function below is pinned by tests/test_oracle_pins.py against what the
 // paper and plain mathematics fix.  What nothing available can fix is the CHOICE
 // of the operators' grids, rounding and tie rules where the paper is silent
@@ -312,19 +316,11 @@ bool compress_row_rand_sparse(const real* v, real* cv, uint64_t N, uint64_t k,
     return !overflow;
 }
 
-// ---------------------------------------------------------------------------
-// One iteration for all workers.  Dense n x N row-major arrays throughout.
-// W comes as CSR (rowptr, col, val) *including* the diagonal entry of every
-// row, columns ascending; the mixing coefficient of line 9 is
-// a_ij = W_ij - I_ij, formed once in `real`.
-// ---------------------------------------------------------------------------
+// Argument and CSR sanity shared by the update rules below: 0 if fine.
 template <typename real>
-int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
-         int kind, int bits, uint64_t block, uint64_t k,
-         real gamma, real eta, uint64_t seed, uint64_t t,
-         real* x, real* delta, const real* g,
-         real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes, uint64_t col0 = 0) {
-    if (n < 1 || N < 1 || !rowptr || !col || !wval || !x || !delta || !g) return 1;
+int check_arguments(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
+                    int kind, int bits, uint64_t block, uint64_t k, const real* x, const real* state2, const real* g) {
+    if (n < 1 || N < 1 || !rowptr || !col || !wval || !x || !state2 || !g) return 1;
     if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && (block < 1 || (block & (block - 1)))) return 1;
     if ((kind == QUANT_MAXABS || kind == QUANT_L2NORM) && (bits < 1 || bits > 8 || 32 % bits)) return 1;
     if ((kind == TOPK || kind == RAND_SPARSE) && (k < 1 || k > N)) return 1;
@@ -338,25 +334,17 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
         }
         if (!diag) return 1;
     }
+    return 0;
+}
 
-    const uint64_t total = (uint64_t)n * N;
-    std::vector<real> xh(total), v(total), cv_local;
-    real* cv = cv_out;
-    if (!cv) { cv_local.resize(total); cv = cv_local.data(); }
+// C_omega applied to every worker's vector (rows of v -> rows of cv), and what each worker sends written to
+// msg_buf in worker order.  Every worker appends to a sink of its own; the sinks are joined afterwards (so
+// workers may be processed side by side).  Returns 0, 1 (unknown operator), 2 (msg_buf too small) or 3 (a
+// random-sparsification message outgrew its capacity).
+template <typename real>
+int compress_workers(int n, uint64_t N, const real* v, real* cv, int kind, int bits, uint64_t block, uint64_t k,
+                     uint64_t seed, uint64_t t, uint64_t col0, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes) {
     bool sparse_overflow = false;
-
-    // Algorithm 1, line 5: the error-compensated variable, evaluated as
-    // (x - gamma g) + delta with the product fused into the first sum.
-#pragma omp parallel for schedule(static)
-    for (int i = 0; i < n; ++i)
-        for (uint64_t j = 0; j < N; ++j) {
-            const uint64_t p = (uint64_t)i * N + j;
-            xh[p] = fma_<real>(-gamma, g[p], x[p]);
-            v[p] = xh[p] + delta[p];
-        }
-
-    // Line 6, first half, and lines 7-8: compress, and write what is sent.  Every worker appends to a sink of
-    // its own; the sinks are joined in worker order afterwards (so workers may be processed side by side).
     std::vector<std::vector<uint8_t>> sent(msg_buf ? n : 0);
     bool bad_kind = false;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -397,13 +385,16 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
         std::memcpy(msg_buf + msg_used, sent[i].data(), sent[i].size());
         msg_used += sent[i].size();
     }
+    if (msg_bytes) *msg_bytes = msg_used;
+    if (sparse_overflow) return 3;
+    return msg_overflow ? 2 : 0;
+}
 
-    // Line 6, second half: what compression lost is carried to the next step.
-#pragma omp parallel for schedule(static)
-    for (uint64_t p = 0; p < total; ++p) delta[p] = v[p] - cv[p];
-
-    // Line 9: gossip on the compressed values, neighbours in ascending index
-    // order (own index included), accumulated by a chain of fused multiply-adds.
+// out_i = sum_{j in N(i)} (W_ij - I_ij) src_j for every worker: neighbours in ascending index order (own index
+// included), accumulated by a chain of fused multiply-adds starting from zero.
+template <typename real>
+void mix_minus_identity(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
+                        const real* src, real* out) {
 #pragma omp parallel for schedule(static)
     for (int i = 0; i < n; ++i)
         for (uint64_t j = 0; j < N; ++j) {
@@ -411,15 +402,132 @@ int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const rea
             for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
                 const int nb = col[e];
                 const real a = (nb == i) ? (wval[e] - (real)1) : wval[e];
-                acc = fma_<real>(a, cv[(uint64_t)nb * N + j], acc);
+                acc = fma_<real>(a, src[(uint64_t)nb * N + j], acc);
             }
+            out[(uint64_t)i * N + j] = acc;
+        }
+}
+
+// ---------------------------------------------------------------------------
+// One iteration for all workers.  Dense n x N row-major arrays throughout.
+// W comes as CSR (rowptr, col, val) *including* the diagonal entry of every
+// row, columns ascending; the mixing coefficient of line 9 is
+// a_ij = W_ij - I_ij, formed once in `real`.
+// ---------------------------------------------------------------------------
+template <typename real>
+int step(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
+         int kind, int bits, uint64_t block, uint64_t k,
+         real gamma, real eta, uint64_t seed, uint64_t t,
+         real* x, real* delta, const real* g,
+         real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes, uint64_t col0 = 0) {
+    if (check_arguments<real>(n, N, rowptr, col, wval, kind, bits, block, k, x, delta, g)) return 1;
+
+    const uint64_t total = (uint64_t)n * N;
+    std::vector<real> xh(total), v(total), mixed(total), cv_local;
+    real* cv = cv_out;
+    if (!cv) { cv_local.resize(total); cv = cv_local.data(); }
+
+    // Algorithm 1, line 5: the error-compensated variable, evaluated as
+    // (x - gamma g) + delta with the product fused into the first sum.
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < n; ++i)
+        for (uint64_t j = 0; j < N; ++j) {
             const uint64_t p = (uint64_t)i * N + j;
-            x[p] = fma_<real>(eta, acc, xh[p]);
+            xh[p] = fma_<real>(-gamma, g[p], x[p]);
+            v[p] = xh[p] + delta[p];
         }
 
-    if (msg_bytes) *msg_bytes = msg_used;
-    if (sparse_overflow) return 3;
-    return msg_overflow ? 2 : 0;
+    // Line 6, first half, and lines 7-8: compress, and write what is sent.
+    const int rc = compress_workers<real>(n, N, v.data(), cv, kind, bits, block, k, seed, t, col0, msg_buf, msg_cap, msg_bytes);
+    if (rc == 1) return 1;
+
+    // Line 6, second half: what compression lost is carried to the next step.
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) delta[p] = v[p] - cv[p];
+
+    // Line 9: gossip on the compressed values.
+    mix_minus_identity<real>(n, N, rowptr, col, wval, cv, mixed.data());
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) x[p] = fma_<real>(eta, mixed[p], xh[p]);
+    return rc;
+}
+
+// ---------------------------------------------------------------------------
+// The two compressed decentralized methods the paper measures DeepSqueeze against (section "Why DeepSqueeze is
+// better", the DCD-PSGD and CHOCO-SGD items; section "Related Work", "Compressed Communication Distributed
+// Learning").  The paper gives no update rule for them, only unrolled forms of X_t and two statements: with no
+// compression error every method is the paper's D-PSGD, X+ = (X - gamma G) W_eff; and the error of one step
+// reaches X through a power of W_eff alone (DCD-PSGD), or through (W_eff - I) times such a power (CHOCO-SGD).
+// The rules below are this repository's reading: the simplest per-worker rules with exactly those two
+// properties, written in the notation of Algorithm 1 and with the same C_omega, message format and mixing
+// coefficients W_ij - I_ij as the step above.  Their unrolled forms (derived by induction, pinned over six steps
+// in tests/test_oracle_pins.py) differ from the printed ones in the exponent of W_eff, a stray factor eta and,
+// for DCD-PSGD, the last term of the sum, the same kind of slip the printed DeepSqueeze form has.  Against
+// the cited papers themselves they are "parity unpinned": neither is available here.
+// ---------------------------------------------------------------------------
+
+// DCD-PSGD ("use the difference of the model updates as the shared information"): every worker compresses
+// the move the uncompressed method would make, and applies the compressed move; so does everyone who keeps
+// a copy of its model, which is why the copies stay exact and X itself can stand for them.
+//   xh_i = x_i - gamma g_i
+//   z_i  = xh_i + eta sum_{j in N(i)} (W_ij - I_ij) xh_j - x_i        (the D-PSGD target minus the model)
+//   x_i  = x_i + C[z_i];     the message is the packed C[z_i]
+// Matrix form: X+ = (X - gamma G) W_eff - Delta_t, Delta_t = Z_t - C[Z_t].
+// Unrolled, X_0 = 0:  X_t = -gamma sum_{s<t} G_s W_eff^{t-s} - sum_{s<t} Delta_s W_eff^{t-1-s}.
+// No state besides x: `delta` is left untouched.
+template <typename real>
+int step_dcd(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
+             int kind, int bits, uint64_t block, uint64_t k, real gamma, real eta, uint64_t seed, uint64_t t,
+             real* x, real* delta_unused, const real* g, real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes) {
+    if (check_arguments<real>(n, N, rowptr, col, wval, kind, bits, block, k, x, delta_unused, g)) return 1;
+    const uint64_t total = (uint64_t)n * N;
+    std::vector<real> xh(total), mixed(total), z(total), cv_local;
+    real* cv = cv_out;
+    if (!cv) { cv_local.resize(total); cv = cv_local.data(); }
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) xh[p] = fma_<real>(-gamma, g[p], x[p]);
+    mix_minus_identity<real>(n, N, rowptr, col, wval, xh.data(), mixed.data());
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) z[p] = fma_<real>(eta, mixed[p], xh[p]) - x[p];
+    const int rc = compress_workers<real>(n, N, z.data(), cv, kind, bits, block, k, seed, t, 0, msg_buf, msg_cap, msg_bytes);
+    if (rc == 1) return 1;
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) x[p] = x[p] + cv[p];
+    return rc;
+}
+
+// CHOCO-SGD ("sharing the difference of the model difference"): every worker i has a public copy xhat_i of its
+// model, known to its neighbours, which moves only by compressed differences; the gossip step runs on the copies.
+//   xh_i   = x_i - gamma g_i
+//   q_i    = C[xh_i - xhat_i];       the message is the packed q_i
+//   xhat_i = xhat_i + q_i
+//   x_i    = xh_i + eta sum_{j in N(i)} (W_ij - I_ij) xhat_j        (the copies after their update)
+// Matrix form: X+ = (X - gamma G) W_eff - Delta_t (W_eff - I), Delta_t = (X - gamma G) - Xhat+  (what the copy
+// still misses; equal to the compression error of this step's difference).
+// Unrolled, X_0 = Xhat_0 = 0:  X_t = -gamma sum_{s<t} G_s W_eff^{t-s} - sum_{s<t} Delta_s (W_eff - I) W_eff^{t-1-s}.
+// `xhat` takes the place of delta in the state.
+template <typename real>
+int step_choco(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
+               int kind, int bits, uint64_t block, uint64_t k, real gamma, real eta, uint64_t seed, uint64_t t,
+               real* x, real* xhat, const real* g, real* cv_out, uint8_t* msg_buf, uint64_t msg_cap, uint64_t* msg_bytes) {
+    if (check_arguments<real>(n, N, rowptr, col, wval, kind, bits, block, k, x, xhat, g)) return 1;
+    const uint64_t total = (uint64_t)n * N;
+    std::vector<real> xh(total), d(total), mixed(total), cv_local;
+    real* q = cv_out;
+    if (!q) { cv_local.resize(total); q = cv_local.data(); }
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) {
+        xh[p] = fma_<real>(-gamma, g[p], x[p]);
+        d[p] = xh[p] - xhat[p];
+    }
+    const int rc = compress_workers<real>(n, N, d.data(), q, kind, bits, block, k, seed, t, 0, msg_buf, msg_cap, msg_bytes);
+    if (rc == 1) return 1;
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) xhat[p] = xhat[p] + q[p];
+    mix_minus_identity<real>(n, N, rowptr, col, wval, xhat, mixed.data());
+#pragma omp parallel for schedule(static)
+    for (uint64_t p = 0; p < total; ++p) x[p] = fma_<real>(eta, mixed[p], xh[p]);
+    return rc;
 }
 
 }  // namespace
@@ -476,6 +584,25 @@ int dso_step_f64(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, c
                  double* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
     return step<double>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t,
                         x, delta, g, cv, msg, msg_cap, msg_bytes);
+}
+
+// The comparison updates: algo 1 = DCD-PSGD (state2 is not used), algo 2 = CHOCO-SGD (state2 = xhat).
+int dso_compare_step_f32(int algo, int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const float* wval,
+                         int kind, int bits, uint64_t block, uint64_t k, float gamma, float eta,
+                         uint64_t seed, uint64_t t, float* x, float* state2, const float* g,
+                         float* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
+    if (algo == 1) return step_dcd<float>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t, x, state2, g, cv, msg, msg_cap, msg_bytes);
+    if (algo == 2) return step_choco<float>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t, x, state2, g, cv, msg, msg_cap, msg_bytes);
+    return 1;
+}
+
+int dso_compare_step_f64(int algo, int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const double* wval,
+                         int kind, int bits, uint64_t block, uint64_t k, double gamma, double eta,
+                         uint64_t seed, uint64_t t, double* x, double* state2, const double* g,
+                         double* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
+    if (algo == 1) return step_dcd<double>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t, x, state2, g, cv, msg, msg_cap, msg_bytes);
+    if (algo == 2) return step_choco<double>(n, N, rowptr, col, wval, kind, bits, block, k, gamma, eta, seed, t, x, state2, g, cv, msg, msg_cap, msg_bytes);
+    return 1;
 }
 
 }  // extern "C"

@@ -21,6 +21,10 @@ KIND_TOPK = 3          # k largest magnitudes of the whole vector
 KIND_QUANT_L2NORM = 4  # b-bit codes over the whole vector + its Euclidean norm (the paper's experiments)
 KIND_RAND_SPARSE = 5   # every element kept with probability k/N, no rescaling
 
+ALGO_DEEPSQUEEZE = 0   # Algorithm 1
+ALGO_DCD_PSGD = 1      # compressed difference of the model update ("Why DeepSqueeze is better", DCD-PSGD item)
+ALGO_CHOCO_SGD = 2     # compressed difference to a public copy, gossip on the copies (same section, CHOCO-SGD item)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ds_oracle.cpp")
 _LIB = os.path.join(_HERE, "libds_oracle.so")
@@ -60,6 +64,11 @@ def _load(omp: bool = False):
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [i32, u64, vp, vp, vp, i32, i32, u64, u64, real, real, u64, u64,
+                       vp, vp, vp, vp, vp, u64, ctypes.POINTER(u64)]
+    for name, real in (("dso_compare_step_f32", ctypes.c_float), ("dso_compare_step_f64", ctypes.c_double)):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [i32, i32, u64, vp, vp, vp, i32, i32, u64, u64, real, real, u64, u64,
                        vp, vp, vp, vp, vp, u64, ctypes.POINTER(u64)]
     lib.dso_step_window_f32.restype = ctypes.c_int
     lib.dso_step_window_f32.argtypes = [i32, u64, u64, vp, vp, vp, i32, i32, u64, ctypes.c_float, ctypes.c_float,
@@ -174,7 +183,10 @@ def message_bytes(kind: int, n: int, N: int, bits: int = 0, block: int = 0, k: i
 
 @dataclass
 class OracleState:
-    """x, delta (n x N), the step counter and the fixed parameters of a run."""
+    """x, delta (n x N), the step counter and the fixed parameters of a run.
+
+    algo selects the update rule; for ALGO_CHOCO_SGD `delta` holds the workers' public copies xhat, for
+    ALGO_DCD_PSGD it is not used."""
     n: int
     N: int
     W: np.ndarray                      # dense n x n, float64
@@ -187,6 +199,7 @@ class OracleState:
     seed: int = 0
     dtype: type = np.float32
     t: int = 0
+    algo: int = ALGO_DEEPSQUEEZE
     x: np.ndarray = field(default=None, repr=False)
     delta: np.ndarray = field(default=None, repr=False)
 
@@ -261,7 +274,12 @@ def step(st: OracleState, g: np.ndarray, want_cv: bool = True, want_msg: bool = 
     cap = message_bytes(st.kind, st.n, st.N, st.bits, st.block, st.k) if want_msg else 0
     msg = np.zeros(cap, dtype=np.uint8) if want_msg else None
     used = ctypes.c_uint64(0)
-    fn = lib.dso_step_f32 if dt == np.dtype(np.float32) else lib.dso_step_f64
+    f32 = dt == np.dtype(np.float32)
+    if st.algo == ALGO_DEEPSQUEEZE:
+        fn = lib.dso_step_f32 if f32 else lib.dso_step_f64
+    else:
+        compare = lib.dso_compare_step_f32 if f32 else lib.dso_compare_step_f64
+        fn = lambda *a: compare(st.algo, *a)
     rc = fn(st.n, st.N, rowptr.ctypes.data, col.ctypes.data, wval.ctypes.data,
             st.kind, st.bits, st.block, st.k, st.gamma, st.eta, st.seed, st.t,
             st.x.ctypes.data, st.delta.ctypes.data, g.ctypes.data,
