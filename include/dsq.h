@@ -80,6 +80,24 @@ typedef struct {
                       /* 1 <= k <= N; otherwise ignored                                         */
 } ds_comp;
 
+/* Update rule of a step.  DS_ALGO_DEEPSQUEEZE is Algorithm 1.  The other two are the compressed decentralized
+ * methods the paper measures DeepSqueeze against (section "Why DeepSqueeze is better", the DCD-PSGD and
+ * CHOCO-SGD items; section "Experiments").  The paper states no update rule for them, only unrolled forms of X_t
+ * and two properties: without compression error each is the paper's D-PSGD, X+ = (X - gamma G) W_eff, and one
+ * step's error reaches X through powers of W_eff alone (DCD-PSGD) or through (W_eff - I) times such powers
+ * (CHOCO-SGD).  The rules below are the simplest per-worker rules with those properties, in Algorithm 1's
+ * notation, with the same C_omega, message layout and coefficients W_ij - I_ij (xh_i = x_i - gamma g_i):
+ *   DS_ALGO_DCD_PSGD   z_i = xh_i + eta sum_{j in N(i)} (W_ij - I_ij) xh_j - x_i;   x_i = x_i + C[z_i];
+ *                      message_i = packed C[z_i].  No second state array: delta is not touched.
+ *   DS_ALGO_CHOCO_SGD  q_i = C[xh_i - xhat_i];   xhat_i = xhat_i + q_i;   message_i = packed q_i;
+ *                      x_i = xh_i + eta sum_{j in N(i)} (W_ij - I_ij) xhat_j  (the copies after their update).
+ *                      The workers' public copies xhat_i take the place of delta_i in the state: wherever this
+ *                      header says delta (ds_read_state, ds_write_state, ds_state_ptrs, ds_diagnostics out[1]
+ *                      and out[2]) read xhat.
+ * Both are served for DS_COMP_QUANT_MAXABS and DS_COMP_SIGN_MEANABS by a fused tile kernel that keeps n rows
+ * of one tile in LDS as fp32: n * max(block, 256) * 4 bytes must fit in 160 KB. */
+typedef enum { DS_ALGO_DEEPSQUEEZE = 0, DS_ALGO_DCD_PSGD = 1, DS_ALGO_CHOCO_SGD = 2 } ds_algorithm;
+
 typedef struct {
     int32_t  n;               /* number of workers (rows), >= 1                                  */
     int32_t  topo;            /* ds_topology                                                     */
@@ -97,6 +115,8 @@ typedef struct {
     float    eta;             /* averaging rate; the paper's Theorem 1 wants eta <= 1/2: a larger */
                               /* value is accepted and noted in ds_last_error                    */
     uint64_t seed;            /* key of the random streams (stochastic rounding, sparsifier mask) */
+    int32_t  algo;            /* ds_algorithm; 0 = DeepSqueeze                                    */
+    int32_t  reserved;        /* must be 0                                                        */
 } ds_config;
 
 /* ---- host-only helpers (no GPU needed) ------------------------------------------------------ */

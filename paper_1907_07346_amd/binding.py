@@ -48,7 +48,7 @@ class ds_config(ctypes.Structure):
                 ("torus_rows", ctypes.c_int32), ("torus_cols", ctypes.c_int32),
                 ("W_rowptr", ctypes.c_void_p), ("W_col", ctypes.c_void_p), ("W_val", ctypes.c_void_p),
                 ("comp", ds_comp), ("gamma", ctypes.c_float), ("eta", ctypes.c_float),
-                ("seed", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("algo", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class DsqError(RuntimeError):
@@ -102,7 +102,7 @@ def lib() -> ctypes.CDLL:
 
 
 def make_config(n: int, N: int, topo: int, kind: int, gamma: float, eta: float, *, bits: int = 0,
-                block: int = 0, k: int = 0, torus=(0, 0), seed: int = 0, W_csr=None):
+                block: int = 0, k: int = 0, torus=(0, 0), seed: int = 0, W_csr=None, algo: int = 0):
     """Fills a ds_config. W_csr = (rowptr int32, col int32, val float32) numpy arrays for TOPO_CSR.
 
     Returns (config, keepalive): keepalive holds the arrays the config points to.
@@ -119,6 +119,7 @@ def make_config(n: int, N: int, topo: int, kind: int, gamma: float, eta: float, 
         c.W_rowptr, c.W_col, c.W_val = rp.ctypes.data, co.ctypes.data, va.ctypes.data
     c.comp.kind, c.comp.bits, c.comp.block, c.comp.k = kind, bits, block, k
     c.gamma, c.eta, c.seed = gamma, eta, seed
+    c.algo = algo
     return c, keep
 
 
@@ -136,7 +137,7 @@ def ds_workload_gradient(kind: str, n: int, N: int, scale: float, seed: int, t: 
 
 def config_from_workload(w: Config):
     return make_config(w.n, w.N, w.topo, w.kind, w.gamma, w.eta, bits=w.bits, block=w.block, k=w.k,
-                       torus=w.torus, seed=w.seed)
+                       torus=w.torus, seed=w.seed, algo=w.algo)
 
 
 def ds_validate_config(cfg: ds_config):

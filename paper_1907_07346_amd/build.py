@@ -11,7 +11,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libdsq.so")
 SOURCES = ["dsq_tile_quant4.hip", "dsq_tile_quant2.hip", "dsq_tile_quant8.hip", "dsq_tile_sign.hip", "dsq_tile_misc.hip", "dsq_host.cpp", "dsq_api.hip",
-           "dsq_topk_kernels.hip", "dsq_l2norm_kernels.hip", "dsq_workload_kernels.hip"]
+           "dsq_topk_kernels.hip", "dsq_l2norm_kernels.hip", "dsq_workload_kernels.hip",
+           "dsq_compare_quant4.hip", "dsq_compare_quant2.hip", "dsq_compare_quant8.hip", "dsq_compare_sign.hip"]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is written out as fmaf, nothing else may fuse
 #  (bit-level agreement of codes and scales depends on it).  The packed-fp32 feature is switched off because

@@ -323,6 +323,7 @@ ds_status ds_step_static(const ds_config* cfg, float* x_dev, float* delta_dev, u
     };
     if (dsq::validate_config(cfg, err, &warn) != DS_OK) return fail_with(DS_EINVAL, err);
     const int kind = cfg->comp.kind;
+    if (cfg->algo != DS_ALGO_DEEPSQUEEZE) return fail_with(DS_EINVAL, "ds_step_static serves Algorithm 1 (DS_ALGO_DEEPSQUEEZE) only");
     if (kind != DS_COMP_QUANT_MAXABS && kind != DS_COMP_SIGN_MEANABS && kind != DS_COMP_IDENTITY)
         return fail_with(DS_EINVAL, "ds_step_static serves the block quantiser, the sign compressor and the identity only "
                                     "(the other compressors need scratch memory in proportion to N)");
@@ -498,7 +499,8 @@ ds_status ds_init_ex(const ds_config* cfg, const ds_plan_request* plan, char* er
     }
     h->ld = base_ld + skew;
     if (tiled)
-        h->plan_name = std::string(h->tile.name) + "/" + std::to_string(h->tile.sweeps) + "sweeps";
+        h->plan_name = std::string(cfg->algo == DS_ALGO_DCD_PSGD ? "dcd/" : cfg->algo == DS_ALGO_CHOCO_SGD ? "choco/" : "") + h->tile.name + "/" +
+                       std::to_string(h->tile.sweeps) + "sweeps";
     h->plan_name += "/pitch+" + std::to_string(skew);
 
     if (cfg->comp.kind == DS_COMP_TOPK) {

@@ -80,6 +80,13 @@ ds_status validate_config(const ds_config* cfg, std::string& err, std::string* w
             break;
         default: err = "unknown compressor"; return DS_EINVAL;
     }
+    if (cfg->algo != DS_ALGO_DEEPSQUEEZE) {
+        if (cfg->algo != DS_ALGO_DCD_PSGD && cfg->algo != DS_ALGO_CHOCO_SGD) { err = "unknown update rule (algo)"; return DS_EINVAL; }
+        if (c.kind != DS_COMP_QUANT_MAXABS && c.kind != DS_COMP_SIGN_MEANABS) {
+            err = "DCD-PSGD and CHOCO-SGD are built for DS_COMP_QUANT_MAXABS and DS_COMP_SIGN_MEANABS only"; return DS_EINVAL;
+        }
+    }
+    if (cfg->reserved != 0) { err = "reserved must be 0"; return DS_EINVAL; }
     if (warn && cfg->eta > 0.5f) *warn = "warning: eta > 1/2, outside the range of the paper's Theorem 1 (W_eff may not be PSD)";
     return DS_OK;
 }

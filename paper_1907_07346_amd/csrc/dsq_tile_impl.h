@@ -204,9 +204,18 @@ struct Tile {
     }
 
     // ---- lines 6-7 for blocks of 64 or 128 columns: G = B/4 lanes hold one block of a sweep --------
-    template <bool FULL>
+    // What a row keeps of an element after C[v] is known.  MODE 0, Algorithm 1 line 6: the residual v - C[v].
+    // MODE 1 and 2 serve the comparison updates (dsq_compare_impl.h): `base` + C[v], where base is the worker's
+    // public copy (MODE 1, the new copy also goes to LDS as fp32 for the gossip phase) or its model (MODE 2).
+    template <int MODE>
+    static __device__ __forceinline__ float kept(float vc, float cv, float base) {
+        if constexpr (MODE == 0) return vc - cv;                     // line 6: delta = v - C[v]
+        else return base + cv;
+    }
+
+    template <bool FULL, int MODE = 0>
     static __device__ __forceinline__ void compress_sub_blocks(const TileArgs& a, int i, int li, uint64_t col0, int lane, const float4 (&v)[SW],
-                                                               uint8_t* msg_row, uint8_t* lds_row, float* lds_units, float* dout) {
+                                                               const float4 (&base)[SW], uint8_t* msg_row, uint8_t* lds_row, float* lds_units, float* dout) {
         const int grp = lane / G, in_blk = lane % G;                  // block of the sweep, lane-slot inside the block
         [[maybe_unused]] uint32_t t_lo = 0;
         if constexpr (KIND == DS_COMP_QUANT_MAXABS) t_lo = (uint32_t)*a.t_ptr;
@@ -225,7 +234,7 @@ struct Tile {
                 const float unit = scale / (float)L;
                 const float inv = (scale > 0.f) ? hl / scale : 0.f;
                 if (in_blk == 0) {
-                    lds_units[li * BPT + s * BPS + grp] = unit;
+                    if constexpr (MODE == 0) lds_units[li * BPT + s * BPS + grp] = unit;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
                 uint32_t rnd[4];
@@ -247,18 +256,19 @@ struct Tile {
                     float cv = (float)(2 * q - L) * unit;
                     if (!FULL && !(j + c < a.N)) { q = 0; cv = 0.f; }
                     codes |= (uint32_t)q << (BITS * c);
-                    set_comp(dnew, c, vc - cv);                      // line 6: delta = v - C[v]
+                    set_comp(dnew, c, kept<MODE>(vc, cv, comp(base[s], c)));
                 }
                 st4(dout + s * kSweep, dnew);
                 using lane_t = typename CT::lane_t;
-                reinterpret_cast<lane_t*>(lds_row)[s * kWave + lane] = (lane_t)codes;
+                if constexpr (MODE == 0) reinterpret_cast<lane_t*>(lds_row)[s * kWave + lane] = (lane_t)codes;
+                if constexpr (MODE == 1) reinterpret_cast<float4*>(lds_row)[s * kWave + lane] = dnew;
                 const uint32_t word = (uint32_t)in_blk * (uint32_t)sizeof(lane_t) / 4u;
                 if (FULL || word < nwords) reinterpret_cast<lane_t*>(msg_blk + 4)[in_blk] = (lane_t)codes;
             } else if constexpr (KIND == DS_COMP_SIGN_MEANABS) {
                 const float sum = group_sum_tree<G>((fabsf(v[s].x) + fabsf(v[s].y)) + (fabsf(v[s].z) + fabsf(v[s].w)));
                 const float scale = block_live ? sum / (float)m : 0.f;
                 if (in_blk == 0) {
-                    lds_units[li * BPT + s * BPS + grp] = scale;
+                    if constexpr (MODE == 0) lds_units[li * BPT + s * BPS + grp] = scale;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
                 uint32_t nib = 0;
@@ -270,15 +280,16 @@ struct Tile {
                     float cv = neg ? -scale : scale;
                     if (!FULL && !(j + c < a.N)) { neg = 0; cv = 0.f; }
                     nib |= neg << c;
-                    set_comp(dnew, c, vc - cv);
+                    set_comp(dnew, c, kept<MODE>(vc, cv, comp(base[s], c)));
                 }
                 st4(dout + s * kSweep, dnew);
+                if constexpr (MODE == 1) reinterpret_cast<float4*>(lds_row)[s * kWave + lane] = dnew;
                 uint32_t word = nib << (4 * (lane & 7));              // 8 lanes share one 32-bit word
                 word |= __shfl_xor(word, 1);
                 word |= __shfl_xor(word, 2);
                 word |= __shfl_xor(word, 4);
                 if ((lane & 7) == 0) {
-                    reinterpret_cast<uint32_t*>(lds_row)[s * 8 + (lane >> 3)] = word;
+                    if constexpr (MODE == 0) reinterpret_cast<uint32_t*>(lds_row)[s * 8 + (lane >> 3)] = word;
                     const uint32_t widx = (uint32_t)in_blk >> 3;
                     if (FULL || widx < nwords) reinterpret_cast<uint32_t*>(msg_blk + 4)[widx] = word;
                 }
@@ -322,12 +333,21 @@ struct Tile {
             xh[s].w = fmaf(-a.gamma, gv[s].w, xv[s].w);  v[s].w = xh[s].w + dv[s].w;
         }
 
-        uint8_t* msg_row = a.msg + (uint64_t)i * a.msg_row_bytes;
         uint8_t* lds_row = lds_codes + (size_t)li * ROW_CODE_BYTES;
         float* dout = a.delta + (uint64_t)i * a.ld + col0 + 4 * lane;
+        encode_row<FULL, 0>(a, i, li, col0, lane, v, v, lds_row, lds_units, dout);
+    }
 
+    // ---- line 6 and line 7 for one row of a tile whose v is in registers: scales, codes, the packed message,
+    //      and what the row keeps (see `kept`) stored through dout.  lds_row: the row's slot of the LDS exchange.
+    template <bool FULL, int MODE>
+    static __device__ __forceinline__ void encode_row(const TileArgs& a, int i, int li, uint64_t col0, int lane, const float4 (&v)[SW],
+                                                      const float4 (&base)[SW], uint8_t* lds_row, float* lds_units, float* dout) {
+        static_assert(MODE == 0 || KIND == DS_COMP_QUANT_MAXABS || KIND == DS_COMP_SIGN_MEANABS,
+                      "the comparison updates are built for the block compressors");
+        uint8_t* msg_row = a.msg + (uint64_t)i * a.msg_row_bytes;
         if constexpr (SUB) {
-            compress_sub_blocks<FULL>(a, i, li, col0, lane, v, msg_row, lds_row, lds_units, dout);
+            compress_sub_blocks<FULL, MODE>(a, i, li, col0, lane, v, base, msg_row, lds_row, lds_units, dout);
             return;
         }
 #pragma unroll
@@ -349,7 +369,7 @@ struct Tile {
                 const float unit = scale / (float)L;
                 const float inv = (scale > 0.f) ? hl / scale : 0.f;
                 if (lane == 0) {
-                    lds_units[li * BPT + b] = unit;
+                    if constexpr (MODE == 0) lds_units[li * BPT + b] = unit;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
 #pragma unroll
@@ -374,11 +394,12 @@ struct Tile {
                         float cv = (float)(2 * q - L) * unit;
                         if (!FULL && !(j + c < a.N)) { q = 0; cv = 0.f; }
                         codes |= (uint32_t)q << (BITS * c);
-                        set_comp(dnew, c, vc - cv);                  // line 6: delta = v - C[v]
+                        set_comp(dnew, c, kept<MODE>(vc, cv, comp(base[s], c)));
                     }
                     st4(dout + s * kSweep, dnew);
                     using lane_t = typename CT::lane_t;
-                    reinterpret_cast<lane_t*>(lds_row)[s * kWave + lane] = (lane_t)codes;
+                    if constexpr (MODE == 0) reinterpret_cast<lane_t*>(lds_row)[s * kWave + lane] = (lane_t)codes;
+                    if constexpr (MODE == 1) reinterpret_cast<float4*>(lds_row)[s * kWave + lane] = dnew;
                     const int in_blk = (s - b * SPB) * kWave + lane;  // lane-slot inside the block
                     const uint32_t word = (uint32_t)in_blk * (uint32_t)sizeof(lane_t) / 4u;
                     if (FULL || word < nwords)
@@ -398,7 +419,7 @@ struct Tile {
                     for (int s = 0; s + w < SPB; s += 2 * w) part[s] = part[s] + part[s + w];
                 const float scale = block_live ? part[0] / (float)m : 0.f;
                 if (lane == 0) {
-                    lds_units[li * BPT + b] = scale;
+                    if constexpr (MODE == 0) lds_units[li * BPT + b] = scale;
                     if (block_live) *reinterpret_cast<float*>(msg_blk) = scale;
                 }
 #pragma unroll
@@ -413,15 +434,16 @@ struct Tile {
                         float cv = neg ? -scale : scale;
                         if (!FULL && !(j + c < a.N)) { neg = 0; cv = 0.f; }
                         nib |= neg << c;
-                        set_comp(dnew, c, vc - cv);
+                        set_comp(dnew, c, kept<MODE>(vc, cv, comp(base[s], c)));
                     }
                     st4(dout + s * kSweep, dnew);
+                    if constexpr (MODE == 1) reinterpret_cast<float4*>(lds_row)[s * kWave + lane] = dnew;
                     uint32_t word = nib << (4 * (lane & 7));          // 8 lanes share one 32-bit word
                     word |= __shfl_xor(word, 1);
                     word |= __shfl_xor(word, 2);
                     word |= __shfl_xor(word, 4);
                     if ((lane & 7) == 0) {
-                        reinterpret_cast<uint32_t*>(lds_row)[s * 8 + (lane >> 3)] = word;
+                        if constexpr (MODE == 0) reinterpret_cast<uint32_t*>(lds_row)[s * 8 + (lane >> 3)] = word;
                         const uint32_t widx = (uint32_t)(s - b * SPB) * 8u + (uint32_t)(lane >> 3);
                         if (FULL || widx < nwords) reinterpret_cast<uint32_t*>(msg_blk + 4)[widx] = word;
                     }

@@ -12,6 +12,11 @@ bool stream_plan_quant4(int block, TilePlan& plan);
 bool stream_plan_quant2(int block, TilePlan& plan);
 bool stream_plan_quant8(int block, TilePlan& plan);
 bool stream_plan_sign(int block, TilePlan& plan);
+// the comparison updates (dsq_compare_*.hip)
+bool compare_plans_quant4(int algo, int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
+bool compare_plans_quant2(int algo, int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
+bool compare_plans_quant8(int algo, int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
+bool compare_plans_sign(int algo, int block, int n, int nnz, std::vector<TilePlan>& plans, std::string& err);
 
 static_assert(kKeepGroup == 16, "the tile kernel finds a sweep's group with a shift by 4");
 
@@ -24,6 +29,7 @@ void launch_keep_offsets(const TileArgs& a, uint32_t* local_off, uint32_t* group
 }
 
 bool stream_plan(const ds_config& cfg, TilePlan& plan) {
+    if (cfg.algo != DS_ALGO_DEEPSQUEEZE) return false;     // the comparison updates exchange fp32 rows through LDS
     if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 4) return stream_plan_quant4(cfg.comp.block, plan);
     if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 2) return stream_plan_quant2(cfg.comp.block, plan);
     if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 8) return stream_plan_quant8(cfg.comp.block, plan);
@@ -33,6 +39,14 @@ bool stream_plan(const ds_config& cfg, TilePlan& plan) {
 }
 
 bool choose_tile_plans(const ds_config& cfg, int nnz, std::vector<TilePlan>& plan, std::string& err) {
+    if (cfg.algo != DS_ALGO_DEEPSQUEEZE) {
+        if (cfg.comp.kind == DS_COMP_SIGN_MEANABS) return compare_plans_sign(cfg.algo, cfg.comp.block, cfg.n, nnz, plan, err);
+        if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 4) return compare_plans_quant4(cfg.algo, cfg.comp.block, cfg.n, nnz, plan, err);
+        if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 2) return compare_plans_quant2(cfg.algo, cfg.comp.block, cfg.n, nnz, plan, err);
+        if (cfg.comp.kind == DS_COMP_QUANT_MAXABS && cfg.comp.bits == 8) return compare_plans_quant8(cfg.algo, cfg.comp.block, cfg.n, nnz, plan, err);
+        err = "no comparison kernel for this compressor";
+        return false;
+    }
     switch (cfg.comp.kind) {
         case DS_COMP_QUANT_MAXABS:
             if (cfg.comp.bits == 4) return tile_plans_quant4(cfg.comp.block, cfg.n, nnz, plan, err);

@@ -19,6 +19,7 @@ import numpy as np
 
 KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE = 0, 1, 2, 3, 4, 5
 TOPO_RING, TOPO_TORUS2D, TOPO_CSR = 0, 1, 2
+ALGO_DEEPSQUEEZE, ALGO_DCD_PSGD, ALGO_CHOCO_SGD = 0, 1, 2       # ds_algorithm
 
 _TAG_CENTRE, _TAG_NOISE = 0x43454E54, 0x47524144   # 'CENT', 'GRAD'
 
@@ -40,6 +41,7 @@ class Config:
     k: int = 0
     torus: Tuple[int, int] = (0, 0)
     seed: int = 0
+    algo: int = 0             # 0 DeepSqueeze, 1 DCD-PSGD, 2 CHOCO-SGD (ds_algorithm)
 
     def scaled(self, N: int, steps: Optional[int] = None) -> "Config":
         """Same workload at another vector length (k follows as 1 % of N for top-k)."""

@@ -34,7 +34,7 @@ def dense_W(w: wl.Config):
 
 def oracle_state(w: wl.Config, W=None, **kw):
     return oracle.OracleState(n=w.n, N=w.N, W=dense_W(w) if W is None else W, kind=w.kind, gamma=w.gamma,
-                              eta=w.eta, bits=w.bits, block=w.block, k=w.k, seed=w.seed, **kw)
+                              eta=w.eta, bits=w.bits, block=w.block, k=w.k, seed=w.seed, algo=w.algo, **kw)
 
 
 def assert_close(name, got, want):
@@ -65,7 +65,7 @@ def lock_step(w: wl.Config, steps, W=None, start="random", pitch=None, bitwise=T
     """Each step: both sides start from the oracle's state, take one step, everything is compared."""
     if csr is not None:
         cfg, keep = b.make_config(w.n, w.N, wl.TOPO_CSR, w.kind, w.gamma, w.eta, bits=w.bits, block=w.block,
-                                  k=w.k, seed=w.seed, W_csr=csr)
+                                  k=w.k, seed=w.seed, W_csr=csr, algo=w.algo)
         ds = b.DeepSqueeze(cfg, keep, plan)
     else:
         ds = b.DeepSqueeze.from_workload(w, plan)
