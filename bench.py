@@ -35,7 +35,9 @@ DEFAULT_SET = [1, 2, 3, 4, 0]
 
 
 def algorithmic_bytes_per_param(w) -> float:
-    """Bytes the method must move per worker-parameter: read x, g, delta; write x, delta; write the message."""
+    """Bytes the method must move per worker-parameter: read x, g, delta; write x, delta; write the message.
+    CHOCO-SGD moves the same arrays (its public copies in place of delta); DCD-PSGD has no second state array:
+    read x, g; write x; write the message."""
     from paper_1907_07346_amd import workloads as wl
     if w.kind == wl.KIND_QUANT_MAXABS:
         msg = w.bits / 8 + 4 / w.block
@@ -49,7 +51,7 @@ def algorithmic_bytes_per_param(w) -> float:
         msg = 4 * w.k / w.N
     else:
         msg = 4.0
-    return 20.0 + msg
+    return (12.0 if w.algo == wl.ALGO_DCD_PSGD else 20.0) + msg
 
 
 def cpu_model() -> str:
@@ -181,6 +183,7 @@ def run_config(torch, b, wl, w, K, Wm, hip_graph, copy_gbs, mix_gbs, traffic_tab
     entry = {
         "workload": w.name, "n": w.n, "N": w.N, "plan": ds.ds_plan_name(), "gradient_buffers": nbuf,
         "launch": "hip-graph" if graph is not None else "eager",
+        "update_rule": {0: "deepsqueeze", 1: "dcd-psgd", 2: "choco-sgd"}[w.algo],
         "compressor": {1: f"quant{w.bits}b/B{w.block}", 2: f"sign/B{w.block}", 3: f"top-{w.k}", 0: "identity",
                        4: f"l2norm{w.bits}b", 5: f"rand-{w.k}"}[w.kind],
         "ms_per_step": wall * 1e3 / K, "value": w.worker_params * K / wall,

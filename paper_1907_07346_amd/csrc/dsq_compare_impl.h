@@ -255,9 +255,12 @@ void launch_compare(const TileArgs& a, int rpw_runtime, hipStream_t stream) {
 
 template <int KIND, int BITS, int B, int SW, int NW, int RPW, int ALGO>
 void add_compare_plan(int n, const char* name, std::vector<TilePlan>& plans) {
-    // registers: CHOCO-SGD holds xh of its rows across the barrier, DCD-PSGD x and xh
+    // registers: CHOCO-SGD holds xh of its rows across the barrier, DCD-PSGD x and xh (float4 each per sweep).
+    // A 16-wave workgroup caps a wave at 128 VGPRs, an 8-wave one at 256; DCD-PSGD has nothing else to hold
+    // while its loads are in flight, so its 8-wave shapes may keep up to 32 float4.
     constexpr int held = (ALGO == kAlgoDcd ? 2 : 1) * RPW * SW;
-    if constexpr (held <= (NW > 8 ? 8 : 16) && (NW <= 8 || SW <= 4)) {   // else the 128-VGPR cap of a 16-wave group spills
+    constexpr int room = NW > 8 ? 8 : (ALGO == kAlgoDcd && SW <= 4 ? 32 : 16);   // 8 sweeps: the encoder's own registers grow too
+    if constexpr (held <= room && (NW <= 8 || SW <= 4)) {
         if (n > NW * RPW) return;
         if (RPW > 1 && n <= NW * (RPW / 2)) return;
         TilePlan p;

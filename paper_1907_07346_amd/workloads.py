@@ -75,7 +75,9 @@ def extra_configs():
     """Workloads beyond the benchmark's list: the compression of the paper's own experiments (b-bit codes plus
     the tensor's Euclidean norm) on its setting (8 workers on a ring, a vector of ResNet-20 size, 4 bits) and
     at a bandwidth-bound size (the shape of configuration 1, 2 bits); random sparsification at the shape of
-    configuration 4 (1 % kept)."""
+    configuration 4 (1 % kept); the two comparison updates (DCD-PSGD, CHOCO-SGD) at the shapes and compressors of
+    configurations 1 and 3."""
+    c = configs()
     return [
         Config("x5_ring8_l2norm4b_resnet20", n=8, N=272_474, topo=TOPO_RING, kind=KIND_QUANT_L2NORM, bits=4,
                gamma=0.1, eta=0.5, steps=100, grad="normal", grad_scale=0.01),
@@ -83,6 +85,10 @@ def extra_configs():
                gamma=0.05, eta=0.3, steps=100, grad="normal", grad_scale=0.01),
         Config("x7_ring32_rand1pct_resnet50", n=32, N=25_557_032, topo=TOPO_RING, kind=KIND_RAND_SPARSE,
                k=25_557_032 // 100, gamma=0.05, eta=0.2, steps=50, grad="normal", grad_scale=1e-3),
+        replace(c[1], name="x8_dcd_ring16_q2b1024_resnet18", algo=ALGO_DCD_PSGD),
+        replace(c[1], name="x9_choco_ring16_q2b1024_resnet18", algo=ALGO_CHOCO_SGD),
+        replace(c[3], name="x10_dcd_torus8x8_q4b512", algo=ALGO_DCD_PSGD),
+        replace(c[3], name="x11_choco_torus8x8_q4b512", algo=ALGO_CHOCO_SGD),
     ]
 
 
