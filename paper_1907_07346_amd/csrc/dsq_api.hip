@@ -86,6 +86,7 @@ dsq::L2Args l2_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     a.x = h->x; a.delta = h->delta; a.g = g_dev; a.msg = h->msg;
     a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
     a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.msg_row_bytes = h->msg_row_bytes; a.n = h->cfg.n;
+    a.msg_half = h->msg_half;
     a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
     return a;
 }
@@ -436,7 +437,8 @@ ds_status ds_init_ex(const ds_config* cfg, const ds_plan_request* plan, char* er
     if (cfg->comp.kind == DS_COMP_TOPK) {
         h->plan_name = "topk/radix-select";
     } else if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {
-        h->plan_name = "l2norm/two-pass";
+        h->plan_name = "l2norm/speculative-codes";
+        h->msg_half = (uint64_t)cfg->n * h->msg_row_bytes;     // the first pass writes codes while the old ones are still read
     } else {
         // the row-streaming variant of the block compressors on request; it is also what serves a number of
         // workers whose codes do not fit in LDS
@@ -636,8 +638,8 @@ ds_status ds_write_state(ds_handle* h, const float* x_host, const float* delta_h
     return DS_OK;
 }
 
-// Row-streaming variant: step t writes message buffer t & 1 and leaves that number in cell 4 of the step cells
-// (the counter itself may have been set from outside since).  The caller has synchronised.
+// Plans with two message buffers (row-streaming block kernels, norm-rescaled codes): a step leaves the number of
+// the buffer it wrote in cell 4 of the step cells.  The caller has synchronised.
 static ds_status last_message_buffer(ds_handle* h, uint8_t** out) {
     *out = h->msg;
     if (!h->msg_half) return DS_OK;
@@ -711,8 +713,9 @@ ds_status ds_diagnostics(ds_handle* h, double* out4) {
 ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count) {
     if (!h || !count) return DS_EINVAL;
     *count = 0;
-    if (!h->topk) return DS_OK;
+    if (!h->topk && !h->l2q) return DS_OK;
     if (!h->stepped) return fail(h, DS_ESTATE, "no step has been taken yet");
+    if (h->l2q) return dsq::l2q_speculated_rows(h->l2q, h->last_stream, count);
     return dsq::topk_candidate_rows(h->topk, h->last_stream, count);
 }
 

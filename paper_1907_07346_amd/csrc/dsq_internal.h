@@ -135,9 +135,12 @@ struct L2Args {
     const int32_t* col;
     const float* coef;
     uint64_t ld, g_ld, N, msg_row_bytes;
+    uint64_t msg_half;         // msg holds two buffers of this many bytes; a step writes the one the last step did not
     int n;
     float gamma, eta;
-    unsigned long long* t_ptr;  // step counter in device memory (advanced once per step)
+    unsigned long long* t_ptr;  // step cells in device memory: [0] the step counter (advanced once per step), [4] the
+                                // message buffer (0 / 1) the last completed step wrote, [5] rows finished in the
+                                // step's last kernel (zero between launches)
 };
 
 struct L2State;                // device scratch: per-row scales, per-chunk partial reductions
@@ -148,6 +151,8 @@ ds_status l2q_step(L2State* s, const L2Args& a, hipStream_t stream);
 // l2q_flush applies them now (no-op if nothing is pending).  Call before the state is read or replaced, with
 // the buffers, mixing matrix and eta the last step ran with (a.g is not used).
 ds_status l2q_flush(L2State* s, const L2Args& a, hipStream_t stream);
+// Number of rows whose last step kept the codes its first pass wrote speculatively (no second dense pass).
+ds_status l2q_speculated_rows(L2State* s, hipStream_t stream, uint32_t* count);
 
 // Device twin of the deterministic host gradient generator (harness aid).
 ds_status launch_workload_gradient(const ds_workload& w, uint64_t t, const float* x, uint64_t x_ld, float* g, uint64_t g_ld,

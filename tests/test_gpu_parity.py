@@ -653,6 +653,44 @@ def test_l2norm_free_run_messages_every_step(bits):
     ds.ds_destroy()
 
 
+@pytest.mark.parametrize("bits,grad", [(2, "normal"), (2, "quadratic"), (4, "normal"), (8, "normal")])
+def test_l2norm_speculative_codes_steady_state(bits, grad):
+    """The norm-rescaled path writes codes from its first pass under a guessed band for the row's range and settles
+    the undecided elements once the range is known (or falls back to the exact second pass).  A free run long enough
+    for the guesses to settle: messages after every step, and -- at 2 bits, where few elements sit next to a level
+    boundary -- every row on the speculative path in the later steps.  Then the range is moved from outside (the
+    state scaled by 3), which the band cannot hold: the next step must take the exact pass and still agree."""
+    w = small(wl.KIND_QUANT_L2NORM, 8, 4096 * 40 + 1001, bits=bits, grad=grad, gamma=0.05, eta=0.3)
+    ds = b.DeepSqueeze.from_workload(w)
+    st = oracle_state(w)
+    c = wl.centres(w) if grad == "quadratic" else None
+    fast = []
+    for t in range(16):
+        g = wl.gradient(w, t, st.x, c)
+        ds.ds_step(upload(g))
+        _, msg = oracle.step(st, g, want_cv=False)
+        assert np.array_equal(ds.ds_read_messages(), msg), f"step {t}: messages differ"
+        fast.append(ds.ds_topk_candidate_rows())
+    say(w.name, "rows on the speculative path per step:", fast)
+    if bits == 2 and grad == "normal":
+        assert sum(fast[-6:]) >= 5 * w.n, fast          # a row's maximum may leave its band now and then
+    x, d = ds.ds_read_state()
+    assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+    # the range jumps: no band holds it
+    ds.ds_write_state(3.0 * x, 3.0 * d, st.t)
+    st.x, st.delta = 3.0 * st.x, 3.0 * st.delta
+    for t in range(16, 19):
+        g = wl.gradient(w, t, st.x, c)
+        ds.ds_step(upload(g))
+        _, msg = oracle.step(st, g, want_cv=False)
+        assert np.array_equal(ds.ds_read_messages(), msg), f"step {t} (after the jump): messages differ"
+        if t == 16:
+            assert ds.ds_topk_candidate_rows() == 0
+    x, d = ds.ds_read_state()
+    assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+    ds.ds_destroy()
+
+
 def test_l2norm_worked_example_and_zero_rows_on_gpu(golden_dir):
     rec = {l.split()[0]: l.split()[1:] for l in open(os.path.join(golden_dir, "l2norm_2bit_micro.txt"))
            if l[0] != "#"}
