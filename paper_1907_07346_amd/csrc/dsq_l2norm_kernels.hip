@@ -401,7 +401,7 @@ __global__ void __launch_bounds__(LQ_ROW_THREADS) l2q_row_unit(L2Args a, L2Scrat
         const bool tried = r.s_hi > 0.f;
         if (tried && r.overflowed) { r.streak = r.streak < 6u ? r.streak + 1u : 6u; r.wait = 1u << r.streak; }
         else if (r.mode) r.streak = 0u;
-        const float rel = (r.s_prev > 0.f) ? fabsf(r.s - r.s_prev) / r.s_prev : 1.f;
+        const float rel = (r.s_prev > 0.f) ? fabsf(r.s - r.s_prev) / r.s_prev : 0.2f;      // first step: wait for a second look
         r.drift = fmaxf(rel, 0.7f * r.drift);
         r.s_prev = r.s;
         const float h = 1.5f * r.drift + 0.02f;
@@ -484,8 +484,8 @@ ds_status l2q_create(const ds_config& cfg, uint64_t ld, L2State** out, std::stri
               hipMalloc(&s.ucount, n * nc * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.uslot, n * nc * LQ_UCAP * sizeof(uint2)) == hipSuccess &&
               hipMalloc(&s.row_flags, n * sizeof(uint32_t)) == hipSuccess;
-    // rows start with no guess (s_hi = 0) and drift = 0: the first step is exact, the second has no s_prev
-    // (relative movement counted as 1), so speculation starts once s has been seen to settle
+    // rows start with no guess (s_hi = 0): the first two steps are exact (the first has no s_prev and counts as a
+    // movement of 20 %, too wide a band), speculation starts with the third if s moved little between them
     ok = ok && hipMemset(s.rows, 0, n * sizeof(L2Row)) == hipSuccess &&
          hipMemset(s.ucount, 0, n * nc * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.row_flags, 0, n * sizeof(uint32_t)) == hipSuccess &&
