@@ -213,20 +213,54 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
             for (int q = threadIdx.x; q < TK_CHUNK; q += TK_THREADS) acc[q] = 0.f;
             for (int q = threadIdx.x; q < TK_CHUNK / 32; q += TK_THREADS) own[q] = 0u;
             __syncthreads();
-            for (int e = e0; e < e1; ++e) {
-                const int nb = a.col[e];
-                const float w = a.coef[e];
-                const uint32_t* off = s.out_off + (size_t)nb * (s.nchunks + 1) + chunk;
-                const uint2* in = reinterpret_cast<const uint2*>(a.msg + (uint64_t)nb * a.k * 8);
-                for (uint32_t p = off[0] + threadIdx.x; p < off[1]; p += TK_THREADS) {
-                    const uint2 pr = in[p];
-                    const uint32_t q = (uint32_t)((uint64_t)pr.x - c0);
-                    if (q < (uint32_t)TK_CHUNK) {
-                        acc[q] = fmaf(w, __uint_as_float(pr.y), acc[q]);
-                        if (nb == row) atomicOr(&own[q >> 5], 1u << (q & 31));
+            // Neighbours in ascending order, four at a time: their pair loads go out together (memory operations
+            // complete in issue order, so a load issued only after the previous neighbour was accumulated would
+            // show its whole latency with nothing else of this workgroup in flight), then they are accumulated one
+            // after the other.  A neighbour with more than one pair per thread in this chunk takes the loop below.
+            constexpr int EB = 4;
+            for (int eb = e0; eb < e1; eb += EB) {
+                uint2 pr[EB];
+                bool have[EB], wide[EB];
+#pragma unroll
+                for (int u = 0; u < EB; ++u) {
+                    have[u] = wide[u] = false;
+                    if (eb + u < e1) {
+                        const int nb = a.col[eb + u];
+                        const uint32_t* off = s.out_off + (size_t)nb * (s.nchunks + 1) + chunk;
+                        const uint32_t p0 = off[0], p1 = off[1];
+                        wide[u] = p1 - p0 > (uint32_t)TK_THREADS;                    // uniform
+                        if (!wide[u] && p0 + threadIdx.x < p1) {
+                            pr[u] = reinterpret_cast<const uint2*>(a.msg + (uint64_t)nb * a.k * 8)[p0 + threadIdx.x];
+                            have[u] = true;
+                        }
                     }
                 }
-                __syncthreads();
+#pragma unroll
+                for (int u = 0; u < EB; ++u) {
+                    if (eb + u < e1) {                                               // uniform
+                        const int nb = a.col[eb + u];
+                        const float w = a.coef[eb + u];
+                        if (wide[u]) {
+                            const uint32_t* off = s.out_off + (size_t)nb * (s.nchunks + 1) + chunk;
+                            const uint2* in = reinterpret_cast<const uint2*>(a.msg + (uint64_t)nb * a.k * 8);
+                            for (uint32_t p = off[0] + threadIdx.x; p < off[1]; p += TK_THREADS) {
+                                const uint2 one = in[p];
+                                const uint32_t q = (uint32_t)((uint64_t)one.x - c0);
+                                if (q < (uint32_t)TK_CHUNK) {
+                                    acc[q] = fmaf(w, __uint_as_float(one.y), acc[q]);
+                                    if (nb == row) atomicOr(&own[q >> 5], 1u << (q & 31));
+                                }
+                            }
+                        } else if (have[u]) {
+                            const uint32_t q = (uint32_t)((uint64_t)pr[u].x - c0);
+                            if (q < (uint32_t)TK_CHUNK) {
+                                acc[q] = fmaf(w, __uint_as_float(pr[u].y), acc[q]);
+                                if (nb == row) atomicOr(&own[q >> 5], 1u << (q & 31));
+                            }
+                        }
+                        __syncthreads();
+                    }
+                }
             }
         }
     }
