@@ -1,5 +1,6 @@
 // Host-only part of libdsq: configuration checks, the mixing matrix W of the built-in
 // topologies, and message sizes.  No GPU call in this file.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -135,11 +136,14 @@ ds_status build_graph(const ds_config* cfg, Graph& g, std::string& err) {
     return DS_OK;
 }
 
+// Values a worker's random-sparsification message has room for: the expected count k, eight standard deviations
+// of the kept count on top (its variance is below k), and a small constant for tiny k; never more than N.
 uint64_t rand_sparse_capacity(uint64_t N, uint64_t k) {
-    uint64_t root = 0;
-    while (root * root < k) ++root;                       // ceil(sqrt(k)), k < 2^32
-    const uint64_t cap = k + 8 * root + 64;               // 8 standard deviations of the kept count and some
-    return cap < N ? cap : N;
+    uint64_t r = (uint64_t)std::sqrt((double)k);          // near floor(sqrt k); the two loops make it exact
+    while (r * r > k) --r;
+    while ((r + 1) * (r + 1) <= k) ++r;
+    const uint64_t sigma_bound = (r * r == k) ? r : r + 1; // ceil(sqrt k)
+    return std::min<uint64_t>(N, k + 8 * sigma_bound + 64);
 }
 
 uint64_t message_row_bytes(const ds_config* cfg) {

@@ -127,6 +127,22 @@ def test_message_sizes():
     assert b.ds_message_bytes(c) == 3 * (4 + 500)
     c, _ = b.make_config(3, 17, wl.TOPO_RING, wl.KIND_QUANT_L2NORM, 0.1, 0.5, bits=2)
     assert b.ds_message_bytes(c) == 3 * (4 + 8)
+    # random sparsification: room for min(N, k + 8 ceil(sqrt k) + 64) values, worked out here with integer square
+    # roots (the library and the oracle each have their own routine), at perfect squares, their neighbours and
+    # values whose double square root rounds the wrong way
+    import math
+    for k in [1, 2, 3, 4, 15, 16, 17, 99, 100, 101, 255_570, 2 ** 26, 2 ** 26 + 1, (2 ** 16 - 1) ** 2, (2 ** 16 - 1) ** 2 + 1,
+              4_294_836_225, 4_294_836_226, 2 ** 32 - 17]:
+        root = math.isqrt(k)
+        root += root * root < k
+        for N in (k, k + 1, k + 8 * root + 63, k + 8 * root + 64, k + 8 * root + 65, 2 ** 32 - 17):
+            if N < k or N > 2 ** 32 - 17:
+                continue
+            c, _ = b.make_config(1, N, wl.TOPO_RING, wl.KIND_RAND_SPARSE, 0.1, 0.5, k=k)
+            c.n = 3
+            want = min(N, k + 8 * root + 64)
+            assert b.ds_message_bytes(c) == 3 * (4 + 4 * want), (k, N)
+            assert oracle.rand_sparse_capacity(N, k) == want, (k, N)
 
 
 def test_workload_generators_are_seeded_and_shaped():
