@@ -1,4 +1,4 @@
-"""Free run of DeepSqueeze on a synthetic quadratic, entirely on the GPU.
+"""Free run of DeepSqueeze (and of the update rules it is compared with) on a synthetic quadratic, entirely on the GPU.
 
 n workers on a ring minimise  f(x) = 1/n sum_i 1/2 |x - c_i|^2  (minimiser: the mean of the c_i) from noisy
 gradients g_i = (x_i - c_i) + sigma xi.  The gradients are drawn on the device by ds_workload_gradient from the
@@ -27,8 +27,8 @@ class _Borrowed:
                                          "strides": None}
 
 
-def run(kind, n, N, steps, gamma, eta, sigma, report, **comp):
-    cfg, keep = b.make_config(n, N, wl.TOPO_RING, kind, gamma, eta, seed=1, **comp)
+def run(kind, n, N, steps, gamma, eta, sigma, report, algo=wl.ALGO_DEEPSQUEEZE, **comp):
+    cfg, keep = b.make_config(n, N, wl.TOPO_RING, kind, gamma, eta, seed=1, algo=algo, **comp)
     ds = b.DeepSqueeze(cfg, keep)
     c = torch.from_numpy(detgen.centres(n, N, seed=1)).cuda()
     opt = c.mean(0)
@@ -82,6 +82,20 @@ def main():
         ratio = n * N * 4 / nbytes
         line = "  ".join(f"t={t}: {gap:.2e} {cons:.2e} {dsq:.2e}" for t, gap, cons, dsq in rows)
         print(f"{name:24s} eta={eta:.1f} msg {ratio:6.1f}x smaller | {line}", flush=True)
+    # The update rules side by side under the same compressor and rates (the setting of the paper's convergence
+    # figure: the same bits for every method).  Third column: the carried error for DeepSqueeze, the squared
+    # norm of the public copies for CHOCO-SGD, nothing for DCD-PSGD (it has no second state array).
+    rules = [("DeepSqueeze", wl.ALGO_DEEPSQUEEZE), ("CHOCO-SGD", wl.ALGO_CHOCO_SGD), ("DCD-PSGD", wl.ALGO_DCD_PSGD)]
+    for cname, kind, eta, comp in (("4-bit blocks of 512", wl.KIND_QUANT_MAXABS, 0.4, dict(bits=4, block=512)),
+                                   ("2-bit blocks of 512", wl.KIND_QUANT_MAXABS, 0.4, dict(bits=2, block=512)),
+                                   ("sign, blocks of 256", wl.KIND_SIGN_MEANABS, 0.4, dict(block=256))):
+        print(f"update rules under {cname}, eta = {eta}:")
+        rows, _ = run(wl.KIND_IDENTITY, n, N, args.steps, args.gamma, eta, args.sigma, report)
+        print(f"  {'D-PSGD (no compression)':24s} | " + "  ".join(f"t={t}: {gap:.2e} {cons:.2e}" for t, gap, cons, _ in rows), flush=True)
+        for rname, algo in rules:
+            rows, _ = run(kind, n, N, args.steps, args.gamma, eta, args.sigma, report, algo=algo, **comp)
+            line = "  ".join(f"t={t}: {gap:.2e} {cons:.2e} {dsq:.2e}" for t, gap, cons, dsq in rows)
+            print(f"  {rname:24s} | {line}", flush=True)
 
 
 if __name__ == "__main__":
