@@ -23,6 +23,12 @@ int dso_step_f64(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, c
 int dso_step_window_f32(int n, uint64_t N, uint64_t col0, const int32_t* rowptr, const int32_t* col, const float* wval, int kind, int bits,
                         uint64_t block, float gamma, float eta, uint64_t seed, uint64_t t, float* x, float* delta, const float* g,
                         uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes);
+int dso_compare_step_f32(int algo, int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const float* wval, int kind, int bits,
+                         uint64_t block, uint64_t k, float gamma, float eta, uint64_t seed, uint64_t t, float* x, float* state2,
+                         const float* g, float* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes);
+int dso_compare_step_f64(int algo, int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const double* wval, int kind, int bits,
+                         uint64_t block, uint64_t k, double gamma, double eta, uint64_t seed, uint64_t t, double* x, double* state2,
+                         const double* g, double* cv, uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes);
 }
 
 static int failures = 0;
@@ -159,6 +165,46 @@ static void oracle_case(Step step, int kind, int bits, uint64_t block, uint64_t 
                nullptr, tight.data(), tight.size(), &used) == 2);
 }
 
+// The two comparison updates (DCD-PSGD = 1, CHOCO-SGD = 2): a few steps on a ragged ring, with and without the
+// optional outputs; x moves by exactly C[z] (DCD-PSGD), the public copy by exactly q (CHOCO-SGD).
+template <typename real, typename Step>
+static void comparison_case(Step step, int algo, int kind, int bits, uint64_t block, uint64_t k, int n, uint64_t N) {
+    std::vector<int32_t> rowptr(n + 1), col;
+    std::vector<real> w;
+    for (int i = 0; i < n; ++i) {
+        int nb[3] = {(i + n - 1) % n, i, (i + 1) % n};
+        for (int a = 0; a < 3; ++a)
+            for (int b = a + 1; b < 3; ++b)
+                if (nb[b] < nb[a]) std::swap(nb[a], nb[b]);
+        for (int e = 0; e < 3; ++e) { col.push_back(nb[e]); w.push_back((real)(1.0 / 3.0)); }
+        rowptr[i + 1] = (int32_t)col.size();
+    }
+    std::vector<real> x(n * N, 0), h(n * N, 0), g(n * N), cv(n * N), before(n * N);
+    std::vector<uint8_t> msg(n * N * 8 + 64);
+    uint32_t ctr[4] = {7, 2, 3, 4}, key[2] = {5, 6}, out[4];
+    for (int t = 0; t < 3; ++t) {
+        for (size_t p = 0; p < g.size(); ++p) {
+            if (p % 4 == 0) { ctr[0] = (uint32_t)p; ctr[1] = (uint32_t)t; dso_philox4x32_10(ctr, key, out); }
+            g[p] = (real)((double)out[p % 4] / 4294967296.0 - 0.5);
+        }
+        before = (algo == 1) ? x : h;
+        uint64_t used = 0;
+        const int rc = step(algo, n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, (uint64_t)t,
+                            x.data(), h.data(), g.data(), cv.data(), msg.data(), msg.size(), &used);
+        CHECK(rc == 0 && used > 0 && used <= msg.size());
+        const std::vector<real>& after = (algo == 1) ? x : h;
+        for (size_t p = 0; p < g.size(); ++p) CHECK(after[p] == before[p] + cv[p]);
+    }
+    CHECK(step(algo, n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, 3, x.data(), h.data(), g.data(),
+               nullptr, nullptr, 0, nullptr) == 0);
+    std::vector<uint8_t> tight(3);
+    uint64_t used = 0;
+    CHECK(step(algo, n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, 4, x.data(), h.data(), g.data(),
+               nullptr, tight.data(), tight.size(), &used) == 2);
+    CHECK(step(7, n, N, rowptr.data(), col.data(), w.data(), kind, bits, block, k, (real)0.1, (real)0.4, 9, 4, x.data(), h.data(), g.data(),
+               nullptr, nullptr, 0, nullptr) == 1);
+}
+
 static void oracle_cases() {
     struct K { int kind, bits; uint64_t block, k; };
     const K kinds[] = {{DS_COMP_IDENTITY, 0, 0, 0}, {DS_COMP_QUANT_MAXABS, 2, 64, 0}, {DS_COMP_QUANT_MAXABS, 4, 512, 0}, {DS_COMP_QUANT_MAXABS, 8, 128, 0},
@@ -169,6 +215,10 @@ static void oracle_cases() {
             const uint64_t k = kd.k ? (kd.k < N ? kd.k : N) : 0;
             oracle_case<float>(dso_step_f32, kd.kind, kd.bits, kd.block, k, 3, N);
             oracle_case<double>(dso_step_f64, kd.kind, kd.bits, kd.block, k, 5, N);
+            for (int algo = 1; algo <= 2; ++algo) {
+                comparison_case<float>(dso_compare_step_f32, algo, kd.kind, kd.bits, kd.block, k, 3, N);
+                comparison_case<double>(dso_compare_step_f64, algo, kd.kind, kd.bits, kd.block, k, 4, N);
+            }
         }
     // refused arguments
     int32_t rowptr[] = {0, 1}, col[] = {0};

@@ -8,6 +8,7 @@ expression order, so the tests also report how many elements differ in any bit a
 """
 import os
 import sys
+from dataclasses import replace
 from fractions import Fraction
 
 import numpy as np
@@ -594,7 +595,10 @@ def test_two_handles_interleaved():
 @pytest.mark.parametrize("w", [small(wl.KIND_QUANT_MAXABS, 8, 512 * 9 + 37, bits=4, block=512),
                                small(wl.KIND_TOPK, 8, 30_011, k=300),
                                small(wl.KIND_QUANT_L2NORM, 8, 4096 * 5 + 11, bits=2),
-                               small(wl.KIND_RAND_SPARSE, 8, 20_000, k=1500)], ids=lambda w: w.name)
+                               small(wl.KIND_RAND_SPARSE, 8, 20_000, k=1500),
+                               replace(small(wl.KIND_QUANT_MAXABS, 8, 512 * 9 + 37, bits=2, block=512), algo=wl.ALGO_DCD_PSGD, name="dcd_graph"),
+                               replace(small(wl.KIND_SIGN_MEANABS, 8, 256 * 9 + 37, block=256), algo=wl.ALGO_CHOCO_SGD, name="choco_graph")],
+                         ids=lambda w: w.name)
 def test_hip_graph_replay(w):
     """ds_step captured once into a HIP graph and replayed: the step counter lives on the device, so every
     replay draws fresh rounding words; each replay is checked against the oracle, with eager work between."""
