@@ -19,7 +19,7 @@
 // its *compressed* value with coefficient W_ii - 1.
 //
 // The paper leaves C_omega generic (Assumption 1.6 only asks for a bounded
-// signal-to-noise factor).  The six operators implemented here, and the exact
+// signal-to-noise factor).  The seven operators implemented here, and the exact
 // floating-point evaluation order used for `real = float`, are this
 // repository's readings; every one is stated next to the code that does it.
 //
@@ -103,7 +103,18 @@ uint32_t keep_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
     return out[j % 4];
 }
 
-enum Kind { IDENTITY = 0, QUANT_MAXABS = 1, SIGN_MEANABS = 2, TOPK = 3, QUANT_L2NORM = 4, RAND_SPARSE = 5 };
+// ... and by the magnitude-proportional sparsifier (operator 6), in a third stream ('GSPR').
+const uint32_t kGsparTag = 0x47535052u;
+
+uint32_t gspar_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
+    const uint32_t ctr[4] = {(uint32_t)(j / 4), i, (uint32_t)t, kGsparTag};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t out[4];
+    philox4x32_10(ctr, key, out);
+    return out[j % 4];
+}
+
+enum Kind { IDENTITY = 0, QUANT_MAXABS = 1, SIGN_MEANABS = 2, TOPK = 3, QUANT_L2NORM = 4, RAND_SPARSE = 5, GSPAR = 6 };
 
 template <typename real> real fma_(real a, real b, real c);
 template <> float  fma_<float>(float a, float b, float c)    { return std::fmaf(a, b, c); }
@@ -316,6 +327,63 @@ bool compress_row_rand_sparse(const real* v, real* cv, uint64_t N, uint64_t k,
     return !overflow;
 }
 
+// ---------------------------------------------------------------------------
+// C_omega, operator 6: GSpar, named next to random sparsification, top-k and
+// random quantisation as satisfying Assumption 1.6 (section "Theoretical
+// analysis", the paragraph after Theorem 1).  The paper says no more about it.
+// Reading: the magnitude-proportional sparsifier that name stands for --
+// element j is kept with probability p_j = min(1, lambda |v_j|), independently,
+// with lambda chosen so that the expected number of kept elements is k when no
+// probability is cut off at 1:  lambda = k / sum_j |v_j|  (one shot: where some
+// p_j are cut off the expected count is below k; no second round redistributes
+// it).  As for operator 5 the kept values are NOT divided by p_j: the unbiased
+// variant has E||C[v] - v||^2 = sum v_j^2 (1/p_j - 1), unbounded against
+// ||v||^2, while the plain mask gives sum v_j^2 (1 - p_j) < ||v||^2, inside
+// the assumption.  sum |v| is taken in double by the balanced adjacent-pairs
+// tree over the zero-padded vector (|v_j| is exact in double), lambda and
+// p_j = lambda * |v_j| are single roundings in `real`; element j is kept iff
+// u_j < p_j with u_j = (word >> 8) / 2^24 from the stream 'GSPR' (so p_j >= 1
+// always keeps).  The mask depends on v, so the receiver cannot rebuild it and
+// the message carries the columns:
+//   [u32 count][u32 0][count (u32 column, f32 value) pairs, ascending column],
+// zero-padded to the capacity of operator 5 (pairs instead of values).
+// Returns false if more elements were kept than the message has room for.
+// ---------------------------------------------------------------------------
+template <typename real>
+double sum_abs_tree(const real* v, uint64_t N) {
+    uint64_t P = 1;
+    while (P < N) P *= 2;
+    std::vector<double> a(P, 0.0);
+    for (uint64_t j = 0; j < N; ++j) a[j] = std::fabs((double)v[j]);
+    for (uint64_t len = P; len > 1; len /= 2)
+        for (uint64_t p = 0; p < len / 2; ++p) a[p] = a[2 * p] + a[2 * p + 1];
+    return a[0];
+}
+
+template <typename real>
+bool compress_row_gspar(const real* v, real* cv, uint64_t N, uint64_t k,
+                        uint64_t seed, uint64_t t, uint32_t i, Msg<real>& msg) {
+    const double total = sum_abs_tree<real>(v, N);
+    const real lambda = (total > 0) ? (real)((double)k / total) : (real)0;
+    const uint64_t cap = rand_sparse_capacity(N, k);
+    std::vector<uint64_t> cols;
+    for (uint64_t j = 0; j < N; ++j) {
+        const real p = lambda * (real)std::fabs(v[j]);
+        const real u = (real)(gspar_word(seed, t, i, j) >> 8) * (real)(1.0 / 16777216.0);
+        const bool keep = u < p;
+        cv[j] = keep ? v[j] : (real)0;
+        if (keep) cols.push_back(j);
+    }
+    const bool overflow = cols.size() > cap;
+    msg.put_u32((uint32_t)(overflow ? cap : cols.size()));
+    msg.put_u32(0u);
+    for (uint64_t r = 0; r < cap; ++r) {
+        if (r < cols.size()) { msg.put_u32((uint32_t)cols[r]); msg.put_f32(v[cols[r]]); }
+        else { msg.put_u32(0u); msg.put_u32(0u); }
+    }
+    return !overflow;
+}
+
 // Argument and CSR sanity shared by the update rules below: 0 if fine.
 template <typename real>
 int check_arguments(int n, uint64_t N, const int32_t* rowptr, const int32_t* col, const real* wval,
@@ -323,8 +391,8 @@ int check_arguments(int n, uint64_t N, const int32_t* rowptr, const int32_t* col
     if (n < 1 || N < 1 || !rowptr || !col || !wval || !x || !state2 || !g) return 1;
     if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && (block < 1 || (block & (block - 1)))) return 1;
     if ((kind == QUANT_MAXABS || kind == QUANT_L2NORM) && (bits < 1 || bits > 8 || 32 % bits)) return 1;
-    if ((kind == TOPK || kind == RAND_SPARSE) && (k < 1 || k > N)) return 1;
-    if (kind == RAND_SPARSE && N > 0xFFFFFFFFull) return 1;
+    if ((kind == TOPK || kind == RAND_SPARSE || kind == GSPAR) && (k < 1 || k > N)) return 1;
+    if ((kind == RAND_SPARSE || kind == GSPAR) && N > 0xFFFFFFFFull) return 1;
     for (int i = 0; i < n; ++i) {                         // CSR sanity: sorted, has diagonal
         bool diag = false;
         for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
@@ -369,6 +437,11 @@ int compress_workers(int n, uint64_t N, const real* v, real* cv, int kind, int b
             compress_row_quant_l2norm<real>(vi, ci, N, bits, msg);
         } else if (kind == RAND_SPARSE) {
             if (!compress_row_rand_sparse<real>(vi, ci, N, k, seed, t, (uint32_t)i, msg)) {
+#pragma omp atomic write
+                sparse_overflow = true;
+            }
+        } else if (kind == GSPAR) {
+            if (!compress_row_gspar<real>(vi, ci, N, k, seed, t, (uint32_t)i, msg)) {
 #pragma omp atomic write
                 sparse_overflow = true;
             }
@@ -544,6 +617,10 @@ uint32_t dso_rounding_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) {
 
 uint32_t dso_keep_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) { return keep_word(seed, t, i, j); }
 
+uint32_t dso_gspar_word(uint64_t seed, uint64_t t, uint32_t i, uint64_t j) { return gspar_word(seed, t, i, j); }
+
+double dso_sum_abs_tree_f32(const float* v, uint64_t N) { return sum_abs_tree<float>(v, N); }
+
 uint64_t dso_rand_sparse_capacity(uint64_t N, uint64_t k) { return rand_sparse_capacity(N, k); }
 
 // Threads the loops over workers are spread over: 1 unless built with -fopenmp.
@@ -572,7 +649,7 @@ int dso_step_window_f32(int n, uint64_t N, uint64_t col0, const int32_t* rowptr,
                         int kind, int bits, uint64_t block, float gamma, float eta,
                         uint64_t seed, uint64_t t, float* x, float* delta, const float* g,
                         uint8_t* msg, uint64_t msg_cap, uint64_t* msg_bytes) {
-    if (kind == TOPK || kind == QUANT_L2NORM || kind == RAND_SPARSE) return 1;   // whole-vector operators and messages have no windows
+    if (kind == TOPK || kind == QUANT_L2NORM || kind == RAND_SPARSE || kind == GSPAR) return 1;   // whole-vector operators and messages have no windows
     if ((kind == QUANT_MAXABS || kind == SIGN_MEANABS) && block && col0 % block) return 1;
     return step<float>(n, N, rowptr, col, wval, kind, bits, block, 0, gamma, eta, seed, t,
                        x, delta, g, nullptr, msg, msg_cap, msg_bytes, col0);

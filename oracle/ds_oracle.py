@@ -20,6 +20,7 @@ KIND_SIGN_MEANABS = 2  # sign bit + block mean-abs scale
 KIND_TOPK = 3          # k largest magnitudes of the whole vector
 KIND_QUANT_L2NORM = 4  # b-bit codes over the whole vector + its Euclidean norm (the paper's experiments)
 KIND_RAND_SPARSE = 5   # every element kept with probability k/N, no rescaling
+KIND_GSPAR = 6         # element j kept with probability min(1, k |v_j| / sum |v|), no rescaling; (column, value) pairs
 
 ALGO_DEEPSQUEEZE = 0   # Algorithm 1
 ALGO_DCD_PSGD = 1      # compressed difference of the model update ("Why DeepSqueeze is better", DCD-PSGD item)
@@ -79,6 +80,10 @@ def _load(omp: bool = False):
     lib.dso_rounding_word.argtypes = [u64, u64, u32, u64]
     lib.dso_keep_word.restype = u32
     lib.dso_keep_word.argtypes = [u64, u64, u32, u64]
+    lib.dso_gspar_word.restype = u32
+    lib.dso_gspar_word.argtypes = [u64, u64, u32, u64]
+    lib.dso_sum_abs_tree_f32.restype = ctypes.c_double
+    lib.dso_sum_abs_tree_f32.argtypes = [vp, u64]
     lib.dso_rand_sparse_capacity.restype = u64
     lib.dso_rand_sparse_capacity.argtypes = [u64, u64]
     lib.dso_sum_squares_tree_f32.restype = ctypes.c_double
@@ -111,6 +116,17 @@ def rounding_word(seed: int, t: int, i: int, j: int) -> int:
 def keep_word(seed: int, t: int, i: int, j: int) -> int:
     """The 32-bit word that decides whether the random sparsifier keeps element (i, j) at step t."""
     return int(_load().dso_keep_word(seed, t, i, j))
+
+
+def gspar_word(seed: int, t: int, i: int, j: int) -> int:
+    """The 32-bit word that decides whether the magnitude-proportional sparsifier keeps element (i, j) at step t."""
+    return int(_load().dso_gspar_word(seed, t, i, j))
+
+
+def sum_abs_tree(v) -> float:
+    """Sum of |v| of a float32 vector in float64, balanced adjacent-pairs tree over the zero-padded vector."""
+    a = np.ascontiguousarray(v, dtype=np.float32)
+    return float(_load().dso_sum_abs_tree_f32(a.ctypes.data, a.size))
 
 
 def rand_sparse_capacity(N: int, k: int) -> int:
@@ -173,6 +189,8 @@ def message_bytes(kind: int, n: int, N: int, bits: int = 0, block: int = 0, k: i
         return n * (4 + 4 * ((N * bits + 31) // 32))
     if kind == KIND_RAND_SPARSE:
         return n * (4 + 4 * rand_sparse_capacity(N, k))
+    if kind == KIND_GSPAR:
+        return n * (8 + 8 * rand_sparse_capacity(N, k))
     b = bits if kind == KIND_QUANT_MAXABS else 1
     full, tail = divmod(N, block)
     per_row = full * (4 + 4 * ((block * b + 31) // 32))

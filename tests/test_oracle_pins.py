@@ -17,7 +17,7 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE,
+from oracle import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE, KIND_GSPAR,
                     OracleState)
 
 
@@ -159,6 +159,7 @@ COMPRESSORS = [
     dict(kind=KIND_QUANT_L2NORM, bits=2),
     dict(kind=KIND_QUANT_L2NORM, bits=4),
     dict(kind=KIND_RAND_SPARSE, k=20),
+    dict(kind=KIND_GSPAR, k=15),
 ]
 
 
@@ -529,6 +530,134 @@ def test_rand_sparse_keeping_everything_is_dpsgd():
     assert np.all(a.delta == 0)
 
 
+# ----------------------------------------------------------------------------- GSpar (magnitude-proportional sparsifier)
+
+def test_gspar_mask_rule_message_and_residual():
+    # keep iff u < p, u = (word >> 8) / 2^24 from the stream 'GSPR', p = fp32(lambda) * |v| in fp32,
+    # lambda = k / sum |v|; the message lists the kept (column, value) pairs in ascending column order
+    n, N, k, seed = 4, 3001, 500, 9
+    r = np.random.default_rng(51)
+    v = (r.standard_normal((n, N)) * np.exp(r.standard_normal((n, N)))).astype(np.float32)      # heavy-ish tails
+    st = OracleState(n=n, N=N, W=np.eye(n), kind=KIND_GSPAR, k=k, gamma=0.0, eta=0.5, seed=seed, t=6, x=v.copy())
+    cv, msg = oracle.step(st, np.zeros_like(v))
+    GSPR = int.from_bytes(b"GSPR", "big")
+    cap = k + 8 * 23 + 64
+    assert len(msg) == n * (8 + 8 * cap)
+    for i in range(n):
+        words = np.array([oracle.philox4x32_10([j // 4, i, 6, GSPR], [seed, 0])[j % 4] for j in range(N)], dtype=np.uint64)
+        assert [oracle.gspar_word(seed, 6, i, j) for j in (0, 1, 5, N - 1)] == [int(words[j]) for j in (0, 1, 5, N - 1)]
+        lam = np.float32(k / np.abs(v[i].astype(np.float64)).sum())          # the tree sum differs from this one in the last bits at most
+        assert abs(float(lam) - k / oracle.sum_abs_tree(v[i])) <= 1e-7 * float(lam)
+        lam = np.float32(k / oracle.sum_abs_tree(v[i]))
+        p = lam * np.abs(v[i])                                               # fp32 product
+        assert p.dtype == np.float32
+        u = ((words >> np.uint64(8)).astype(np.float64) / 2.0 ** 24).astype(np.float32)     # exact in fp32
+        keep = u < p
+        assert 0.5 * k < keep.sum() < 1.5 * k
+        np.testing.assert_array_equal(cv[i], np.where(keep, v[i], np.float32(0)))
+        np.testing.assert_array_equal(st.delta[i], np.where(keep, np.float32(0), v[i]))
+        row = msg[i * (8 + 8 * cap):(i + 1) * (8 + 8 * cap)]
+        head = np.frombuffer(row[:8].tobytes(), np.uint32)
+        assert head[0] == keep.sum() and head[1] == 0
+        pairs = np.frombuffer(row[8:].tobytes(), np.uint32).reshape(cap, 2)
+        np.testing.assert_array_equal(pairs[:head[0], 0], np.nonzero(keep)[0])
+        np.testing.assert_array_equal(pairs[:head[0], 1].view(np.float32), v[i][keep])
+        assert np.all(pairs[head[0]:] == 0)
+    assert oracle.gspar_word(seed, 6, 0, 0) not in (oracle.keep_word(seed, 6, 0, 0), oracle.rounding_word(seed, 6, 0, 0))
+
+
+def test_gspar_sum_of_magnitudes_is_the_adjacent_pairs_tree_in_double():
+    # an input where the balanced tree and a left-to-right sum give different doubles
+    v = np.array([1.0, -2.0 ** -53, 2.0 ** -53, -2.0 ** -53, 2.0 ** -60], dtype=np.float32)
+    tree = ((1.0 + 2.0 ** -53) + (2.0 ** -53 + 2.0 ** -53)) + ((2.0 ** -60 + 0.0) + (0.0 + 0.0))
+    seq = 0.0
+    for a in np.abs(v.astype(np.float64)):
+        seq += a
+    assert tree == 1.0 + 2.0 ** -52 and seq == 1.0
+    assert oracle.sum_abs_tree(v) == tree
+    big = np.random.default_rng(52).standard_normal(100_003).astype(np.float32)
+    assert abs(oracle.sum_abs_tree(big) - np.abs(big.astype(np.float64)).sum()) < 1e-9 * np.abs(big).sum()
+    assert oracle.sum_abs_tree(np.zeros(7, np.float32)) == 0.0
+
+
+def test_gspar_threshold_is_strict_and_uses_24_bits():
+    # keep iff u < p with u the top 24 bits of the word.  Four elements whose magnitudes sum to exactly 16 make
+    # lambda = k / 16 = 1/8 exact for k = 2; element 0 gets |v| = 8 u_0, so p_0 = u_0 exactly: it must be dropped
+    # (u <= p would keep it; so would a u built from 23 bits, since u_0's lowest bit is set).  Element 1 gets the
+    # next fp32 above 8 u_1 and must be kept.
+    found = 0
+    for seed in range(200):
+        w0, w1 = oracle.gspar_word(seed, 0, 0, 0) >> 8, oracle.gspar_word(seed, 0, 0, 1) >> 8
+        if not (w0 & 1) or not (2 ** 21 < w0 < 2 ** 23) or not (2 ** 21 < w1 < 2 ** 23):
+            continue
+        a0 = np.float32(8.0 * w0 / 2.0 ** 24)
+        a1 = np.nextafter(np.float32(8.0 * w1 / 2.0 ** 24), np.float32(16))
+        rest = 16.0 - float(a0) - float(a1)                     # exact in double; split into two fp32
+        lo = rest % 2.0 ** -19
+        hi = rest - lo
+        v = np.array([[a0, -a1, hi, lo]], dtype=np.float32)
+        assert float(v[0, 2]) == hi and float(v[0, 3]) == lo and oracle.sum_abs_tree(v[0]) == 16.0
+        st = OracleState(n=1, N=4, W=np.ones((1, 1)), kind=KIND_GSPAR, k=2, gamma=0.0, eta=0.5, seed=seed, x=v.copy())
+        cv, _ = oracle.step(st, np.zeros_like(v), want_msg=False)
+        assert cv[0, 0] == 0 and cv[0, 1] == -a1
+        found += 1
+        if found == 3:
+            break
+    assert found == 3
+
+
+def test_gspar_probabilities_rate_and_signal_to_noise():
+    # over many steps (fresh masks) the keep frequency of an element is min(1, lambda |v_j|); the expected count is
+    # k when nothing is cut off; E|C[v] - v|^2 = sum v_j^2 (1 - p_j) < |v|^2: Assumption 1.6 with alpha < 1
+    N, k, T = 2000, 300, 400
+    r = np.random.default_rng(53)
+    v = r.standard_normal((1, N))
+    lam = k / np.abs(v[0]).sum()
+    p = np.minimum(1.0, lam * np.abs(v[0]))
+    assert p.max() < 1.0 and abs(p.sum() - k) < 1e-9 * k
+    freq = np.zeros(N)
+    err = 0.0
+    st = OracleState(n=1, N=N, W=np.ones((1, 1)), kind=KIND_GSPAR, k=k, gamma=0.0, eta=0.5, seed=4, dtype=np.float64, x=v.copy())
+    counts = []
+    for t in range(T):
+        st.x[:], st.delta[:] = v, 0.0
+        cv, _ = oracle.step(st, np.zeros_like(v), want_msg=False)
+        kept = cv[0] != 0
+        np.testing.assert_array_equal(cv[0][kept], v[0][kept])             # kept values are exact, no rescaling
+        freq += kept
+        counts.append(kept.sum())
+        err += ((cv[0] - v[0]) ** 2).sum()
+    sd = np.sqrt(p * (1 - p) / T)
+    assert np.all(np.abs(freq / T - p) < 5 * sd + 1e-12)
+    assert abs(np.mean(counts) - k) < 5 * np.sqrt((p * (1 - p)).sum() / T)
+    want = (v[0] ** 2 * (1 - p)).sum()
+    assert abs(err / T - want) < 0.02 * want and want < (v[0] ** 2).sum()
+    # larger magnitudes are kept more often: the operator is not the uniform mask of the random sparsifier
+    order = np.argsort(np.abs(v[0]))
+    assert freq[order[-200:]].mean() > 3 * freq[order[:200]].mean()
+
+
+def test_gspar_cut_off_probabilities_zero_vector_and_k_equal_N():
+    # one dominant element: lambda |v_j| >= 1, so it is kept at every step and the expected count stays below k
+    N, k = 512, 64
+    v = np.full((1, N), 1e-3, dtype=np.float32)
+    v[0, 77] = 50.0
+    for t in range(20):
+        st = OracleState(n=1, N=N, W=np.ones((1, 1)), kind=KIND_GSPAR, k=k, gamma=0.0, eta=0.5, seed=2, t=t, x=v.copy())
+        cv, _ = oracle.step(st, np.zeros_like(v), want_msg=False)
+        assert cv[0, 77] == np.float32(50.0)
+        assert (cv[0] != 0).sum() < k
+    # all-zero vector: nothing is kept, the message is an empty list
+    st = OracleState(n=1, N=N, W=np.ones((1, 1)), kind=KIND_GSPAR, k=k, gamma=0.0, eta=0.5)
+    cv, msg = oracle.step(st, np.zeros((1, N), np.float32))
+    assert not cv.any() and not msg.any()
+    # k = N on a constant-magnitude vector: every p_j = 1 up to rounding of lambda; u < 1 always, so all are kept
+    v = np.where(np.random.default_rng(54).random((1, 64)) < 0.5, -2.0, 2.0).astype(np.float32)
+    st = OracleState(n=1, N=64, W=np.ones((1, 1)), kind=KIND_GSPAR, k=64, gamma=0.0, eta=0.5, x=v.copy())
+    cv, _ = oracle.step(st, np.zeros_like(v), want_msg=False)
+    np.testing.assert_array_equal(cv, v)
+
+
 # ----------------------------------------------------------------------------- P7: quantiser
 
 def test_quantiser_worked_example(golden_dir):
@@ -800,7 +929,7 @@ def test_all_cores_build_gives_the_same_bits():
     n, N = 6, 3000
     for kind, kw in ((oracle.KIND_QUANT_MAXABS, dict(bits=2, block=256)), (oracle.KIND_SIGN_MEANABS, dict(block=128)),
                      (oracle.KIND_TOPK, dict(k=37)), (oracle.KIND_QUANT_L2NORM, dict(bits=4)),
-                     (oracle.KIND_RAND_SPARSE, dict(k=300)), (oracle.KIND_IDENTITY, {})):
+                     (oracle.KIND_RAND_SPARSE, dict(k=300)), (oracle.KIND_GSPAR, dict(k=300)), (oracle.KIND_IDENTITY, {})):
         outs = []
         for all_cores in (False, True):
             st = oracle.OracleState(n=n, N=N, W=oracle.ring_matrix(n), kind=kind, gamma=0.1, eta=0.4, seed=3, **kw)
