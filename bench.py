@@ -49,6 +49,8 @@ def algorithmic_bytes_per_param(w) -> float:
         msg = w.bits / 8
     elif w.kind == wl.KIND_RAND_SPARSE:
         msg = 4 * w.k / w.N
+    elif w.kind == wl.KIND_GSPAR:
+        msg = 8 * w.k / w.N
     else:
         msg = 4.0
     return (12.0 if w.algo == wl.ALGO_DCD_PSGD else 20.0) + msg
@@ -185,7 +187,7 @@ def run_config(torch, b, wl, w, K, Wm, hip_graph, copy_gbs, mix_gbs, traffic_tab
         "launch": "hip-graph" if graph is not None else "eager",
         "update_rule": {0: "deepsqueeze", 1: "dcd-psgd", 2: "choco-sgd"}[w.algo],
         "compressor": {1: f"quant{w.bits}b/B{w.block}", 2: f"sign/B{w.block}", 3: f"top-{w.k}", 0: "identity",
-                       4: f"l2norm{w.bits}b", 5: f"rand-{w.k}"}[w.kind],
+                       4: f"l2norm{w.bits}b", 5: f"rand-{w.k}", 6: f"gspar-{w.k}"}[w.kind],
         "ms_per_step": wall * 1e3 / K, "value": w.worker_params * K / wall,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_table.get(w.name),

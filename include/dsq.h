@@ -62,6 +62,13 @@ typedef enum {
                               /* level (ties to the even code); code q stands for y = 2q - L,     */
                               /* C[v] = y * (norm / ||y||_2).  Message per worker:                */
                               /* [f32 norm][ceil(N*bits/32) u32 words]; bits in {2, 4, 8}         */
+    DS_COMP_GSPAR = 6,        /* GSpar (named next to random sparsification under Assumption 1.6), read as the */
+                              /* magnitude-proportional sparsifier: element j is kept with probability          */
+                              /* p_j = min(1, k |v_j| / sum_j |v_j|) (one shot: no second round where some p_j  */
+                              /* are cut off at 1) and, like DS_COMP_RAND_SPARSE, not rescaled; the mask depends */
+                              /* on v, so the message carries the columns: [u32 count][u32 0][count (u32 column, */
+                              /* f32 value) pairs, ascending column], zero-padded to min(N, k + 8 ceil(sqrt k)   */
+                              /* + 64) pairs                                                                     */
     DS_COMP_RAND_SPARSE = 5   /* random sparsification (named next to top-k under Assumption 1.6): */
                               /* every element is kept independently with probability k/N (floor   */
                               /* to a multiple of 2^-24) and not rescaled; the mask comes from the  */
@@ -76,8 +83,8 @@ typedef struct {
     int32_t  block;   /* QUANT_MAXABS, SIGN_MEANABS: power of two, 64 <= block <= 2048 (the fused  */
                       /* kernel holds a whole block in one wave's registers)                    */
     int32_t  reserved;
-    uint64_t k;       /* TOPK: 1 <= k <= N; RAND_SPARSE: expected kept elements per worker,     */
-                      /* 1 <= k <= N; otherwise ignored                                         */
+    uint64_t k;       /* TOPK: 1 <= k <= N; RAND_SPARSE, GSPAR: expected kept elements per      */
+                      /* worker, 1 <= k <= N; otherwise ignored                                 */
 } ds_comp;
 
 /* Update rule of a step.  DS_ALGO_DEEPSQUEEZE is Algorithm 1.  The other two are the compressed decentralized
@@ -146,6 +153,10 @@ ds_status ds_build_topology(const ds_config* cfg, int32_t* rowptr, int32_t* col,
  *                 min(N, k + 8 ceil(sqrt k) + 64) values; which columns were kept follows from the seed
  *                 (Philox4x32-10, counter (floor(j/4), i, t, 'SPAR'), word j mod 4, kept iff
  *                 (word >> 8) < floor(k 2^24 / N)).
+ *   GSPAR:        [u32 count][u32 0][count pairs (u32 column, f32 value) in ascending column order], zero-padded
+ *                 to the same capacity in pairs.  Element j is kept iff u < p_j, u = (word >> 8) / 2^24 with the
+ *                 Philox word of counter (floor(j/4), i, t, 'GSPR'), word j mod 4, and p_j = fp32(k / S) * |v_j| in
+ *                 fp32, S = sum_j |v_j| in double (balanced adjacent-pairs tree over the zero-padded vector).
  * Returns 0 for an invalid configuration. */
 uint64_t ds_message_bytes(const ds_config* cfg);
 

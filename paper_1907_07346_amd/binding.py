@@ -14,7 +14,7 @@ from typing import Optional
 import numpy as np
 import torch  # noqa: F401  (must be loaded before libdsq.so: one HIP runtime per process)
 
-from .workloads import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE,  # noqa: F401
+from .workloads import (KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE, KIND_GSPAR,  # noqa: F401
                         TOPO_CSR, TOPO_RING, TOPO_TORUS2D, Config)
 
 DS_OK, DS_EINVAL, DS_ENOMEM, DS_EHIP, DS_ESTATE = range(5)

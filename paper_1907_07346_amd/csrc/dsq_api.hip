@@ -78,6 +78,11 @@ dsq::TopkArgs topk_args(const ds_handle* h, const float* g_dev, uint64_t g_ld) {
     a.rowptr = h->d_rowptr; a.col = h->d_col; a.coef = h->d_coef;
     a.ld = h->ld; a.g_ld = g_ld; a.N = h->cfg.N; a.k = h->cfg.comp.k; a.n = h->cfg.n;
     a.gamma = h->cfg.gamma; a.eta = h->cfg.eta; a.t_ptr = h->d_t;
+    if (h->cfg.comp.kind == DS_COMP_GSPAR) {               // rows of [header pair][capacity pairs]
+        a.k = h->msg_row_bytes / 8;
+        a.k_expected = h->cfg.comp.k;
+        a.seed_lo = (uint32_t)h->cfg.seed; a.seed_hi = (uint32_t)(h->cfg.seed >> 32);
+    }
     return a;
 }
 
@@ -433,8 +438,11 @@ ds_status ds_init_ex(const ds_config* cfg, const ds_plan_request* plan, char* er
     h->ld = base_ld + kMaxPitchSkew;                       // allocation pitch; the working pitch is fixed below
     h->msg_row_bytes = dsq::message_row_bytes(cfg);
 
-    const bool tiled = cfg->comp.kind != DS_COMP_TOPK && cfg->comp.kind != DS_COMP_QUANT_L2NORM;
-    if (cfg->comp.kind == DS_COMP_TOPK) {
+    const bool sparse_pairs = cfg->comp.kind == DS_COMP_TOPK || cfg->comp.kind == DS_COMP_GSPAR;   // (column, value) messages
+    const bool tiled = !sparse_pairs && cfg->comp.kind != DS_COMP_QUANT_L2NORM;
+    if (cfg->comp.kind == DS_COMP_GSPAR) {
+        h->plan_name = "gspar/count-scan-write";
+    } else if (cfg->comp.kind == DS_COMP_TOPK) {
         h->plan_name = "topk/radix-select";
     } else if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {
         h->plan_name = "l2norm/speculative-codes";
@@ -505,7 +513,7 @@ ds_status ds_init_ex(const ds_config* cfg, const ds_plan_request* plan, char* er
                        std::to_string(h->tile.sweeps) + "sweeps";
     h->plan_name += "/pitch+" + std::to_string(skew);
 
-    if (cfg->comp.kind == DS_COMP_TOPK) {
+    if (sparse_pairs) {
         const ds_status st = dsq::topk_create(h->cfg, h->ld, &h->topk, err);
         if (st != DS_OK) return bail(st, err);
     }
@@ -529,7 +537,7 @@ ds_status ds_step(ds_handle* h, const float* g_dev, uint64_t g_ld, void* hip_str
         return fail(h, DS_ESTATE, "the current HIP device is not the one the handle was created on");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
-    if (h->cfg.comp.kind == DS_COMP_TOPK) {
+    if (h->topk) {
         const ds_status st = dsq::topk_step(h->topk, topk_args(h, g_dev, g_ld), stream);
         if (st != DS_OK) return st;
     } else if (h->cfg.comp.kind == DS_COMP_QUANT_L2NORM) {
@@ -659,6 +667,11 @@ ds_status ds_read_messages(ds_handle* h, void* host_buf, uint64_t cap, uint64_t*
     uint8_t* src = nullptr;
     if (last_message_buffer(h, &src) != DS_OK) return DS_EHIP;
     DSQ_HIP(h, hipMemcpy(host_buf, src, total, hipMemcpyDeviceToHost));
+    if (h->cfg.comp.kind == DS_COMP_GSPAR) {
+        bool over = false;
+        if (dsq::gspar_overflowed(h->topk, h->last_stream, &over) != DS_OK) return DS_EHIP;
+        if (over) return fail(h, DS_ESTATE, "a worker kept more elements than its message has room for: the messages since then are cut short");
+    }
     if (h->d_keep) {
         uint32_t overflow = 0;
         DSQ_HIP(h, hipMemcpy(&overflow, h->d_keep + (size_t)h->cfg.n * (h->nsweeps + h->ngroups) + h->cfg.n, sizeof(overflow), hipMemcpyDeviceToHost));

@@ -77,6 +77,7 @@ ds_status validate_config(const ds_config* cfg, std::string& err, std::string* w
             if (c.bits != 2 && c.bits != 4 && c.bits != 8) { err = "bits must be 2, 4 or 8"; return DS_EINVAL; }
             break;
         case DS_COMP_RAND_SPARSE:
+        case DS_COMP_GSPAR:
             if (c.k < 1 || c.k > cfg->N) { err = "k (expected number of kept elements) must be in [1, N]"; return DS_EINVAL; }
             break;
         default: err = "unknown compressor"; return DS_EINVAL;
@@ -153,6 +154,7 @@ uint64_t message_row_bytes(const ds_config* cfg) {
         case DS_COMP_TOPK: return c.k * 8;
         case DS_COMP_QUANT_L2NORM: return 4 + 4 * ((cfg->N * (uint64_t)c.bits + 31) / 32);
         case DS_COMP_RAND_SPARSE: return 4 + 4 * rand_sparse_capacity(cfg->N, c.k);
+        case DS_COMP_GSPAR: return 8 + 8 * rand_sparse_capacity(cfg->N, c.k);
         case DS_COMP_QUANT_MAXABS:
         case DS_COMP_SIGN_MEANABS: {
             const uint64_t b = (c.kind == DS_COMP_QUANT_MAXABS) ? (uint64_t)c.bits : 1;

@@ -108,10 +108,14 @@ struct TopkArgs {
     const int32_t* rowptr;
     const int32_t* col;
     const float* coef;
-    uint64_t ld, g_ld, N, k;
+    uint64_t ld, g_ld, N, k;   // k: pairs from one row's message to the next (top-k: the k of the operator; GSpar: the
+                               // capacity plus the header pair)
     int n;
     float gamma, eta;
-    unsigned long long* t_ptr;  // step counter in device memory (advanced once per step; top-k draws no random numbers)
+    unsigned long long* t_ptr;  // step counter in device memory (advanced once per step)
+    // GSpar only:
+    uint64_t k_expected;       // the operator's k (expected kept elements)
+    uint32_t seed_lo, seed_hi; // key of the mask's random stream
 };
 
 struct TopkState;              // device scratch of the radix select (histograms, per-chunk counts)
@@ -124,6 +128,8 @@ ds_status topk_step(TopkState* s, const TopkArgs& a, hipStream_t stream);
 ds_status topk_flush(TopkState* s, const TopkArgs& a, hipStream_t stream);
 // Number of rows whose last step selected from the candidate slots (the fast path).
 ds_status topk_candidate_rows(TopkState* s, hipStream_t stream, uint32_t* count);
+// GSpar: true if a row has kept more elements than its message has room for in some step since the handle was made.
+ds_status gspar_overflowed(TopkState* s, hipStream_t stream, bool* overflowed);
 
 // ---- norm-rescaled b-bit path (DS_COMP_QUANT_L2NORM) ----------------------------------------------
 struct L2Args {

@@ -22,28 +22,10 @@
 #pragma once
 
 #include "dsq_internal.h"
+#include "dsq_philox.h"
 
 namespace dsq {
 namespace {
-
-// ---- Philox4x32-10 (Salmon et al., SC'11), counter-based, no state --------------------------
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-        c1 = (uint32_t)p1;
-        c3 = (uint32_t)p0;
-        c0 = n0;
-        c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
 
 constexpr uint32_t kQuantStreamTag = 0x51554E54u;   // 4th counter word of the rounding stream
 constexpr uint32_t kSparseStreamTag = 0x53504152u;  // ... and of the stream that draws the random sparsifier's mask

@@ -38,6 +38,7 @@
 // applied by topk_flush before anyone else looks at the state.
 
 #include "dsq_internal.h"
+#include "dsq_philox.h"
 
 namespace dsq {
 
@@ -77,6 +78,8 @@ struct TopkRow {
     uint32_t bin_need;         //                 how many elements to take inside that bin
     uint32_t list_count;       //                 elements of that bin listed so far by topk_bin_collect
     float drift_prev;          // last step's movement of |tau| as a float (for the forecast of the next threshold)
+    float lambda;              // GSpar: this step's k / sum |v|
+    uint32_t gs_total;         // GSpar: pairs in the row's last message (what a shorter message must clear behind it)
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -134,6 +137,8 @@ struct Scratch {               // device pointers of the select's scratch (all o
                                // passes read only these
     uint16_t* slot_idx;        // same shape: the candidates' columns, relative to the start of the chunk
     uint2* list;               // n x TK_LIST_CAP: (key, chunk) of the candidates inside the threshold's histogram bin
+    double* csum;              // GSpar: n x nchunks tree sums of |v| over the chunks
+    uint32_t* gs_overflow;     // GSpar: set once a row kept more than its message holds
     uint32_t nchunks;
 };
 
@@ -160,9 +165,19 @@ __device__ __forceinline__ uint32_t row_exclusive_scan(uint32_t v, uint32_t* wav
     return base + inc - v;
 }
 
+__device__ __forceinline__ double wave_tree_sum_f64(double v) {   // adjacent pairs first; every lane gets the sum
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
 // ---- pass 1: pending gossip of the previous step, Algorithm 1 line 5, candidate collection ------
+// GS (the GSpar operator shares this pass and the message conventions): no candidates; instead the chunk's sum of
+// |v| in double, as the balanced adjacent-pairs tree the operator's lambda is defined with.
+template <bool GS>
 __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scratch s) {
     __shared__ float acc[TK_CHUNK];
+    [[maybe_unused]] __shared__ double sweep_abs[TK_ITERS * (TK_THREADS / 64)];
     __shared__ uint32_t own[TK_CHUNK / 32];       // columns this worker itself sent in the previous step
     __shared__ uint32_t h[TK_H1];                              // level-1 digits of the candidates, relative to tlo's
     __shared__ uint32_t cand_count;
@@ -294,6 +309,11 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
         xh.x += 0.f; xh.y += 0.f; xh.z += 0.f; xh.w += 0.f;
         st4_stream(xr + j, xh);
         st4_stream(dr + j, v);
+        if constexpr (GS) {                                    // padding columns hold v = 0
+            const double sw = wave_tree_sum_f64(((double)fabsf(v.x) + (double)fabsf(v.y)) + ((double)fabsf(v.z) + (double)fabsf(v.w)));
+            if ((threadIdx.x & 63) == 0) sweep_abs[it * (TK_THREADS / 64) + (threadIdx.x >> 6)] = sw;   // sweep index = column order
+            continue;
+        }
         const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c)
@@ -305,6 +325,19 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
             }
     }
     __syncthreads();
+    if constexpr (GS) {
+        if (threadIdx.x == 0) {
+            double t[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) t[q] = sweep_abs[q];
+#pragma unroll
+            for (int len = 16; len > 1; len >>= 1)
+#pragma unroll
+                for (int q = 0; q < len / 2; ++q) t[q] = t[2 * q] + t[2 * q + 1];
+            s.csum[(size_t)row * s.nchunks + chunk] = t[0];
+        }
+        return;
+    }
     // the row histogram is used if the row ends up in candidate mode and wiped by topk_decide_select either way;
     // a candidate beyond the tracked bins (256 bins = 2^32 in magnitude above tlo) sends the row the exact way
     uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
@@ -904,6 +937,165 @@ __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
     }
 }
 
+// ---- GSpar: the magnitude-proportional sparsifier on the message conventions of the top-k path ------------
+// A row's message is [count, 0][pairs ...]: the header takes the place of pair 0, so the message offsets of the
+// chunks (out_off) start at 1 and the first pass / the flush apply the tail exactly as for top-k.
+static_assert(TK_ITERS * (TK_THREADS / 64) == 16, "the chunk trees are written for 16 sweeps");
+constexpr uint32_t kGsparStreamTag = 0x47535052u;            // 4th counter word of the mask's random stream
+
+// Per row: S = sum |v| (the tree continued over the chunk sums, padded with zeros to a power of two), lambda = k / S.
+__global__ void __launch_bounds__(TK_RTHREADS) gs_row_lambda(Scratch s, double k_expected) {
+    __shared__ double wsum[TK_RTHREADS / 64];
+    const int row = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t nchunks = s.nchunks;
+    uint32_t per = 1;                                         // leaves per thread: a power of two
+    while ((uint64_t)per * TK_RTHREADS < nchunks) per <<= 1;
+    const double* leaf = s.csum + (size_t)row * nchunks;
+    double stack[32];                                         // adjacent-pairs tree over this thread's leaves: a binary counter
+    int sp = 0;
+    const uint64_t first = (uint64_t)threadIdx.x * per;
+    for (uint32_t e = 0; e < per; ++e) {
+        const uint64_t c = first + e;
+        double val = (c < nchunks) ? leaf[c] : 0.0;
+        for (uint32_t bit = e; bit & 1u; bit >>= 1) val = stack[--sp] + val;
+        stack[sp++] = val;
+    }
+    const double sum = wave_tree_sum_f64(stack[0]);           // per is a power of two: one entry is left
+    if (lane == 0) wsum[wave] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t[q] = wsum[q];
+#pragma unroll
+        for (int len = 16; len > 1; len >>= 1)
+#pragma unroll
+            for (int q = 0; q < len / 2; ++q) t[q] = t[2 * q] + t[2 * q + 1];
+        s.rows[row].lambda = (t[0] > 0.0) ? (float)(k_expected / t[0]) : 0.f;
+    }
+}
+static_assert(TK_RTHREADS / 64 == 16, "the wave tree above is written for 16 waves");
+
+// The keep decisions of four adjacent columns of worker `row`.
+__device__ __forceinline__ uint32_t gs_keep4(const TopkArgs& a, int row, uint64_t j, uint32_t t_lo, float lambda, const float4& v) {
+    uint32_t rnd[4];
+    philox4x32_10((uint32_t)(j >> 2), (uint32_t)row, t_lo, kGsparStreamTag, a.seed_lo, a.seed_hi, rnd);
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+    uint32_t keep = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float p = lambda * fabsf(vv[c]);
+        const float u = (float)(rnd[c] >> 8) * (1.0f / 16777216.0f);
+        if (j + c < a.N && u < p) keep |= 1u << c;
+    }
+    return keep;
+}
+
+// Per chunk: the kept elements in column order -> the chunk's slot (the first TK_CAP of them) and their number.
+__global__ void __launch_bounds__(TK_THREADS) gs_count(TopkArgs a, Scratch s) {
+    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    const int row = blockIdx.y;
+    const uint32_t chunk = blockIdx.x;
+    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+    const float lambda = s.rows[row].lambda;
+    const uint32_t t_lo = (uint32_t)*a.t_ptr;
+    const float* dr = a.delta + (uint64_t)row * a.ld;         // holds v
+    uint32_t* slot_val = s.slot_val + ((size_t)row * s.nchunks + chunk) * TK_CAP;
+    uint16_t* slot_idx = s.slot_idx + ((size_t)row * s.nchunks + chunk) * TK_CAP;
+    float4 vin[TK_ITERS];
+#pragma unroll
+    for (int it = 0; it < TK_ITERS; ++it) vin[it] = ld4_stream(dr + c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x);   // rows are padded to whole chunks
+    uint32_t run = 0;
+#pragma unroll
+    for (int it = 0; it < TK_ITERS; ++it) {
+        const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
+        const uint32_t keep = gs_keep4(a, row, c0 + q0, t_lo, lambda, vin[it]);
+        uint32_t tot;
+        uint32_t pos = run + block_exclusive_scan(__popc(keep), wave_sums, &tot);
+        const float vv[4] = {vin[it].x, vin[it].y, vin[it].z, vin[it].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (keep & (1u << c)) {
+                if (pos < (uint32_t)TK_CAP) { slot_val[pos] = __float_as_uint(vv[c]); slot_idx[pos] = (uint16_t)(q0 + c); }
+                ++pos;
+            }
+        run += tot;
+    }
+    if (threadIdx.x == 0) s.cnt_gt[(size_t)row * s.nchunks + chunk] = run;
+}
+
+// Per row: where each chunk's pairs go in the message (offsets in pairs from the start of the row, the header
+// being pair 0), the header, zeros behind a message shorter than the last one, the overflow flag.
+__global__ void __launch_bounds__(TK_RTHREADS) gs_scan(TopkArgs a, Scratch s) {
+    __shared__ uint32_t wave_sums[TK_RTHREADS / 64];
+    const int row = blockIdx.x;
+    const uint32_t nchunks = s.nchunks;
+    const uint32_t cap = (uint32_t)a.k - 1u;                  // pairs the message has room for
+    const uint32_t* cnt = s.cnt_gt + (size_t)row * nchunks;
+    uint32_t* off = s.out_off + (size_t)row * (nchunks + 1);
+    uint32_t base = 0;
+    for (uint32_t b0 = 0; b0 < nchunks; b0 += TK_RTHREADS) {
+        const uint32_t c = b0 + threadIdx.x;
+        const uint32_t mine = (c < nchunks) ? cnt[c] : 0u;
+        uint32_t tot;
+        const uint32_t before = base + row_exclusive_scan(mine, wave_sums, &tot);
+        if (c < nchunks) off[c] = 1u + (before < cap ? before : cap);       // never past the row's last pair
+        base += tot;
+    }
+    const uint32_t count = base < cap ? base : cap;
+    uint2* mrow = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
+    const uint32_t last = s.rows[row].gs_total;
+    for (uint32_t p = count + threadIdx.x; p < last; p += TK_RTHREADS) mrow[1 + p] = make_uint2(0u, 0u);
+    __syncthreads();                                          // every thread has read gs_total
+    if (threadIdx.x == 0) {
+        off[nchunks] = 1u + count;
+        mrow[0] = make_uint2(count, 0u);
+        s.rows[row].gs_total = count;
+        if (base > cap) atomicOr(s.gs_overflow, 1u);
+    }
+}
+
+// Per chunk: the slot's pairs to their place in the message; a chunk that kept more than its slot holds decides again.
+__global__ void __launch_bounds__(TK_THREADS) gs_write(TopkArgs a, Scratch s) {
+    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    const int row = blockIdx.y;
+    const uint32_t chunk = blockIdx.x;
+    const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+    const uint32_t cnt = s.cnt_gt[(size_t)row * s.nchunks + chunk];
+    const uint32_t limit = (uint32_t)a.k;                     // pair positions of the row: [1, limit)
+    const uint32_t base = s.out_off[(size_t)row * (s.nchunks + 1) + chunk];
+    uint2* mrow = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
+    if (cnt <= (uint32_t)TK_CAP) {                            // uniform
+        const uint32_t* slot_val = s.slot_val + ((size_t)row * s.nchunks + chunk) * TK_CAP;
+        const uint16_t* slot_idx = s.slot_idx + ((size_t)row * s.nchunks + chunk) * TK_CAP;
+        for (uint32_t p = threadIdx.x; p < cnt; p += TK_THREADS)
+            if (base + p < limit) mrow[base + p] = make_uint2((uint32_t)(c0 + slot_idx[p]), slot_val[p]);
+        return;
+    }
+    const float lambda = s.rows[row].lambda;
+    const uint32_t t_lo = (uint32_t)*a.t_ptr;                 // the step's counter: advanced only after this kernel
+    const float* dr = a.delta + (uint64_t)row * a.ld;
+    uint32_t run = base;
+    for (int it = 0; it < TK_ITERS; ++it) {
+        const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
+        const float4 v = ld4_stream(dr + c0 + q0);
+        const uint32_t keep = gs_keep4(a, row, c0 + q0, t_lo, lambda, v);
+        uint32_t tot;
+        uint32_t pos = run + block_exclusive_scan(__popc(keep), wave_sums, &tot);
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (keep & (1u << c)) {
+                if (pos < limit) mrow[pos] = make_uint2((uint32_t)(c0 + q0 + c), __float_as_uint(vv[c]));
+                ++pos;
+            }
+        run += tot;
+    }
+}
+
+__global__ void gs_close(unsigned long long* t_ptr) { atomicAdd(t_ptr, 1ull); }      // one step taken
+
 // ---- the deferred sparse tail of a step, applied in place (when the state must be complete now) --
 // One workgroup per (row, chunk): the neighbours' pairs that fall into the chunk are contiguous in
 // their messages (out_off), so they are accumulated in ascending neighbour order into an LDS copy
@@ -976,6 +1168,7 @@ __global__ void topk_init_rows(TopkRow* rows, int n) {
 struct TopkState {
     Scratch s{};
     int n = 0;
+    bool gspar = false;            // the GSpar operator runs on this state (its own select-free chain of kernels)
     bool pending = false;          // a step has been enqueued since the last flush (or may have been, by a
                                    // replayed graph): its sparse tail may not have been applied yet
 };
@@ -983,7 +1176,7 @@ struct TopkState {
 void topk_destroy(TopkState* st) {
     if (!st) return;
     void* ptrs[] = {st->s.hist, st->s.hist2, st->s.hist3, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slot_val, st->s.slot_idx,
-                    st->s.list};
+                    st->s.list, st->s.csum, st->s.gs_overflow};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     delete st;
@@ -992,6 +1185,7 @@ void topk_destroy(TopkState* st) {
 ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::string& err) {
     TopkState* st = new TopkState();
     st->n = cfg.n;
+    st->gspar = cfg.comp.kind == DS_COMP_GSPAR;
     Scratch& s = st->s;
     s.nchunks = (uint32_t)((cfg.N + TK_CHUNK - 1) / TK_CHUNK);
     // the first pass reads and writes whole chunks of x and delta
@@ -1008,12 +1202,15 @@ ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::s
               hipMalloc(&s.cand_cnt, n * nc * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.slot_val, n * nc * TK_CAP * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.slot_idx, n * nc * TK_CAP * sizeof(uint16_t)) == hipSuccess &&
-              hipMalloc(&s.list, n * TK_LIST_CAP * sizeof(uint2)) == hipSuccess;
+              hipMalloc(&s.list, n * TK_LIST_CAP * sizeof(uint2)) == hipSuccess &&
+              hipMalloc(&s.csum, (st->gspar ? n * nc : 1) * sizeof(double)) == hipSuccess &&
+              hipMalloc(&s.gs_overflow, sizeof(uint32_t)) == hipSuccess;
     ok = ok && hipMemset(s.hist, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.hist2, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.hist3, 0, n * BINS3 * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.out_off, 0, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
-         hipMemset(s.cand_cnt, 0, n * nc * sizeof(uint32_t)) == hipSuccess;
+         hipMemset(s.cand_cnt, 0, n * nc * sizeof(uint32_t)) == hipSuccess &&
+         hipMemset(s.gs_overflow, 0, sizeof(uint32_t)) == hipSuccess;
     if (ok) {
         hipLaunchKernelGGL(topk_init_rows, dim3((cfg.n + 63) / 64), dim3(64), 0, 0, s.rows, cfg.n);
         ok = hipDeviceSynchronize() == hipSuccess;
@@ -1050,9 +1247,28 @@ ds_status topk_flush(TopkState* st, const TopkArgs& a, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
 }
 
+ds_status gspar_overflowed(TopkState* st, hipStream_t stream, bool* overflowed) {
+    uint32_t flag = 0;
+    if (hipStreamSynchronize(stream) != hipSuccess) return DS_EHIP;
+    if (hipMemcpy(&flag, st->s.gs_overflow, sizeof(flag), hipMemcpyDeviceToHost) != hipSuccess) return DS_EHIP;
+    *overflowed = flag != 0;
+    return DS_OK;
+}
+
 ds_status topk_step(TopkState* st, const TopkArgs& a, hipStream_t stream) {
     const Scratch& s = st->s;
     const dim3 grid(s.nchunks, a.n), block(TK_THREADS), rblock(TK_RTHREADS);
+    if (st->gspar) {
+        // form (tail of the last step, line 5, sums of |v|) -> lambda -> decisions and counts -> offsets -> pairs
+        hipLaunchKernelGGL(topk_form_collect<true>, grid, block, 0, stream, a, s);
+        hipLaunchKernelGGL(gs_row_lambda, dim3(a.n), rblock, 0, stream, s, (double)a.k_expected);
+        hipLaunchKernelGGL(gs_count, grid, block, 0, stream, a, s);
+        hipLaunchKernelGGL(gs_scan, dim3(a.n), rblock, 0, stream, a, s);
+        hipLaunchKernelGGL(gs_write, grid, block, 0, stream, a, s);
+        hipLaunchKernelGGL(gs_close, dim3(1), dim3(1), 0, stream, a.t_ptr);
+        st->pending = true;
+        return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
+    }
     const dim3 wgrid((s.nchunks + TK_WPW - 1) / TK_WPW, a.n);
     // full mode walks a row's chunks with a fixed number of workgroups, so that a step in which no row needs it
     // pays little for the launches
@@ -1061,7 +1277,7 @@ ds_status topk_step(TopkState* st, const TopkArgs& a, hipStream_t stream) {
     const dim3 rows(a.n);
     const uint32_t k = (uint32_t)a.k;
     // after a flush (and at the start) all message offsets are zero, so the first pass finds no tail to apply
-    hipLaunchKernelGGL(topk_form_collect, grid, block, 0, stream, a, s);
+    hipLaunchKernelGGL(topk_form_collect<false>, grid, block, 0, stream, a, s);
     hipLaunchKernelGGL(topk_decide_select, rows, block, 0, stream, s, k);
     hipLaunchKernelGGL(topk_hist_cand2, hgrid, hblock, 0, stream, s);
     hipLaunchKernelGGL(topk_select2_cand, rows, block, 0, stream, s);

@@ -17,7 +17,7 @@ from typing import Optional, Tuple
 
 import numpy as np
 
-KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE = 0, 1, 2, 3, 4, 5
+KIND_IDENTITY, KIND_QUANT_MAXABS, KIND_SIGN_MEANABS, KIND_TOPK, KIND_QUANT_L2NORM, KIND_RAND_SPARSE, KIND_GSPAR = 0, 1, 2, 3, 4, 5, 6
 TOPO_RING, TOPO_TORUS2D, TOPO_CSR = 0, 1, 2
 ALGO_DEEPSQUEEZE, ALGO_DCD_PSGD, ALGO_CHOCO_SGD = 0, 1, 2       # ds_algorithm
 
@@ -45,7 +45,7 @@ class Config:
 
     def scaled(self, N: int, steps: Optional[int] = None) -> "Config":
         """Same workload at another vector length (k follows as 1 % of N for top-k)."""
-        k = max(1, N // 100) if self.kind in (KIND_TOPK, KIND_RAND_SPARSE) else 0
+        k = max(1, N // 100) if self.kind in (KIND_TOPK, KIND_RAND_SPARSE, KIND_GSPAR) else 0
         return replace(self, N=N, k=k, steps=self.steps if steps is None else steps,
                        name=f"{self.name}@N={N}")
 
@@ -89,6 +89,8 @@ def extra_configs():
         replace(c[1], name="x9_choco_ring16_q2b1024_resnet18", algo=ALGO_CHOCO_SGD),
         replace(c[3], name="x10_dcd_torus8x8_q4b512", algo=ALGO_DCD_PSGD),
         replace(c[3], name="x11_choco_torus8x8_q4b512", algo=ALGO_CHOCO_SGD),
+        Config("x12_ring32_gspar1pct_resnet50", n=32, N=25_557_032, topo=TOPO_RING, kind=KIND_GSPAR,
+               k=25_557_032 // 100, gamma=0.05, eta=0.2, steps=50, grad="normal", grad_scale=1e-3),
     ]
 
 

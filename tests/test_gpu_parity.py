@@ -180,9 +180,19 @@ SMALL = [
     small(wl.KIND_QUANT_MAXABS, 5, 2048 * 2 + 100, bits=8, block=2048),
     small(wl.KIND_QUANT_L2NORM, 8, 4096 * 2 + 37, bits=8),
 ]
+SMALL_GSPAR = [
+    small(wl.KIND_GSPAR, 8, 30_011, k=300),                                          # magnitude-proportional sparsifier
+    small(wl.KIND_GSPAR, 32, 8192 * 2 + 5, k=163),
+    small(wl.KIND_GSPAR, 3, 5, k=1),
+    small(wl.KIND_GSPAR, 4, 9000, k=9000),                                           # k = N: most p_j are cut off at 1
+    small(wl.KIND_GSPAR, 5, 4096 * 3, k=4000),                                       # more kept per chunk than a slot holds
+    small(wl.KIND_GSPAR, 16, 20_000, k=200, topo=wl.TOPO_TORUS2D, torus=(4, 4)),
+    small(wl.KIND_GSPAR, 3, 1, k=1),
+    small(wl.KIND_GSPAR, 3, 4096 * 1030 + 3, k=40_000),                              # > 1024 chunks: 2 tree leaves per thread
+]
 
 
-@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+@pytest.mark.parametrize("w", SMALL + SMALL_GSPAR, ids=lambda w: w.name)
 def test_lock_step_small_shapes(w):
     say("case", w.name)
     lock_step(w, steps=3)
@@ -596,6 +606,7 @@ def test_two_handles_interleaved():
                                small(wl.KIND_TOPK, 8, 30_011, k=300),
                                small(wl.KIND_QUANT_L2NORM, 8, 4096 * 5 + 11, bits=2),
                                small(wl.KIND_RAND_SPARSE, 8, 20_000, k=1500),
+                               small(wl.KIND_GSPAR, 8, 20_000, k=1500),
                                replace(small(wl.KIND_QUANT_MAXABS, 8, 512 * 9 + 37, bits=2, block=512), algo=wl.ALGO_DCD_PSGD, name="dcd_graph"),
                                replace(small(wl.KIND_SIGN_MEANABS, 8, 256 * 9 + 37, block=256), algo=wl.ALGO_CHOCO_SGD, name="choco_graph")],
                          ids=lambda w: w.name)
@@ -693,6 +704,28 @@ def test_l2norm_speculative_codes_steady_state(bits, grad):
     x, d = ds.ds_read_state()
     assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
     ds.ds_destroy()
+
+
+def test_gspar_free_runs_messages_every_step():
+    """GSpar without anything read back in between: every step's tail goes through the next step's first pass, a
+    shorter message clears what the longer one before it left behind; heavy-tailed gradients cut some p_j off at 1."""
+    for w in (small(wl.KIND_GSPAR, 8, 4096 * 6 + 1001, k=700, grad="quadratic"),
+              small(wl.KIND_GSPAR, 9, 50_021, k=2500, grad="student_t3", topo=wl.TOPO_TORUS2D, torus=(3, 3))):
+        ds = b.DeepSqueeze.from_workload(w)
+        st = oracle_state(w)
+        c = wl.centres(w) if w.grad == "quadratic" else None
+        counts = []
+        for t in range(10):
+            g = wl.gradient(w, t, st.x, c)
+            ds.ds_step(upload(g))
+            _, msg = oracle.step(st, g, want_cv=False)
+            got = ds.ds_read_messages()
+            assert np.array_equal(got, msg), f"{w.name} step {t}: messages differ in {int((got != msg).sum())} bytes"
+            counts.append(int(np.frombuffer(msg[:4].tobytes(), np.uint32)[0]))
+        assert len(set(counts)) > 1                                  # the count moves, so stale pairs had to be cleared
+        x, d = ds.ds_read_state()
+        assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
+        ds.ds_destroy()
 
 
 def test_l2norm_worked_example_and_zero_rows_on_gpu(golden_dir):
