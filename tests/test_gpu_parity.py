@@ -966,7 +966,7 @@ def test_block_configs_full_size_one_step(idx):
     assert nb == 0
 
 
-def _full_size_free_run(w, idx, steps, t0=3):
+def _full_size_free_run(w, idx, steps, t0=3, all_cores=False):
     """`steps` iterations at full size with no state rewrite in between (so deferred tails, double-buffered
     messages and counts carried from one step to the next all go through their steady-state code), from a
     seeded non-zero state; messages are compared after every step, the whole state at the end."""
@@ -984,7 +984,7 @@ def _full_size_free_run(w, idx, steps, t0=3):
         gm = ds.ds_read_messages()                           # does not touch x or delta: the run stays free
         g_host = np.ascontiguousarray(g[:, :w.N].cpu().numpy())
         say("case", w.name, "oracle step", t)
-        _, om = oracle.step(st, g_host, want_cv=False)
+        _, om = oracle.step(st, g_host, want_cv=False, all_cores=all_cores)
         assert np.array_equal(gm, om), f"step {t}: {int((gm != om).sum())} message bytes differ"
         del gm, om, g_host
     assert pitch == g.shape[1]
@@ -1012,6 +1012,14 @@ def test_rand_sparse_full_size_two_free_steps():
     _full_size_free_run(wl.extra_configs()[2], 7, steps=2)
 
 
+def test_gspar_full_size_two_free_steps():
+    """GSpar at the size bench.py --config 12 times (32 x 25.56 M, 1 % expected): more than 1024 chunks per row (the
+    sum tree and the offset scan walk several chunks per thread), the second step applies the first one's tail in
+    its first pass.  The oracle runs all 32 rows (the mask's random words are addressed by the worker's number, so
+    sampled sub-rings would not see the same words), on all host cores: the same bits as on one (pinned)."""
+    _full_size_free_run(wl.extra_configs()[7], 12, steps=2, all_cores=True)
+
+
 def test_l2norm_full_size_steady_state():
     """The norm-rescaled compressor at the size bench.py --config 6 times (16 x 11.17 M, 2 bits): seven steps in a row
     with nothing read back or rewritten in between, so every tail goes through the next step's first pass, the
@@ -1034,7 +1042,7 @@ def test_l2norm_full_size_steady_state():
         fast.append(ds.ds_topk_candidate_rows())
         g_host = np.ascontiguousarray(g[:, :w.N].cpu().numpy())
         say("case", w.name, "oracle step", t, "rows on the speculative path so far", fast)
-        _, om = oracle.step(st, g_host, want_cv=False)
+        _, om = oracle.step(st, g_host, want_cv=False, all_cores=all_cores)
         assert np.array_equal(gm, om), f"step {t}: {int((gm != om).sum())} message bytes differ"
         del gm, om, g_host
     assert fast[0] == 0 and fast[-1] == w.n and fast[-2] >= w.n - 2, fast       # the written state takes a few steps to settle
