@@ -79,6 +79,8 @@ struct TopkRow {
     uint32_t list_count;       //                 elements of that bin listed so far by topk_bin_collect
     float drift_prev;          // last step's movement of |tau| as a float (for the forecast of the next threshold)
     float lambda;              // GSpar: this step's k / sum |v|
+    float lambda_hi;           // GSpar: the upper bound the NEXT first pass collects with (0: none)
+    uint32_t gs_mode;          // GSpar: 1 = this step's kept elements are among those its first pass collected
     uint32_t gs_total;         // GSpar: pairs in the row's last message (what a shorter message must clear behind it)
 };
 
@@ -165,6 +167,75 @@ __device__ __forceinline__ uint32_t row_exclusive_scan(uint32_t v, uint32_t* wav
     return base + inc - v;
 }
 
+constexpr uint32_t kGsparStreamTag = 0x47535052u;            // GSpar: 4th counter word of the mask's random stream
+
+// The keep decisions of four adjacent columns of worker `row`.
+__device__ __forceinline__ uint32_t gs_keep4(const TopkArgs& a, int row, uint64_t j, uint32_t t_lo, float lambda, const float4& v) {
+    uint32_t rnd[4];
+    philox4x32_10((uint32_t)(j >> 2), (uint32_t)row, t_lo, kGsparStreamTag, a.seed_lo, a.seed_hi, rnd);
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+    uint32_t keep = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float p = lambda * fabsf(vv[c]);
+        const float u = (float)(rnd[c] >> 8) * (1.0f / 16777216.0f);
+        if (j + c < a.N && u < p) keep |= 1u << c;
+    }
+    return keep;
+}
+
+// Exclusive prefix sums of four small counts at once (16 bits each, packed; sums stay below 2^16) over the 256
+// threads of a workgroup; *total receives the packed sums.
+__device__ __forceinline__ unsigned long long block_exclusive_scan4(unsigned long long v, unsigned long long* wave_sums /*[4]*/,
+                                                                    unsigned long long* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long up = __shfl_up(inc, o);
+        if (lane >= o) inc += up;
+    }
+    __syncthreads();                       // wave_sums may still be read from a previous call
+    if (lane == 63) wave_sums[wave] = inc;
+    __syncthreads();
+    unsigned long long base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < TK_THREADS / 64; ++w) {
+        const unsigned long long sm = wave_sums[w];
+        if (w < wave) base += sm;
+        tot += sm;
+    }
+    *total = tot;
+    return base + inc - v;
+}
+
+// The elements of one chunk whose mask bit is set, in column order, into the chunk's slot (the first TK_CAP of
+// them); returns their number.  vin: the lane's four float4 of the chunk, keep: their four 4-bit masks.
+__device__ __forceinline__ uint32_t gs_collect(const float4 (&vin)[TK_ITERS], const uint32_t (&keep)[TK_ITERS], uint32_t* slot_val,
+                                               uint16_t* slot_idx, unsigned long long* wave_sums) {
+    unsigned long long packed = 0;
+#pragma unroll
+    for (int it = 0; it < TK_ITERS; ++it) packed |= (unsigned long long)__popc(keep[it]) << (16 * it);
+    unsigned long long tot;
+    const unsigned long long before = block_exclusive_scan4(packed, wave_sums, &tot);
+    uint32_t run = 0;
+#pragma unroll
+    for (int it = 0; it < TK_ITERS; ++it) {
+        const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
+        uint32_t pos = run + (uint32_t)((before >> (16 * it)) & 0xFFFFu);
+        const float vv[4] = {vin[it].x, vin[it].y, vin[it].z, vin[it].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (keep[it] & (1u << c)) {
+                if (pos < (uint32_t)TK_CAP) { slot_val[pos] = __float_as_uint(vv[c]); slot_idx[pos] = (uint16_t)(q0 + c); }
+                ++pos;
+            }
+        run += (uint32_t)((tot >> (16 * it)) & 0xFFFFu);
+    }
+    return run;
+}
+static_assert(TK_ITERS == 4 && TK_THREADS * 4 < 65536, "four 16-bit fields");
+
 __device__ __forceinline__ double wave_tree_sum_f64(double v) {   // adjacent pairs first; every lane gets the sum
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) v += __shfl_xor(v, o);
@@ -178,6 +249,8 @@ template <bool GS>
 __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scratch s) {
     __shared__ float acc[TK_CHUNK];
     [[maybe_unused]] __shared__ double sweep_abs[TK_ITERS * (TK_THREADS / 64)];
+    [[maybe_unused]] __shared__ unsigned long long wave_sums4[TK_THREADS / 64];
+    [[maybe_unused]] float4 gs_v[TK_ITERS];
     __shared__ uint32_t own[TK_CHUNK / 32];       // columns this worker itself sent in the previous step
     __shared__ uint32_t h[TK_H1];                              // level-1 digits of the candidates, relative to tlo's
     __shared__ uint32_t cand_count;
@@ -312,6 +385,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
         if constexpr (GS) {                                    // padding columns hold v = 0
             const double sw = wave_tree_sum_f64(((double)fabsf(v.x) + (double)fabsf(v.y)) + ((double)fabsf(v.z) + (double)fabsf(v.w)));
             if ((threadIdx.x & 63) == 0) sweep_abs[it * (TK_THREADS / 64) + (threadIdx.x >> 6)] = sw;   // sweep index = column order
+            gs_v[it] = v;
             continue;
         }
         const float vv[4] = {v.x, v.y, v.z, v.w};
@@ -326,6 +400,18 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     }
     __syncthreads();
     if constexpr (GS) {
+        // With an upper bound of this step's lambda from the last step, the elements that can be kept at all
+        // (u < lambda_hi |v|, about 1 % of the chunk) go into the slot now, in column order, and the second pass
+        // over v is not needed if the bound holds.
+        const float lambda_hi = s.rows[row].lambda_hi;
+        if (lambda_hi > 0.f) {                                 // uniform
+            const uint32_t t_lo = (uint32_t)*a.t_ptr;
+            uint32_t keep[TK_ITERS];
+#pragma unroll
+            for (int it = 0; it < TK_ITERS; ++it) keep[it] = gs_keep4(a, row, c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x, t_lo, lambda_hi, gs_v[it]);
+            const uint32_t n = gs_collect(gs_v, keep, slot_val, slot_idx, wave_sums4);
+            if (threadIdx.x == 0) s.cand_cnt[(size_t)row * s.nchunks + chunk] = n;
+        }
         if (threadIdx.x == 0) {
             double t[16];
 #pragma unroll
@@ -941,7 +1027,6 @@ __global__ void __launch_bounds__(64) topk_write_cand(TopkArgs a, Scratch s) {
 // A row's message is [count, 0][pairs ...]: the header takes the place of pair 0, so the message offsets of the
 // chunks (out_off) start at 1 and the first pass / the flush apply the tail exactly as for top-k.
 static_assert(TK_ITERS * (TK_THREADS / 64) == 16, "the chunk trees are written for 16 sweeps");
-constexpr uint32_t kGsparStreamTag = 0x47535052u;            // 4th counter word of the mask's random stream
 
 // Per row: S = sum |v| (the tree continued over the chunk sums, padded with zeros to a power of two), lambda = k / S.
 __global__ void __launch_bounds__(TK_RTHREADS) gs_row_lambda(Scratch s, double k_expected) {
@@ -972,57 +1057,68 @@ __global__ void __launch_bounds__(TK_RTHREADS) gs_row_lambda(Scratch s, double k
         for (int len = 16; len > 1; len >>= 1)
 #pragma unroll
             for (int q = 0; q < len / 2; ++q) t[q] = t[2 * q] + t[2 * q + 1];
-        s.rows[row].lambda = (t[0] > 0.0) ? (float)(k_expected / t[0]) : 0.f;
+        const float lambda = (t[0] > 0.0) ? (float)(k_expected / t[0]) : 0.f;
+        const float used = s.rows[row].lambda_hi;              // what this step's first pass collected with (0: nothing)
+        s.rows[row].lambda = lambda;
+        s.rows[row].gs_mode = (used > 0.f && lambda <= used) ? 1u : 0u;
+        // sum |v| of 10^5 .. 10^8 elements moves by a fraction of a per cent per step: 5 % of room costs 5 % more
+        // slot entries to sift and is missed only when the state is replaced from outside
+        s.rows[row].lambda_hi = (lambda > 0.f && lambda < 1.0e30f) ? lambda * 1.05f : 0.f;
     }
 }
 static_assert(TK_RTHREADS / 64 == 16, "the wave tree above is written for 16 waves");
 
-// The keep decisions of four adjacent columns of worker `row`.
-__device__ __forceinline__ uint32_t gs_keep4(const TopkArgs& a, int row, uint64_t j, uint32_t t_lo, float lambda, const float4& v) {
-    uint32_t rnd[4];
-    philox4x32_10((uint32_t)(j >> 2), (uint32_t)row, t_lo, kGsparStreamTag, a.seed_lo, a.seed_hi, rnd);
-    const float vv[4] = {v.x, v.y, v.z, v.w};
-    uint32_t keep = 0;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const float p = lambda * fabsf(vv[c]);
-        const float u = (float)(rnd[c] >> 8) * (1.0f / 16777216.0f);
-        if (j + c < a.N && u < p) keep |= 1u << c;
-    }
-    return keep;
-}
-
-// Per chunk: the kept elements in column order -> the chunk's slot (the first TK_CAP of them) and their number.
+// Per chunk: the kept elements in column order -> the chunk's slot and their number.  A row whose first pass
+// collected with an upper bound of lambda that held (gs_mode) only sifts what that pass left in the slot -- the
+// elements with u < lambda_hi |v|, a superset in column order -- unless the chunk had more of them than a slot
+// holds; everything else decides from v itself.
 __global__ void __launch_bounds__(TK_THREADS) gs_count(TopkArgs a, Scratch s) {
+    __shared__ unsigned long long wave_sums4[TK_THREADS / 64];
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
     const uint32_t chunk = blockIdx.x;
     const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
     const float lambda = s.rows[row].lambda;
     const uint32_t t_lo = (uint32_t)*a.t_ptr;
+    const size_t slot = (size_t)row * s.nchunks + chunk;
+    uint32_t* slot_val = s.slot_val + slot * TK_CAP;
+    uint16_t* slot_idx = s.slot_idx + slot * TK_CAP;
+    const uint32_t have = s.cand_cnt[slot];
+    if (s.rows[row].gs_mode && have <= (uint32_t)TK_CAP) {     // uniform
+        // two consecutive entries per thread, so one scan keeps the column order
+        uint32_t val[2], keep = 0;
+        uint16_t idx[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const uint32_t p = 2 * threadIdx.x + e;
+            if (p < have) {
+                val[e] = slot_val[p];
+                idx[e] = slot_idx[p];
+                const uint64_t j = c0 + idx[e];
+                uint32_t rnd[4];
+                philox4x32_10((uint32_t)(j >> 2), (uint32_t)row, t_lo, kGsparStreamTag, a.seed_lo, a.seed_hi, rnd);
+                const uint32_t word = (j & 3) == 0 ? rnd[0] : (j & 3) == 1 ? rnd[1] : (j & 3) == 2 ? rnd[2] : rnd[3];
+                const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
+                if (u < lambda * fabsf(__uint_as_float(val[e]))) keep |= 1u << e;
+            }
+        }
+        uint32_t tot;
+        uint32_t pos = block_exclusive_scan(__popc(keep), wave_sums, &tot);    // its barriers separate the reads from the writes
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+            if (keep & (1u << e)) { slot_val[pos] = val[e]; slot_idx[pos] = idx[e]; ++pos; }
+        if (threadIdx.x == 0) s.cnt_gt[slot] = tot;
+        return;
+    }
     const float* dr = a.delta + (uint64_t)row * a.ld;         // holds v
-    uint32_t* slot_val = s.slot_val + ((size_t)row * s.nchunks + chunk) * TK_CAP;
-    uint16_t* slot_idx = s.slot_idx + ((size_t)row * s.nchunks + chunk) * TK_CAP;
     float4 vin[TK_ITERS];
+    uint32_t keep[TK_ITERS];
 #pragma unroll
     for (int it = 0; it < TK_ITERS; ++it) vin[it] = ld4_stream(dr + c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x);   // rows are padded to whole chunks
-    uint32_t run = 0;
 #pragma unroll
-    for (int it = 0; it < TK_ITERS; ++it) {
-        const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
-        const uint32_t keep = gs_keep4(a, row, c0 + q0, t_lo, lambda, vin[it]);
-        uint32_t tot;
-        uint32_t pos = run + block_exclusive_scan(__popc(keep), wave_sums, &tot);
-        const float vv[4] = {vin[it].x, vin[it].y, vin[it].z, vin[it].w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (keep & (1u << c)) {
-                if (pos < (uint32_t)TK_CAP) { slot_val[pos] = __float_as_uint(vv[c]); slot_idx[pos] = (uint16_t)(q0 + c); }
-                ++pos;
-            }
-        run += tot;
-    }
-    if (threadIdx.x == 0) s.cnt_gt[(size_t)row * s.nchunks + chunk] = run;
+    for (int it = 0; it < TK_ITERS; ++it) keep[it] = gs_keep4(a, row, c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x, t_lo, lambda, vin[it]);
+    const uint32_t n = gs_collect(vin, keep, slot_val, slot_idx, wave_sums4);
+    if (threadIdx.x == 0) s.cnt_gt[slot] = n;
 }
 
 // Per row: where each chunk's pairs go in the message (offsets in pairs from the start of the row, the header
@@ -1229,7 +1325,7 @@ ds_status topk_candidate_rows(TopkState* st, hipStream_t stream, uint32_t* count
     if (hipStreamSynchronize(stream) != hipSuccess) return DS_EHIP;
     if (hipMemcpy(rows.data(), st->s.rows, rows.size() * sizeof(TopkRow), hipMemcpyDeviceToHost) != hipSuccess) return DS_EHIP;
     uint32_t c = 0;
-    for (const TopkRow& r : rows) c += r.cand_mode ? 1u : 0u;
+    for (const TopkRow& r : rows) c += (st->gspar ? r.gs_mode : r.cand_mode) ? 1u : 0u;
     *count = c;
     return DS_OK;
 }

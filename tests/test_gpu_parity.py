@@ -714,7 +714,7 @@ def test_gspar_free_runs_messages_every_step():
         ds = b.DeepSqueeze.from_workload(w)
         st = oracle_state(w)
         c = wl.centres(w) if w.grad == "quadratic" else None
-        counts = []
+        counts, fast = [], []
         for t in range(10):
             g = wl.gradient(w, t, st.x, c)
             ds.ds_step(upload(g))
@@ -722,7 +722,11 @@ def test_gspar_free_runs_messages_every_step():
             got = ds.ds_read_messages()
             assert np.array_equal(got, msg), f"{w.name} step {t}: messages differ in {int((got != msg).sum())} bytes"
             counts.append(int(np.frombuffer(msg[:4].tobytes(), np.uint32)[0]))
+            fast.append(ds.ds_topk_candidate_rows())
         assert len(set(counts)) > 1                                  # the count moves, so stale pairs had to be cleared
+        # from the second step on the first pass collects under an upper bound of lambda and the bound holds
+        say(w.name, "rows whose first pass collected the kept elements:", fast)
+        assert fast[0] == 0 and sum(fast[-5:]) >= 5 * w.n - 2, fast
         x, d = ds.ds_read_state()
         assert assert_close("x", x, st.x) + assert_close("delta", d, st.delta) == 0
         ds.ds_destroy()
