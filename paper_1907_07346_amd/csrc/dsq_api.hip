@@ -441,7 +441,7 @@ ds_status ds_init_ex(const ds_config* cfg, const ds_plan_request* plan, char* er
     const bool sparse_pairs = cfg->comp.kind == DS_COMP_TOPK || cfg->comp.kind == DS_COMP_GSPAR;   // (column, value) messages
     const bool tiled = !sparse_pairs && cfg->comp.kind != DS_COMP_QUANT_L2NORM;
     if (cfg->comp.kind == DS_COMP_GSPAR) {
-        h->plan_name = "gspar/count-scan-write";
+        h->plan_name = "gspar/sift-scan-write";
     } else if (cfg->comp.kind == DS_COMP_TOPK) {
         h->plan_name = "topk/radix-select";
     } else if (cfg->comp.kind == DS_COMP_QUANT_L2NORM) {

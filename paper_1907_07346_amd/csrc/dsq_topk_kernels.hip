@@ -1068,57 +1068,76 @@ __global__ void __launch_bounds__(TK_RTHREADS) gs_row_lambda(Scratch s, double k
 }
 static_assert(TK_RTHREADS / 64 == 16, "the wave tree above is written for 16 waves");
 
-// Per chunk: the kept elements in column order -> the chunk's slot and their number.  A row whose first pass
-// collected with an upper bound of lambda that held (gs_mode) only sifts what that pass left in the slot -- the
-// elements with u < lambda_hi |v|, a superset in column order -- unless the chunk had more of them than a slot
-// holds; everything else decides from v itself.
-__global__ void __launch_bounds__(TK_THREADS) gs_count(TopkArgs a, Scratch s) {
-    __shared__ unsigned long long wave_sums4[TK_THREADS / 64];
-    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+// Per chunk, one wave each: a row whose first pass collected with an upper bound of lambda that held (gs_mode)
+// only sifts what that pass left in the slot -- the elements with u < lambda_hi |v|, a superset of the kept ones
+// in column order -- and closes the gaps in place.  Chunks with more of them than a slot holds, and rows without a
+// bound that held, are left to gs_count_dense.
+constexpr int GS_WAVES = 4;                                   // chunks per workgroup
+__device__ __forceinline__ bool gs_chunk_is_sifted(const Scratch& s, int row, size_t slot) {
+    return s.rows[row].gs_mode && s.cand_cnt[slot] <= (uint32_t)TK_CAP;
+}
+__global__ void __launch_bounds__(GS_WAVES * 64) gs_sift(TopkArgs a, Scratch s) {
     const int row = blockIdx.y;
-    const uint32_t chunk = blockIdx.x;
+    const uint32_t chunk = blockIdx.x * GS_WAVES + (threadIdx.x >> 6);
+    if (chunk >= s.nchunks) return;
+    const size_t slot = (size_t)row * s.nchunks + chunk;
+    if (!gs_chunk_is_sifted(s, row, slot)) return;             // uniform over the wave
+    const int lane = threadIdx.x & 63;
     const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
     const float lambda = s.rows[row].lambda;
     const uint32_t t_lo = (uint32_t)*a.t_ptr;
-    const size_t slot = (size_t)row * s.nchunks + chunk;
     uint32_t* slot_val = s.slot_val + slot * TK_CAP;
     uint16_t* slot_idx = s.slot_idx + slot * TK_CAP;
     const uint32_t have = s.cand_cnt[slot];
-    if (s.rows[row].gs_mode && have <= (uint32_t)TK_CAP) {     // uniform
-        // two consecutive entries per thread, so one scan keeps the column order
-        uint32_t val[2], keep = 0;
-        uint16_t idx[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const uint32_t p = 2 * threadIdx.x + e;
-            if (p < have) {
-                val[e] = slot_val[p];
-                idx[e] = slot_idx[p];
-                const uint64_t j = c0 + idx[e];
-                uint32_t rnd[4];
-                philox4x32_10((uint32_t)(j >> 2), (uint32_t)row, t_lo, kGsparStreamTag, a.seed_lo, a.seed_hi, rnd);
-                const uint32_t word = (j & 3) == 0 ? rnd[0] : (j & 3) == 1 ? rnd[1] : (j & 3) == 2 ? rnd[2] : rnd[3];
-                const float u = (float)(word >> 8) * (1.0f / 16777216.0f);
-                if (u < lambda * fabsf(__uint_as_float(val[e]))) keep |= 1u << e;
-            }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    uint32_t kept = 0;
+    for (uint32_t p0 = 0; p0 < have; p0 += 64) {               // a kept entry moves to a place at or before its own,
+        const uint32_t p = p0 + lane;                          // which this or an earlier round has already read
+        uint32_t val = 0;
+        uint16_t idx = 0;
+        bool keep = false;
+        if (p < have) {
+            val = slot_val[p];
+            idx = slot_idx[p];
+            const uint64_t j = c0 + idx;
+            uint32_t rnd[4];
+            philox4x32_10((uint32_t)(j >> 2), (uint32_t)row, t_lo, kGsparStreamTag, a.seed_lo, a.seed_hi, rnd);
+            const uint32_t word = (j & 3) == 0 ? rnd[0] : (j & 3) == 1 ? rnd[1] : (j & 3) == 2 ? rnd[2] : rnd[3];
+            keep = (float)(word >> 8) * (1.0f / 16777216.0f) < lambda * fabsf(__uint_as_float(val));
         }
-        uint32_t tot;
-        uint32_t pos = block_exclusive_scan(__popc(keep), wave_sums, &tot);    // its barriers separate the reads from the writes
-#pragma unroll
-        for (int e = 0; e < 2; ++e)
-            if (keep & (1u << e)) { slot_val[pos] = val[e]; slot_idx[pos] = idx[e]; ++pos; }
-        if (threadIdx.x == 0) s.cnt_gt[slot] = tot;
-        return;
+        const unsigned long long m = __ballot(keep);
+        if (keep) {
+            const uint32_t pos = kept + (uint32_t)__popcll(m & below);
+            slot_val[pos] = val;
+            slot_idx[pos] = idx;
+        }
+        kept += (uint32_t)__popcll(m);
     }
+    if (lane == 0) s.cnt_gt[slot] = kept;
+}
+
+// The chunks gs_sift left out: decisions from v itself, the kept elements in column order into the slot (the first
+// TK_CAP of them), their number.  A fixed number of workgroups per row walks the chunks, so that a step in which
+// every chunk was sifted pays little for the launch.
+__global__ void __launch_bounds__(TK_THREADS) gs_count_dense(TopkArgs a, Scratch s) {
+    __shared__ unsigned long long wave_sums4[TK_THREADS / 64];
+    const int row = blockIdx.y;
+    const float lambda = s.rows[row].lambda;
+    const uint32_t t_lo = (uint32_t)*a.t_ptr;
     const float* dr = a.delta + (uint64_t)row * a.ld;         // holds v
-    float4 vin[TK_ITERS];
-    uint32_t keep[TK_ITERS];
+    for (uint32_t chunk = blockIdx.x; chunk < s.nchunks; chunk += gridDim.x) {
+        const size_t slot = (size_t)row * s.nchunks + chunk;
+        if (gs_chunk_is_sifted(s, row, slot)) continue;        // uniform
+        const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+        float4 vin[TK_ITERS];
+        uint32_t keep[TK_ITERS];
 #pragma unroll
-    for (int it = 0; it < TK_ITERS; ++it) vin[it] = ld4_stream(dr + c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x);   // rows are padded to whole chunks
+        for (int it = 0; it < TK_ITERS; ++it) vin[it] = ld4_stream(dr + c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x);   // rows are padded to whole chunks
 #pragma unroll
-    for (int it = 0; it < TK_ITERS; ++it) keep[it] = gs_keep4(a, row, c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x, t_lo, lambda, vin[it]);
-    const uint32_t n = gs_collect(vin, keep, slot_val, slot_idx, wave_sums4);
-    if (threadIdx.x == 0) s.cnt_gt[slot] = n;
+        for (int it = 0; it < TK_ITERS; ++it) keep[it] = gs_keep4(a, row, c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x, t_lo, lambda, vin[it]);
+        const uint32_t n = gs_collect(vin, keep, s.slot_val + slot * TK_CAP, s.slot_idx + slot * TK_CAP, wave_sums4);
+        if (threadIdx.x == 0) s.cnt_gt[slot] = n;
+    }
 }
 
 // Per row: where each chunk's pairs go in the message (offsets in pairs from the start of the row, the header
@@ -1152,41 +1171,53 @@ __global__ void __launch_bounds__(TK_RTHREADS) gs_scan(TopkArgs a, Scratch s) {
     }
 }
 
-// Per chunk: the slot's pairs to their place in the message; a chunk that kept more than its slot holds decides again.
-__global__ void __launch_bounds__(TK_THREADS) gs_write(TopkArgs a, Scratch s) {
-    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+// Per chunk, one wave each: the slot's pairs to their place in the message.  Chunks that kept more than a slot
+// holds are left to gs_write_dense.
+__global__ void __launch_bounds__(GS_WAVES * 64) gs_write(TopkArgs a, Scratch s) {
     const int row = blockIdx.y;
-    const uint32_t chunk = blockIdx.x;
+    const uint32_t chunk = blockIdx.x * GS_WAVES + (threadIdx.x >> 6);
+    if (chunk >= s.nchunks) return;
+    const size_t slot = (size_t)row * s.nchunks + chunk;
+    const uint32_t cnt = s.cnt_gt[slot];
+    if (cnt > (uint32_t)TK_CAP) return;                        // uniform over the wave
     const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
-    const uint32_t cnt = s.cnt_gt[(size_t)row * s.nchunks + chunk];
     const uint32_t limit = (uint32_t)a.k;                     // pair positions of the row: [1, limit)
     const uint32_t base = s.out_off[(size_t)row * (s.nchunks + 1) + chunk];
     uint2* mrow = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
-    if (cnt <= (uint32_t)TK_CAP) {                            // uniform
-        const uint32_t* slot_val = s.slot_val + ((size_t)row * s.nchunks + chunk) * TK_CAP;
-        const uint16_t* slot_idx = s.slot_idx + ((size_t)row * s.nchunks + chunk) * TK_CAP;
-        for (uint32_t p = threadIdx.x; p < cnt; p += TK_THREADS)
-            if (base + p < limit) mrow[base + p] = make_uint2((uint32_t)(c0 + slot_idx[p]), slot_val[p]);
-        return;
-    }
+    const uint32_t* slot_val = s.slot_val + slot * TK_CAP;
+    const uint16_t* slot_idx = s.slot_idx + slot * TK_CAP;
+    for (uint32_t p = threadIdx.x & 63; p < cnt; p += 64)
+        if (base + p < limit) mrow[base + p] = make_uint2((uint32_t)(c0 + slot_idx[p]), slot_val[p]);
+}
+
+// The chunks that kept more than a slot holds decide again from v and write their pairs directly.
+__global__ void __launch_bounds__(TK_THREADS) gs_write_dense(TopkArgs a, Scratch s) {
+    __shared__ uint32_t wave_sums[TK_THREADS / 64];
+    const int row = blockIdx.y;
+    const uint32_t limit = (uint32_t)a.k;
+    uint2* mrow = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
     const float lambda = s.rows[row].lambda;
     const uint32_t t_lo = (uint32_t)*a.t_ptr;                 // the step's counter: advanced only after this kernel
     const float* dr = a.delta + (uint64_t)row * a.ld;
-    uint32_t run = base;
-    for (int it = 0; it < TK_ITERS; ++it) {
-        const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
-        const float4 v = ld4_stream(dr + c0 + q0);
-        const uint32_t keep = gs_keep4(a, row, c0 + q0, t_lo, lambda, v);
-        uint32_t tot;
-        uint32_t pos = run + block_exclusive_scan(__popc(keep), wave_sums, &tot);
-        const float vv[4] = {v.x, v.y, v.z, v.w};
+    for (uint32_t chunk = blockIdx.x; chunk < s.nchunks; chunk += gridDim.x) {
+        if (s.cnt_gt[(size_t)row * s.nchunks + chunk] <= (uint32_t)TK_CAP) continue;    // uniform
+        const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
+        uint32_t run = s.out_off[(size_t)row * (s.nchunks + 1) + chunk];
+        for (int it = 0; it < TK_ITERS; ++it) {
+            const uint32_t q0 = (uint32_t)it * TK_VEC + 4 * threadIdx.x;
+            const float4 v = ld4_stream(dr + c0 + q0);
+            const uint32_t keep = gs_keep4(a, row, c0 + q0, t_lo, lambda, v);
+            uint32_t tot;
+            uint32_t pos = run + block_exclusive_scan(__popc(keep), wave_sums, &tot);
+            const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (keep & (1u << c)) {
-                if (pos < limit) mrow[pos] = make_uint2((uint32_t)(c0 + q0 + c), __float_as_uint(vv[c]));
-                ++pos;
-            }
-        run += tot;
+            for (int c = 0; c < 4; ++c)
+                if (keep & (1u << c)) {
+                    if (pos < limit) mrow[pos] = make_uint2((uint32_t)(c0 + q0 + c), __float_as_uint(vv[c]));
+                    ++pos;
+                }
+            run += tot;
+        }
     }
 }
 
@@ -1355,12 +1386,17 @@ ds_status topk_step(TopkState* st, const TopkArgs& a, hipStream_t stream) {
     const Scratch& s = st->s;
     const dim3 grid(s.nchunks, a.n), block(TK_THREADS), rblock(TK_RTHREADS);
     if (st->gspar) {
-        // form (tail of the last step, line 5, sums of |v|) -> lambda -> decisions and counts -> offsets -> pairs
+        // form (tail of the last step, line 5, sums of |v|, what can be kept at all) -> lambda -> kept elements and
+        // their number per chunk -> offsets -> pairs
         hipLaunchKernelGGL(topk_form_collect<true>, grid, block, 0, stream, a, s);
         hipLaunchKernelGGL(gs_row_lambda, dim3(a.n), rblock, 0, stream, s, (double)a.k_expected);
-        hipLaunchKernelGGL(gs_count, grid, block, 0, stream, a, s);
+        const dim3 wgrid((s.nchunks + GS_WAVES - 1) / GS_WAVES, a.n), wblock(GS_WAVES * 64);
+        const dim3 dgrid(s.nchunks < (uint32_t)TK_FWG ? s.nchunks : (uint32_t)TK_FWG, a.n);
+        hipLaunchKernelGGL(gs_sift, wgrid, wblock, 0, stream, a, s);
+        hipLaunchKernelGGL(gs_count_dense, dgrid, block, 0, stream, a, s);
         hipLaunchKernelGGL(gs_scan, dim3(a.n), rblock, 0, stream, a, s);
-        hipLaunchKernelGGL(gs_write, grid, block, 0, stream, a, s);
+        hipLaunchKernelGGL(gs_write, wgrid, wblock, 0, stream, a, s);
+        hipLaunchKernelGGL(gs_write_dense, dgrid, block, 0, stream, a, s);
         hipLaunchKernelGGL(gs_close, dim3(1), dim3(1), 0, stream, a.t_ptr);
         st->pending = true;
         return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
