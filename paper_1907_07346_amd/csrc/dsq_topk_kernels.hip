@@ -81,6 +81,8 @@ struct TopkRow {
     float lambda;              // GSpar: this step's k / sum |v|
     float lambda_hi;           // GSpar: the upper bound the NEXT first pass collects with (0: none)
     uint32_t gs_mode;          // GSpar: 1 = this step's kept elements are among those its first pass collected
+    uint32_t gs_need_count;    // GSpar: chunks of the row that must decide from v itself (0: gs_count_dense has nothing to do)
+    uint32_t gs_need_write;    // GSpar: chunks that kept more than a slot holds (0: gs_write_dense has nothing to do)
     uint32_t gs_total;         // GSpar: pairs in the row's last message (what a shorter message must clear behind it)
 };
 
@@ -1060,7 +1062,10 @@ __global__ void __launch_bounds__(TK_RTHREADS) gs_row_lambda(Scratch s, double k
         const float lambda = (t[0] > 0.0) ? (float)(k_expected / t[0]) : 0.f;
         const float used = s.rows[row].lambda_hi;              // what this step's first pass collected with (0: nothing)
         s.rows[row].lambda = lambda;
-        s.rows[row].gs_mode = (used > 0.f && lambda <= used) ? 1u : 0u;
+        const uint32_t mode = (used > 0.f && lambda <= used) ? 1u : 0u;
+        s.rows[row].gs_mode = mode;
+        s.rows[row].gs_need_count = mode ? 0u : s.nchunks;     // gs_sift adds the chunks whose slot overflowed
+        s.rows[row].gs_need_write = 0u;                        // gs_count_dense adds the chunks that keep more than a slot
         // sum |v| of 10^5 .. 10^8 elements moves by a fraction of a per cent per step: 5 % of room costs 5 % more
         // slot entries to sift and is missed only when the state is replaced from outside
         s.rows[row].lambda_hi = (lambda > 0.f && lambda < 1.0e30f) ? lambda * 1.05f : 0.f;
@@ -1081,8 +1086,11 @@ __global__ void __launch_bounds__(GS_WAVES * 64) gs_sift(TopkArgs a, Scratch s) 
     const uint32_t chunk = blockIdx.x * GS_WAVES + (threadIdx.x >> 6);
     if (chunk >= s.nchunks) return;
     const size_t slot = (size_t)row * s.nchunks + chunk;
-    if (!gs_chunk_is_sifted(s, row, slot)) return;             // uniform over the wave
     const int lane = threadIdx.x & 63;
+    if (!gs_chunk_is_sifted(s, row, slot)) {                   // uniform over the wave
+        if (s.rows[row].gs_mode && lane == 0) atomicAdd(&s.rows[row].gs_need_count, 1u);
+        return;
+    }
     const uint64_t c0 = (uint64_t)chunk * TK_CHUNK;
     const float lambda = s.rows[row].lambda;
     const uint32_t t_lo = (uint32_t)*a.t_ptr;
@@ -1122,6 +1130,7 @@ __global__ void __launch_bounds__(GS_WAVES * 64) gs_sift(TopkArgs a, Scratch s) 
 __global__ void __launch_bounds__(TK_THREADS) gs_count_dense(TopkArgs a, Scratch s) {
     __shared__ unsigned long long wave_sums4[TK_THREADS / 64];
     const int row = blockIdx.y;
+    if (s.rows[row].gs_need_count == 0u) return;              // every chunk of the row was sifted
     const float lambda = s.rows[row].lambda;
     const uint32_t t_lo = (uint32_t)*a.t_ptr;
     const float* dr = a.delta + (uint64_t)row * a.ld;         // holds v
@@ -1136,7 +1145,10 @@ __global__ void __launch_bounds__(TK_THREADS) gs_count_dense(TopkArgs a, Scratch
 #pragma unroll
         for (int it = 0; it < TK_ITERS; ++it) keep[it] = gs_keep4(a, row, c0 + (uint64_t)it * TK_VEC + 4 * threadIdx.x, t_lo, lambda, vin[it]);
         const uint32_t n = gs_collect(vin, keep, s.slot_val + slot * TK_CAP, s.slot_idx + slot * TK_CAP, wave_sums4);
-        if (threadIdx.x == 0) s.cnt_gt[slot] = n;
+        if (threadIdx.x == 0) {
+            s.cnt_gt[slot] = n;
+            if (n > (uint32_t)TK_CAP) atomicAdd(&s.rows[row].gs_need_write, 1u);
+        }
     }
 }
 
@@ -1194,6 +1206,7 @@ __global__ void __launch_bounds__(GS_WAVES * 64) gs_write(TopkArgs a, Scratch s)
 __global__ void __launch_bounds__(TK_THREADS) gs_write_dense(TopkArgs a, Scratch s) {
     __shared__ uint32_t wave_sums[TK_THREADS / 64];
     const int row = blockIdx.y;
+    if (s.rows[row].gs_need_write == 0u) return;              // no chunk of the row kept more than its slot holds
     const uint32_t limit = (uint32_t)a.k;
     uint2* mrow = reinterpret_cast<uint2*>(a.msg + (uint64_t)row * a.k * 8);
     const float lambda = s.rows[row].lambda;
