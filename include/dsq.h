@@ -281,12 +281,14 @@ ds_status ds_message_ptr(ds_handle* h, void** msg_dev, uint64_t* bytes);
  *   out[3] = bytes of one step's packed messages (= ds_message_bytes) */
 ds_status ds_diagnostics(ds_handle* h, double* out4);
 
-/* Diagnostics for DS_COMP_TOPK and DS_COMP_QUANT_L2NORM: the number of workers whose last ds_step took the
+/* Diagnostics for DS_COMP_TOPK, DS_COMP_GSPAR and DS_COMP_QUANT_L2NORM: the number of workers whose last ds_step took the
  * path that needs no second pass over v.  Top-k: the k largest were found among the candidates collected while
  * forming v, instead of re-reading v (the exact fallback taken on the first step and whenever the threshold
  * guess of the previous step was too high or a candidate slot overflowed).  Norm-rescaled codes: the codes written
  * while forming v under a guessed band for max|v| stood (the band held the real maximum and no slot of undecided
- * elements overflowed), instead of the exact second pass.  Results are identical either way.  Synchronises; 0
+ * elements overflowed), instead of the exact second pass.  GSpar: everything that was kept was among the elements
+ * collected while forming v under an upper bound of lambda taken from the step before.  Results are identical
+ * either way.  Synchronises; 0
  * for other compressors; DS_ESTATE before the first step. */
 ds_status ds_topk_candidate_rows(ds_handle* h, uint32_t* count);
 

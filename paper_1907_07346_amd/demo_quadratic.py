@@ -72,6 +72,7 @@ def main():
         ("sign, blocks of 256", wl.KIND_SIGN_MEANABS, 0.2, dict(block=256)),
         ("top 1 %", wl.KIND_TOPK, 0.2, dict(k=max(1, N // 100))),
         ("random 10 %", wl.KIND_RAND_SPARSE, 0.2, dict(k=max(1, N // 10))),
+        ("GSpar 10 %", wl.KIND_GSPAR, 0.2, dict(k=max(1, N // 10))),
         ("4 bits + norm (paper)", wl.KIND_QUANT_L2NORM, 0.5, dict(bits=4)),
         ("2 bits + norm (paper)", wl.KIND_QUANT_L2NORM, 0.3, dict(bits=2)),
     ]

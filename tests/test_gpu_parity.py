@@ -1046,7 +1046,7 @@ def test_l2norm_full_size_steady_state():
         fast.append(ds.ds_topk_candidate_rows())
         g_host = np.ascontiguousarray(g[:, :w.N].cpu().numpy())
         say("case", w.name, "oracle step", t, "rows on the speculative path so far", fast)
-        _, om = oracle.step(st, g_host, want_cv=False, all_cores=all_cores)
+        _, om = oracle.step(st, g_host, want_cv=False)
         assert np.array_equal(gm, om), f"step {t}: {int((gm != om).sum())} message bytes differ"
         del gm, om, g_host
     assert fast[0] == 0 and fast[-1] == w.n and fast[-2] >= w.n - 2, fast       # the written state takes a few steps to settle
