@@ -60,6 +60,7 @@ constexpr int BINS2 = 2048, SHIFT2 = 9;      // level 2: key bits 19..9
 constexpr int BINS3 = 512;                   // level 3: key bits 8..0
 constexpr int HIST_BINS = 2048;
 constexpr uint32_t FINE_SPAN = 1u << SHIFT2; // keys in a level-2 bin
+constexpr int TK_HPARTS = 16;                // partial level-1 histograms per row the first pass spreads its atomics over
 constexpr uint32_t TK_LIST_CAP = 8192;       // candidates inside the threshold's level-2 bin a row can list
 constexpr float TK_TARGET = 1.6f;            // candidates aimed at, in units of k
 
@@ -129,6 +130,8 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t* wave_sums) {
 
 struct Scratch {               // device pointers of the select's scratch (all owned by TopkState)
     uint32_t* hist;            // n x 2048: level-1 histogram (candidates of the first pass, or all keys in full mode)
+    uint32_t* hist_part;       // n x TK_HPARTS x 2048: what the first pass's workgroups add to (chunk mod TK_HPARTS picks the
+                               // part: a few hot addresses per row serialise their atomics); folded into hist by topk_decide_select
     uint32_t* hist2;           // n x 2048: level 2
     uint32_t* hist3;           // n x 512:  level 3 (full mode)
     TopkRow* rows;             // n
@@ -428,7 +431,7 @@ __global__ void __launch_bounds__(TK_THREADS) topk_form_collect(TopkArgs a, Scra
     }
     // the row histogram is used if the row ends up in candidate mode and wiped by topk_decide_select either way;
     // a candidate beyond the tracked bins (256 bins = 2^32 in magnitude above tlo) sends the row the exact way
-    uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
+    uint32_t* hrow = s.hist_part + ((size_t)row * TK_HPARTS + (chunk & (uint32_t)(TK_HPARTS - 1))) * HIST_BINS;
     for (int b = threadIdx.x; b < TK_H1; b += TK_THREADS)
         if (h[b]) atomicAdd(&hrow[bin0 + b], h[b]);
     if (far) atomicOr(&s.rows[row].overflow, 1u);
@@ -473,6 +476,19 @@ __global__ void __launch_bounds__(TK_THREADS) topk_decide_select(Scratch s, uint
     const int row = blockIdx.x;
     uint32_t* hrow = s.hist + (size_t)row * HIST_BINS;
     TopkRow& r = s.rows[row];
+    // the first pass left its counts in TK_HPARTS partial histograms, in the TK_H1 bins from tlo's upwards
+    const uint32_t bin0 = r.tlo >> SHIFT1;
+    for (uint32_t b = bin0 + threadIdx.x; b < bin0 + (uint32_t)TK_H1 && b < (uint32_t)HIST_BINS; b += TK_THREADS) {
+        uint32_t sum = 0;
+#pragma unroll
+        for (int q = 0; q < TK_HPARTS; ++q) {
+            uint32_t* part = s.hist_part + ((size_t)row * TK_HPARTS + q) * HIST_BINS + b;
+            sum += *part;
+            *part = 0;
+        }
+        hrow[b] += sum;
+    }
+    __syncthreads();
     select_digit(hrow, BINS1, k, wave_sums, res);
     for (int b = threadIdx.x; b < HIST_BINS; b += TK_THREADS) { hrow[b] = 0; s.hist2[(size_t)row * HIST_BINS + b] = 0; }
     for (int b = threadIdx.x; b < BINS3; b += TK_THREADS) s.hist3[(size_t)row * BINS3 + b] = 0;
@@ -1315,7 +1331,7 @@ struct TopkState {
 
 void topk_destroy(TopkState* st) {
     if (!st) return;
-    void* ptrs[] = {st->s.hist, st->s.hist2, st->s.hist3, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slot_val, st->s.slot_idx,
+    void* ptrs[] = {st->s.hist, st->s.hist_part, st->s.hist2, st->s.hist3, st->s.rows, st->s.cnt_gt, st->s.cnt_eq, st->s.eq_before, st->s.out_off, st->s.cand_cnt, st->s.slot_val, st->s.slot_idx,
                     st->s.list, st->s.csum, st->s.gs_overflow};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
@@ -1332,6 +1348,7 @@ ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::s
     if ((uint64_t)s.nchunks * TK_CHUNK > ld) { err = "internal: row pitch smaller than the chunked row"; delete st; return DS_EINVAL; }
     const size_t n = (size_t)cfg.n, nc = s.nchunks;
     bool ok = hipMalloc(&s.hist, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(&s.hist_part, n * TK_HPARTS * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.hist2, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.hist3, n * BINS3 * sizeof(uint32_t)) == hipSuccess &&
               hipMalloc(&s.rows, n * sizeof(TopkRow)) == hipSuccess &&
@@ -1346,6 +1363,7 @@ ds_status topk_create(const ds_config& cfg, uint64_t ld, TopkState** out, std::s
               hipMalloc(&s.csum, (st->gspar ? n * nc : 1) * sizeof(double)) == hipSuccess &&
               hipMalloc(&s.gs_overflow, sizeof(uint32_t)) == hipSuccess;
     ok = ok && hipMemset(s.hist, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
+         hipMemset(s.hist_part, 0, n * TK_HPARTS * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.hist2, 0, n * HIST_BINS * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.hist3, 0, n * BINS3 * sizeof(uint32_t)) == hipSuccess &&
          hipMemset(s.out_off, 0, n * (nc + 1) * sizeof(uint32_t)) == hipSuccess &&
