@@ -166,10 +166,13 @@ uint64_t autotune(ds_handle* h, uint64_t base_ld, size_t state_bytes, size_t msg
     if (ok) {
         float best_ms = 1e30f;
         h->ld = base_ld + dsq::kPitchSkew;
+        // A later candidate (or, below, another pitch) must win by 2 % to be taken: differences below that are
+        // timing noise, and a choice that flips between near-equal candidates from run to run makes measurements
+        // hard to compare.
         for (const dsq::TilePlan& plan : h->tile_candidates) {
             const float ms = time_plan(h, plan, g, e0, e1);
             if (ms < 0.f) { ok = false; break; }
-            if (ms < best_ms) { best_ms = ms; h->tile = plan; }
+            if (ms < 0.98f * best_ms) { best_ms = ms; h->tile = plan; }
         }
         for (uint64_t skew : kPitchCandidates) {
             if (!ok) break;
@@ -177,7 +180,7 @@ uint64_t autotune(ds_handle* h, uint64_t base_ld, size_t state_bytes, size_t msg
             h->ld = base_ld + skew;
             const float ms = time_plan(h, h->tile, g, e0, e1);
             if (ms < 0.f) { ok = false; break; }
-            if (ms < best_ms) { best_ms = ms; best_skew = skew; }
+            if (ms < 0.98f * best_ms) { best_ms = ms; best_skew = skew; }
         }
         (void)hipEventDestroy(e0);
         (void)hipEventDestroy(e1);
