@@ -62,19 +62,19 @@ typedef enum {
                               /* level (ties to the even code); code q stands for y = 2q - L,     */
                               /* C[v] = y * (norm / ||y||_2).  Message per worker:                */
                               /* [f32 norm][ceil(N*bits/32) u32 words]; bits in {2, 4, 8}         */
-    DS_COMP_GSPAR = 6,        /* GSpar (named next to random sparsification under Assumption 1.6), read as the */
+    DS_COMP_RAND_SPARSE = 5,  /* random sparsification (named next to top-k under Assumption 1.6): */
+                              /* every element is kept independently with probability k/N (floor   */
+                              /* to a multiple of 2^-24) and not rescaled; the mask comes from the  */
+                              /* shared seed, so the message carries values only:                  */
+                              /* [u32 count][count f32, ascending column], zero-padded to          */
+                              /* min(N, k + 8 ceil(sqrt k) + 64) values per worker                  */
+    DS_COMP_GSPAR = 6         /* GSpar (named next to random sparsification under Assumption 1.6), read as the */
                               /* magnitude-proportional sparsifier: element j is kept with probability          */
                               /* p_j = min(1, k |v_j| / sum_j |v_j|) (one shot: no second round where some p_j  */
                               /* are cut off at 1) and, like DS_COMP_RAND_SPARSE, not rescaled; the mask depends */
                               /* on v, so the message carries the columns: [u32 count][u32 0][count (u32 column, */
                               /* f32 value) pairs, ascending column], zero-padded to min(N, k + 8 ceil(sqrt k)   */
                               /* + 64) pairs                                                                     */
-    DS_COMP_RAND_SPARSE = 5   /* random sparsification (named next to top-k under Assumption 1.6): */
-                              /* every element is kept independently with probability k/N (floor   */
-                              /* to a multiple of 2^-24) and not rescaled; the mask comes from the  */
-                              /* shared seed, so the message carries values only:                  */
-                              /* [u32 count][count f32, ascending column], zero-padded to          */
-                              /* min(N, k + 8 ceil(sqrt k) + 64) values per worker                  */
 } ds_comp_kind;
 
 typedef struct {

@@ -209,7 +209,7 @@ static void oracle_cases() {
     struct K { int kind, bits; uint64_t block, k; };
     const K kinds[] = {{DS_COMP_IDENTITY, 0, 0, 0}, {DS_COMP_QUANT_MAXABS, 2, 64, 0}, {DS_COMP_QUANT_MAXABS, 4, 512, 0}, {DS_COMP_QUANT_MAXABS, 8, 128, 0},
                        {DS_COMP_SIGN_MEANABS, 0, 256, 0}, {DS_COMP_TOPK, 0, 0, 13}, {DS_COMP_QUANT_L2NORM, 2, 0, 0}, {DS_COMP_QUANT_L2NORM, 4, 0, 0},
-                       {DS_COMP_RAND_SPARSE, 0, 0, 40}, {6 /* GSpar */, 0, 0, 40}};
+                       {DS_COMP_RAND_SPARSE, 0, 0, 40}, {DS_COMP_GSPAR, 0, 0, 40}};
     for (const K& kd : kinds)
         for (uint64_t N : {(uint64_t)1, (uint64_t)63, (uint64_t)513, (uint64_t)1100}) {
             const uint64_t k = kd.k ? (kd.k < N ? kd.k : N) : 0;
