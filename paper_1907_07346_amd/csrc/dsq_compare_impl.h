@@ -274,6 +274,125 @@ void add_compare_plan(int n, const char* name, std::vector<TilePlan>& plans) {
     }
 }
 
+// DCD-PSGD with the next tile's streams requested ahead.  The kernel above has all loads of a workgroup before its
+// barrier and all arithmetic and stores behind it, and LDS (n rows of a tile in fp32) leaves room for one or two
+// workgroups per CU, so nothing is in flight while a workgroup encodes.  Here a workgroup walks over tiles
+// (tile = blockIdx.x, + gridDim.x, ...): after the barrier that publishes xh of tile T it requests x and g of its
+// next tile into a second set of registers and then mixes, encodes and stores tile T (SPARE).  Where the registers
+// do not allow a second set (many rows per wave), the request for row r of the next tile goes out as soon as row r
+// of tile T is stored, into the registers that row has just given up: all but the last row's loads then overlap the
+// encoding of the rows behind it.  Whole tiles only; the ragged last tile, if there is one, is taken by one
+// workgroup with the plain routine at the end.
+template <int KIND, int BITS, int B, int SW, int NW, int RPW, bool SPARE>
+__global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
+    using C = CompareTile<KIND, BITS, B, SW, NW>;
+    extern __shared__ __align__(16) uint8_t lds[];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint8_t* lds_vals = lds;
+    int32_t* lds_graph = reinterpret_cast<int32_t*>(lds + (size_t)a.n * C::ROW_BYTES);
+    const int gtotal = a.n + 1 + 2 * a.nnz;
+    for (int q = threadIdx.x; q < gtotal; q += NW * kWave) lds_graph[q] = a.rowptr[q];
+    const uint64_t whole = a.N / C::TC;                              // tiles without a ragged end
+    constexpr int RS = SPARE ? RPW : 1;
+    float4 xv[RPW][SW], gv[RPW][SW], xh[RPW][SW];
+    [[maybe_unused]] float4 xn[RS][SW], gn[RS][SW];
+    uint64_t tile = blockIdx.x;
+    if (tile < whole) {
+#pragma unroll
+        for (int r = 0; r < RPW; ++r)
+            if (wave + r * NW < a.n) C::template load_x_g<true>(a, wave + r * NW, tile * C::TC, lane, xv[r], gv[r]);
+    }
+    for (; tile < whole; tile += gridDim.x) {
+        const uint64_t col0 = tile * C::TC;
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const int i = wave + r * NW;
+            if (i < a.n) {
+                C::local_step(a, xv[r], gv[r], xh[r]);
+                float4* row = reinterpret_cast<float4*>(lds_vals + (size_t)i * C::ROW_BYTES);
+#pragma unroll
+                for (int s = 0; s < SW; ++s) row[s * kWave + lane] = xh[r][s];
+            }
+        }
+        __syncthreads();                                             // xh of all rows of tile T (and the graph) are in LDS
+        const uint64_t next = tile + gridDim.x;
+        if constexpr (SPARE) {
+            if (next < whole) {                                      // uniform
+#pragma unroll
+                for (int r = 0; r < RPW; ++r)
+                    if (wave + r * NW < a.n) C::template load_x_g<true>(a, wave + r * NW, next * C::TC, lane, xn[r], gn[r]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RPW; ++r) {
+            const int i = wave + r * NW;
+            if (i < a.n) {
+                C::template dcd_phase2<true>(a, i, col0, lane, lds_vals, lds_graph, xv[r], xh[r]);
+                if constexpr (!SPARE) {
+                    if (next < whole) C::template load_x_g<true>(a, i, next * C::TC, lane, xv[r], gv[r]);
+                }
+            }
+        }
+        __syncthreads();                                             // every wave is done with tile T's rows in LDS
+        if constexpr (SPARE) {
+#pragma unroll
+            for (int r = 0; r < RPW; ++r)
+#pragma unroll
+                for (int s = 0; s < SW; ++s) { xv[r][s] = xn[r][s]; gv[r][s] = gn[r][s]; }
+        }
+    }
+    if (whole * C::TC < a.N && blockIdx.x == (unsigned)(whole % gridDim.x))            // uniform over the workgroup
+        C::template run<kAlgoDcd, RPW, false>(a, 0, whole * C::TC, lds);
+    __syncthreads();                                                 // every wave has read the step counter for the last time
+    step_counter_bump<KIND, BITS, B, SW, NW>(a, blockIdx.x, gridDim.x, false);
+}
+
+template <int KIND, int BITS, int B, int SW, int NW, int RPW, bool SPARE>
+void launch_dcd_ahead(const TileArgs& a, int, hipStream_t stream) {
+    using C = CompareTile<KIND, BITS, B, SW, NW>;
+    const size_t lds = C::lds_bytes(a.n, a.nnz);
+    auto kern = dcd_ahead_kernel<KIND, BITS, B, SW, NW, RPW, SPARE>;
+    // as many workgroups as the device holds at once (asked once per kernel, device and LDS size)
+    static int resident[64] = {0};
+    static size_t resident_lds[64] = {0};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    dev &= 63;
+    if (resident[dev] == 0 || resident_lds[dev] != lds) {
+        if (lds > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, NW * kWave, lds) != hipSuccess || per_cu < 1) per_cu = 1;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        resident[dev] = per_cu * cus;
+        resident_lds[dev] = lds;
+        (void)hipGetLastError();
+    }
+    const uint64_t whole = a.N / C::TC;
+    const uint64_t want = whole ? whole : 1;
+    const unsigned grid = (unsigned)(want < (uint64_t)resident[dev] ? want : (uint64_t)resident[dev]);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * kWave), lds, stream, a);
+}
+
+template <int KIND, int BITS, int B, int SW, int NW, int RPW, bool SPARE>
+void add_dcd_ahead_plan(int n, const char* name, std::vector<TilePlan>& plans) {
+    // registers: x, xh of the tile in work and, with SPARE, x, g of the next one, in float4 per lane
+    constexpr int held = (SPARE ? 4 : 2) * RPW * SW;
+    constexpr int room = SPARE ? (NW > 8 ? 16 : 32) : (NW > 8 ? 8 : (SW <= 2 ? 32 : 16));    // beyond these the compiler spills
+    if constexpr (held <= room && (NW <= 8 || SW <= 4)) {
+        if (n > NW * RPW) return;
+        if (RPW > 1 && n <= NW * (RPW / 2)) return;
+        TilePlan p;
+        p.name = name;
+        p.launch = &launch_dcd_ahead<KIND, BITS, B, SW, NW, RPW, SPARE>;
+        p.tile_cols = SW * kSweep;
+        p.waves = NW;
+        p.rows_per_wave = RPW;
+        p.sweeps = SW;
+        plans.push_back(p);
+    }
+}
+
 template <int KIND, int BITS, int B, int ALGO>
 bool pick_compare_for_block(int n, int nnz, std::vector<TilePlan>& plans, std::string& err) {
     constexpr int SW = (B <= kSweep) ? 1 : (B / kSweep);
@@ -289,6 +408,17 @@ bool pick_compare_for_block(int n, int nnz, std::vector<TilePlan>& plans, std::s
     add_compare_plan<KIND, BITS, B, SW, 16, 1, ALGO>(n, "16w/1row", plans);
     add_compare_plan<KIND, BITS, B, SW, 16, 2, ALGO>(n, "16w/2rows", plans);
     add_compare_plan<KIND, BITS, B, SW, 16, 4, ALGO>(n, "16w/4rows", plans);
+    if constexpr (ALGO == kAlgoDcd) {                               // after the plain shapes: small problems take the first candidate
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 1, true>(n, "16w/1row/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 1, true>(n, "8w/1row/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 2, true>(n, "8w/2rows/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 4, true>(n, "8w/4rows/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 8, true>(n, "8w/8rows/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 4, false>(n, "8w/4rows/ahead-in-turn", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 8, false>(n, "8w/8rows/ahead-in-turn", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 2, false>(n, "16w/2rows/ahead-in-turn", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 4, false>(n, "16w/4rows/ahead-in-turn", plans);
+    }
     if (plans.empty()) {
         constexpr int LW = SW >= 8 ? 8 : 16;                        // waves of the looped fallback
         TilePlan p;

@@ -65,12 +65,17 @@ def test_comparison_lock_step_small_shapes(w):
 def test_comparison_every_launch_shape(algo, tag):
     """Every candidate launch shape of the comparison kernels that fits the configuration gives the same bits."""
     seen = 0
+    all_names = set()
     for base in (small(wl.KIND_QUANT_MAXABS, 8, 256 * 9 + 11, bits=2, block=256),
                  small(wl.KIND_QUANT_MAXABS, 16, 512 * 5 + 3, bits=4, block=512),
-                 small(wl.KIND_SIGN_MEANABS, 30, 1024 * 2 + 77, block=1024)):
+                 small(wl.KIND_SIGN_MEANABS, 30, 1024 * 2 + 77, block=1024),
+                 # more tiles than workgroups fit on the device at once: the shapes that walk over tiles and
+                 # request the next one ahead (DCD-PSGD) take several tiles per workgroup, and a ragged one
+                 small(wl.KIND_QUANT_MAXABS, 16, 512 * 2100 + 3, bits=4, block=512),
+                 small(wl.KIND_QUANT_MAXABS, 40, 256 * 2600 + 9, bits=2, block=256)):
         w = with_algo(base, algo, tag)
         names = set()
-        for i in range(12):
+        for i in range(24):
             ds = b.DeepSqueeze.from_workload(w, plan=dict(tile_plan=i))
             name = ds.ds_plan_name()
             ds.ds_destroy()
@@ -82,7 +87,10 @@ def test_comparison_every_launch_shape(algo, tag):
             lock_step(w, steps=2, plan=dict(tile_plan=i))
         assert names
         seen += len(names)
+        all_names |= names
     assert seen >= 5
+    if algo == wl.ALGO_DCD_PSGD:
+        assert any("ahead" in nm for nm in all_names) and any("in-turn" in nm for nm in all_names)
 
 
 @pytest.mark.parametrize("algo,tag", ALGOS)
