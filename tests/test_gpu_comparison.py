@@ -90,7 +90,7 @@ def test_comparison_every_launch_shape(algo, tag):
         all_names |= names
     assert seen >= 5
     if algo == wl.ALGO_DCD_PSGD:
-        assert any("ahead" in nm for nm in all_names) and any("in-turn" in nm for nm in all_names)
+        assert any("/ahead/" in nm for nm in all_names) and any("in-turn" in nm for nm in all_names)
 
 
 @pytest.mark.parametrize("algo,tag", ALGOS)
