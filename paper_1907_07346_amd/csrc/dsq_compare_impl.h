@@ -277,7 +277,8 @@ void add_compare_plan(int n, const char* name, std::vector<TilePlan>& plans) {
 // DCD-PSGD with the next tile's streams requested ahead.  The kernel above has all loads of a workgroup before its
 // barrier and all arithmetic and stores behind it, and LDS (n rows of a tile in fp32) leaves room for one or two
 // workgroups per CU, so nothing is in flight while a workgroup encodes.  Here a workgroup walks over tiles
-// (tile = blockIdx.x, + gridDim.x, ...): after the barrier that publishes xh of tile T it requests x and g of its
+// (the first one is blockIdx.x, the following ones are drawn from a counter in device memory, so that a workgroup
+// on a slow CU takes fewer): after the barrier that publishes xh of tile T it requests x and g of its
 // next tile into a second set of registers and then mixes, encodes and stores tile T (SPARE).  Where the registers
 // do not allow a second set (many rows per wave), the request for row r of the next tile goes out as soon as row r
 // of tile T is stored, into the registers that row has just given up: all but the last row's loads then overlap the
@@ -297,13 +298,19 @@ __global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
     constexpr int RS = SPARE ? RPW : 1;
     float4 xv[RPW][SW], gv[RPW][SW], xh[RPW][SW];
     [[maybe_unused]] float4 xn[RS][SW], gn[RS][SW];
+    // tile queue: thread 0 draws the tile after next while the current one is in work and hands it to the others
+    // through LDS at the first barrier
+    __shared__ unsigned long long s_next;
+    unsigned long long* queue = a.t_ptr + 16;
+    unsigned long long upcoming = whole;
+    if (threadIdx.x == 0) upcoming = gridDim.x + __hip_atomic_fetch_add(queue, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     uint64_t tile = blockIdx.x;
     if (tile < whole) {
 #pragma unroll
         for (int r = 0; r < RPW; ++r)
             if (wave + r * NW < a.n) C::template load_x_g<true>(a, wave + r * NW, tile * C::TC, lane, xv[r], gv[r]);
     }
-    for (; tile < whole; tile += gridDim.x) {
+    while (tile < whole) {
         const uint64_t col0 = tile * C::TC;
 #pragma unroll
         for (int r = 0; r < RPW; ++r) {
@@ -315,8 +322,13 @@ __global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
                 for (int s = 0; s < SW; ++s) row[s * kWave + lane] = xh[r][s];
             }
         }
+        if (threadIdx.x == 0) s_next = upcoming;
         __syncthreads();                                             // xh of all rows of tile T (and the graph) are in LDS
-        const uint64_t next = tile + gridDim.x;
+        const unsigned long long nx = s_next;
+        const uint64_t next = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(nx >> 32)) << 32) |
+                              (uint32_t)__builtin_amdgcn_readfirstlane((int)nx);
+        if (threadIdx.x == 0 && next < whole)
+            upcoming = gridDim.x + __hip_atomic_fetch_add(queue, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if constexpr (SPARE) {
             if (next < whole) {                                      // uniform
 #pragma unroll
@@ -341,11 +353,12 @@ __global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
 #pragma unroll
                 for (int s = 0; s < SW; ++s) { xv[r][s] = xn[r][s]; gv[r][s] = gn[r][s]; }
         }
+        tile = next;
     }
     if (whole * C::TC < a.N && blockIdx.x == (unsigned)(whole % gridDim.x))            // uniform over the workgroup
         C::template run<kAlgoDcd, RPW, false>(a, 0, whole * C::TC, lds);
     __syncthreads();                                                 // every wave has read the step counter for the last time
-    step_counter_bump<KIND, BITS, B, SW, NW>(a, blockIdx.x, gridDim.x, false);
+    step_counter_bump<KIND, BITS, B, SW, NW>(a, blockIdx.x, gridDim.x, false, queue);
 }
 
 template <int KIND, int BITS, int B, int SW, int NW, int RPW, bool SPARE>
@@ -375,13 +388,14 @@ void launch_dcd_ahead(const TileArgs& a, int, hipStream_t stream) {
 }
 
 template <int KIND, int BITS, int B, int SW, int NW, int RPW, bool SPARE>
-void add_dcd_ahead_plan(int n, const char* name, std::vector<TilePlan>& plans) {
+void add_dcd_ahead_plan(int n, int nnz, const char* name, std::vector<TilePlan>& plans) {
     // registers: x, xh of the tile in work and, with SPARE, x, g of the next one, in float4 per lane
     constexpr int held = (SPARE ? 4 : 2) * RPW * SW;
     constexpr int room = SPARE ? (NW > 8 ? 16 : 32) : (NW > 8 ? 8 : (SW <= 2 ? 32 : 16));    // beyond these the compiler spills
     if constexpr (held <= room && (NW <= 8 || SW <= 4)) {
         if (n > NW * RPW) return;
         if (RPW > 1 && n <= NW * (RPW / 2)) return;
+        if (CompareTile<KIND, BITS, B, SW, NW>::lds_bytes(n, nnz) + 64 > kMaxLds) return;   // the kernel's own queue word
         TilePlan p;
         p.name = name;
         p.launch = &launch_dcd_ahead<KIND, BITS, B, SW, NW, RPW, SPARE>;
@@ -409,15 +423,15 @@ bool pick_compare_for_block(int n, int nnz, std::vector<TilePlan>& plans, std::s
     add_compare_plan<KIND, BITS, B, SW, 16, 2, ALGO>(n, "16w/2rows", plans);
     add_compare_plan<KIND, BITS, B, SW, 16, 4, ALGO>(n, "16w/4rows", plans);
     if constexpr (ALGO == kAlgoDcd) {                               // after the plain shapes: small problems take the first candidate
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 1, true>(n, "16w/1row/ahead", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 1, true>(n, "8w/1row/ahead", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 2, true>(n, "8w/2rows/ahead", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 4, true>(n, "8w/4rows/ahead", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 8, true>(n, "8w/8rows/ahead", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 4, false>(n, "8w/4rows/ahead-in-turn", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 8, false>(n, "8w/8rows/ahead-in-turn", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 2, false>(n, "16w/2rows/ahead-in-turn", plans);
-        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 4, false>(n, "16w/4rows/ahead-in-turn", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 1, true>(n, nnz, "16w/1row/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 1, true>(n, nnz, "8w/1row/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 2, true>(n, nnz, "8w/2rows/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 4, true>(n, nnz, "8w/4rows/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 8, true>(n, nnz, "8w/8rows/ahead", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 4, false>(n, nnz, "8w/4rows/ahead-in-turn", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 8, 8, false>(n, nnz, "8w/8rows/ahead-in-turn", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 2, false>(n, nnz, "16w/2rows/ahead-in-turn", plans);
+        add_dcd_ahead_plan<KIND, BITS, B, SW, 16, 4, false>(n, nnz, "16w/4rows/ahead-in-turn", plans);
     }
     if (plans.empty()) {
         constexpr int LW = SW >= 8 ? 8 : 16;                        // waves of the looped fallback

@@ -64,8 +64,10 @@ struct TileArgs {
                                        // [1]: finished first-level cells; [2]: random sparsifier: the step whose keep
                                        // counts are in keep_raw (~0 if none); [3]: row-streaming variant: a gossip sum is
                                        // pending; [4]: row-streaming variant: the message buffer (0 / 1) the last step
-                                       // wrote; [32 (1+c)], c < 64: finished workgroups with blockIdx % 64 == c.
-                                       // Cells [1] and [32 (1+c)] are zero between launches.
+                                       // wrote; [16]: tile queue of the kernels whose workgroups walk over tiles (next tile
+                                       // to hand out, counted from the grid size); [32 (1+c)], c < 64: finished
+                                       // workgroups with blockIdx % 64 == c.
+                                       // Cells [1], [16] and [32 (1+c)] are zero between launches.
 };
 
 // A compiled variant of the fused tile kernel, chosen once at init.

@@ -805,7 +805,8 @@ __global__ void __launch_bounds__(NW* kWave) fused_tile_kernel(TileArgs a, int r
 // workers fits; the price is reading (degree + 1) code streams per column (mostly cache hits) and a
 // deferred gossip sum that readers of x must flush.
 template <int KIND, int BITS, int B, int SW, int NW>
-__device__ __forceinline__ void step_counter_bump(const TileArgs& a, unsigned long long linear_block, unsigned long long blocks, bool set_pending) {
+__device__ __forceinline__ void step_counter_bump(const TileArgs& a, unsigned long long linear_block, unsigned long long blocks, bool set_pending,
+                                                  unsigned long long* also_clear = nullptr) {
     if (threadIdx.x == 0) {
         const unsigned cell = (unsigned)(linear_block & 63u);
         const unsigned long long members = (blocks >> 6) + (cell < (blocks & 63u) ? 1u : 0u);
@@ -817,6 +818,8 @@ __device__ __forceinline__ void step_counter_bump(const TileArgs& a, unsigned lo
             if (__hip_atomic_fetch_add(done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == cells - 1ull) {
                 __hip_atomic_store(done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const unsigned long long t = __hip_atomic_fetch_add(a.t_ptr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // a cell the launch used as a work queue: every other workgroup has drawn its last number
+                if (also_clear != nullptr) __hip_atomic_store(also_clear, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (set_pending) {
                     __hip_atomic_store(a.pending, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     // which of the two message buffers this step wrote (readers must not infer it from t: the
