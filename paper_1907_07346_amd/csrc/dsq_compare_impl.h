@@ -149,16 +149,19 @@ struct CompareTile {
         for (int s = 0; s < SW; ++s) row[s * kWave + lane] = xh[s];
     }
 
-    template <bool FULL>
+    // XH_LDS: the row's own xh is read from its LDS slot (where phase 1 put it) when it is needed, not passed in.
+    template <bool FULL, bool XH_LDS = false>
     static __device__ __forceinline__ void dcd_phase2(const TileArgs& a, int i, uint64_t col0, int lane, const uint8_t* lds_vals,
                                                       const int32_t* lds_graph, const float4 (&xv)[SW], const float4 (&xh)[SW]) {
         float acc[SW][4];
         mix_row(a, i, lane, lds_vals, lds_graph, acc);
         float4 z[SW];
+        const float4* own = reinterpret_cast<const float4*>(lds_vals + (size_t)i * ROW_BYTES);
 #pragma unroll
         for (int s = 0; s < SW; ++s) {                               // the uncompressed method's target minus the model
-            z[s].x = fmaf(a.eta, acc[s][0], xh[s].x) - xv[s].x; z[s].y = fmaf(a.eta, acc[s][1], xh[s].y) - xv[s].y;
-            z[s].z = fmaf(a.eta, acc[s][2], xh[s].z) - xv[s].z; z[s].w = fmaf(a.eta, acc[s][3], xh[s].w) - xv[s].w;
+            const float4 h = XH_LDS ? own[s * kWave + lane] : xh[s];
+            z[s].x = fmaf(a.eta, acc[s][0], h.x) - xv[s].x; z[s].y = fmaf(a.eta, acc[s][1], h.y) - xv[s].y;
+            z[s].z = fmaf(a.eta, acc[s][2], h.z) - xv[s].z; z[s].w = fmaf(a.eta, acc[s][3], h.w) - xv[s].w;
         }
         float* xout = a.x + (uint64_t)i * a.ld + col0 + 4 * lane;
         T::template encode_row<FULL, 2>(a, i, i, col0, lane, z, xv, nullptr, nullptr, xout);     // x = x + C[z]
@@ -283,7 +286,8 @@ void add_compare_plan(int n, const char* name, std::vector<TilePlan>& plans) {
 // do not allow a second set (many rows per wave), the request for row r of the next tile goes out as soon as row r
 // of tile T is stored, into the registers that row has just given up: all but the last row's loads then overlap the
 // encoding of the rows behind it.  Whole tiles only; the ragged last tile, if there is one, is taken by one
-// workgroup with the plain routine at the end.
+// workgroup with the plain routine at the end.  A row's own xh is read back from its LDS slot in phase 2 (the same
+// fp32 values) rather than held in registers across the barrier: measured equal or faster, and 50 VGPRs fewer.
 template <int KIND, int BITS, int B, int SW, int NW, int RPW, bool SPARE>
 __global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
     using C = CompareTile<KIND, BITS, B, SW, NW>;
@@ -296,14 +300,21 @@ __global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
     for (int q = threadIdx.x; q < gtotal; q += NW * kWave) lds_graph[q] = a.rowptr[q];
     const uint64_t whole = a.N / C::TC;                              // tiles without a ragged end
     constexpr int RS = SPARE ? RPW : 1;
-    float4 xv[RPW][SW], gv[RPW][SW], xh[RPW][SW];
+    float4 xv[RPW][SW], gv[RPW][SW], xh[SW];
     [[maybe_unused]] float4 xn[RS][SW], gn[RS][SW];
     // tile queue: thread 0 draws the tile after next while the current one is in work and hands it to the others
     // through LDS at the first barrier
-    __shared__ unsigned long long s_next;
+    // (32-bit numbers: a row of 2^32 tiles would be a terabyte)
+    __shared__ unsigned s_next;
     unsigned long long* queue = a.t_ptr + 16;
-    unsigned long long upcoming = whole;
-    if (threadIdx.x == 0) upcoming = gridDim.x + __hip_atomic_fetch_add(queue, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned* queue32 = reinterpret_cast<unsigned*>(queue);
+    const unsigned none = 0xFFFFFFFFu;
+    unsigned upcoming = none;
+    auto draw = [&]() {
+        const unsigned q = gridDim.x + __hip_atomic_fetch_add(queue32, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return q < whole ? q : none;
+    };
+    if (threadIdx.x == 0) upcoming = draw();
     uint64_t tile = blockIdx.x;
     if (tile < whole) {
 #pragma unroll
@@ -316,19 +327,17 @@ __global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
         for (int r = 0; r < RPW; ++r) {
             const int i = wave + r * NW;
             if (i < a.n) {
-                C::local_step(a, xv[r], gv[r], xh[r]);
+                C::local_step(a, xv[r], gv[r], xh);
                 float4* row = reinterpret_cast<float4*>(lds_vals + (size_t)i * C::ROW_BYTES);
 #pragma unroll
-                for (int s = 0; s < SW; ++s) row[s * kWave + lane] = xh[r][s];
+                for (int s = 0; s < SW; ++s) row[s * kWave + lane] = xh[s];
             }
         }
         if (threadIdx.x == 0) s_next = upcoming;
         __syncthreads();                                             // xh of all rows of tile T (and the graph) are in LDS
-        const unsigned long long nx = s_next;
-        const uint64_t next = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(nx >> 32)) << 32) |
-                              (uint32_t)__builtin_amdgcn_readfirstlane((int)nx);
-        if (threadIdx.x == 0 && next < whole)
-            upcoming = gridDim.x + __hip_atomic_fetch_add(queue, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned nx = (unsigned)__builtin_amdgcn_readfirstlane((int)s_next);
+        const uint64_t next = nx != none ? (uint64_t)nx : whole;
+        if (threadIdx.x == 0 && nx != none) upcoming = draw();
         if constexpr (SPARE) {
             if (next < whole) {                                      // uniform
 #pragma unroll
@@ -340,7 +349,7 @@ __global__ void __launch_bounds__(NW* kWave) dcd_ahead_kernel(TileArgs a) {
         for (int r = 0; r < RPW; ++r) {
             const int i = wave + r * NW;
             if (i < a.n) {
-                C::template dcd_phase2<true>(a, i, col0, lane, lds_vals, lds_graph, xv[r], xh[r]);
+                C::template dcd_phase2<true, true>(a, i, col0, lane, lds_vals, lds_graph, xv[r], xh);
                 if constexpr (!SPARE) {
                     if (next < whole) C::template load_x_g<true>(a, i, next * C::TC, lane, xv[r], gv[r]);
                 }
@@ -389,9 +398,11 @@ void launch_dcd_ahead(const TileArgs& a, int, hipStream_t stream) {
 
 template <int KIND, int BITS, int B, int SW, int NW, int RPW, bool SPARE>
 void add_dcd_ahead_plan(int n, int nnz, const char* name, std::vector<TilePlan>& plans) {
-    // registers: x, xh of the tile in work and, with SPARE, x, g of the next one, in float4 per lane
+    // registers, counted as x and the encoder's copy of a row of the tile in work and, with SPARE, x, g of the next
+    // one, in float4 per lane
     constexpr int held = (SPARE ? 4 : 2) * RPW * SW;
-    constexpr int room = SPARE ? (NW > 8 ? 16 : 32) : (NW > 8 ? 8 : (SW <= 2 ? 32 : 16));    // beyond these the compiler spills
+    constexpr int room = SPARE ? (NW > 8 ? 16 : (SW <= 2 ? 64 : 32))
+                               : (NW > 8 ? (SW <= 2 ? 16 : 8) : 32);          // beyond these the compiler spills
     if constexpr (held <= room && (NW <= 8 || SW <= 4)) {
         if (n > NW * RPW) return;
         if (RPW > 1 && n <= NW * (RPW / 2)) return;
