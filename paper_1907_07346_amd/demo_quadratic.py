@@ -8,7 +8,11 @@ consensus distance and the carried compression error.  This illustrates the beha
 describes (convergence under compression thanks to the error compensation); it is not the paper's experiment,
 whose data and model are not available here.
 
-    python -m paper_1907_07346_amd.demo_quadratic [--steps 300] [--N 65536] [--workers 8]
+    python -m paper_1907_07346_amd.demo_quadratic [--steps 300] [--N 65536] [--workers 8] [--eta-sweep]
+
+--eta-sweep adds, per compressor, the averaging rate eta swept from 0.05 to 1 next to the rate Theorem 1 allows,
+min(1/2, (alpha^(-2/3) - 1) / 4), with alpha measured on the run itself as |v - C[v]| / |v| (Assumption 1.6's
+constant; the last step's value).
 """
 from __future__ import annotations
 
@@ -27,15 +31,16 @@ class _Borrowed:
                                          "strides": None}
 
 
-def run(kind, n, N, steps, gamma, eta, sigma, report, algo=wl.ALGO_DEEPSQUEEZE, **comp):
+def run(kind, n, N, steps, gamma, eta, sigma, report, algo=wl.ALGO_DEEPSQUEEZE, want_alpha=False, **comp):
     cfg, keep = b.make_config(n, N, wl.TOPO_RING, kind, gamma, eta, seed=1, algo=algo, **comp)
     ds = b.DeepSqueeze(cfg, keep)
     c = torch.from_numpy(detgen.centres(n, N, seed=1)).cuda()
     opt = c.mean(0)
     f_opt = float(0.5 * ((opt - c) ** 2).sum(1).mean())
-    xp, _, ld = ds.ds_state_ptrs()
+    xp, dp, ld = ds.ds_state_ptrs()
     g = torch.zeros((n, ld), device="cuda")
     rows = []
+    alpha = float("nan")
     for t in range(steps + 1):
         if t in report:
             ds.ds_state_ptrs()                                  # completes a deferred tail, if the path has one
@@ -48,9 +53,19 @@ def run(kind, n, N, steps, gamma, eta, sigma, report, algo=wl.ALGO_DEEPSQUEEZE, 
             break
         ds.ds_state_ptrs()
         b.ds_workload_gradient("quadratic", n, N, sigma, 1, t, g, xp, ld)
+        if want_alpha and t == steps - 1:                       # v of Algorithm 1, line 5, formed here for the ratio only
+            x = torch.as_tensor(_Borrowed(xp, (n, ld)), device="cuda")[:, :N]
+            d = torch.as_tensor(_Borrowed(dp, (n, ld)), device="cuda")[:, :N]
+            v_norm = float((x.double() - gamma * g[:, :N].double() + d.double()).norm())
         ds.ds_step(g)
+        if want_alpha and t == steps - 1:
+            ds.ds_state_ptrs()
+            d = torch.as_tensor(_Borrowed(dp, (n, ld)), device="cuda")[:, :N]
+            alpha = float(d.double().norm()) / v_norm if v_norm > 0 else 0.0
     bytes_per_step = ds.ds_diagnostics()["message_bytes"]
     ds.ds_destroy()
+    if want_alpha:
+        return rows, bytes_per_step, alpha
     return rows, bytes_per_step
 
 
@@ -61,6 +76,7 @@ def main():
     ap.add_argument("--workers", type=int, default=8)
     ap.add_argument("--gamma", type=float, default=0.1)
     ap.add_argument("--sigma", type=float, default=0.1)
+    ap.add_argument("--eta-sweep", action="store_true")
     args = ap.parse_args()
     n, N = args.workers, args.N
     report = sorted({0, args.steps // 10, args.steps // 3, args.steps})
@@ -97,6 +113,27 @@ def main():
             rows, _ = run(kind, n, N, args.steps, args.gamma, eta, args.sigma, report, algo=algo, **comp)
             line = "  ".join(f"t={t}: {gap:.2e} {cons:.2e} {dsq:.2e}" for t, gap, cons, dsq in rows)
             print(f"  {rname:24s} | {line}", flush=True)
+    if args.eta_sweep:
+        eta_sweep(args, cases)
+
+
+def eta_sweep(args, cases):
+    """Consensus distance and carried error at the end of the run for a range of averaging rates, next to the
+    rate Theorem 1 allows for the compressor's measured alpha."""
+    n, N = args.workers, args.N
+    etas = (0.05, 0.1, 0.2, 0.4, 0.6, 0.8, 1.0)
+    print(f"averaging rate sweep, {args.steps} steps; per parameter at the end: consensus distance / carried error "
+          f"(inf or nan: diverged)")
+    for name, kind, _, comp in cases:
+        cells, alpha = [], float("nan")
+        for eta in etas:
+            rows, _, a = run(kind, n, N, args.steps, args.gamma, eta, args.sigma, [args.steps], want_alpha=True, **comp)
+            _, _, cons, dsq = rows[-1]
+            cells.append(f"eta={eta:g}: {cons:.2e}/{dsq:.2e}")
+            if eta == 0.2:
+                alpha = a
+        bound = 0.5 if not alpha > 0 else min(0.5, (alpha ** (-2.0 / 3.0) - 1.0) / 4.0)
+        print(f"{name:24s} alpha={alpha:.3f} Theorem 1: eta <= {bound:.3f} | " + "  ".join(cells), flush=True)
 
 
 if __name__ == "__main__":
