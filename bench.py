@@ -106,8 +106,8 @@ def cpu_baseline(w, budget_s=9.0):
 
 
 def yardsticks(torch, b):
-    """What a trivial kernel reaches on this GPU: a plain copy, and the access mix of ds_step (3 streaming loads,
-    2 stores, in place) without its arithmetic."""
+    """What a trivial kernel reaches on this GPU: a plain copy, the access mix of ds_step (3 streaming loads,
+    2 stores, in place) without its arithmetic, and the same for the DCD-PSGD step (2 loads, 1 store)."""
     nbytes = 1 << 30
     src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
     dst = torch.empty_like(src)
@@ -133,12 +133,21 @@ def yardsticks(torch, b):
     e1.record()
     torch.cuda.synchronize()
     mix_gbs = 5 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    for _ in range(3):
+        b.ds_bench_stream(dst, None, src)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        b.ds_bench_stream(dst, None, src)
+    e1.record()
+    torch.cuda.synchronize()
+    mix21_gbs = 3 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del src, dst, third
     torch.cuda.empty_cache()
-    return copy_gbs, mix_gbs
+    return copy_gbs, mix_gbs, mix21_gbs
 
 
-def run_config(torch, b, wl, w, K, Wm, hip_graph, copy_gbs, mix_gbs, traffic_table):
+def run_config(torch, b, wl, w, K, Wm, hip_graph, copy_gbs, mix_gbs, mix21_gbs, traffic_table):
     """Times K steps of one configuration after Wm warm-up steps; returns its report entry."""
     ds = b.DeepSqueeze.from_workload(w)
     _, _, ld = ds.ds_state_ptrs()
@@ -196,6 +205,9 @@ def run_config(torch, b, wl, w, K, Wm, hip_graph, copy_gbs, mix_gbs, traffic_tab
                      "frac_of_plain_copy": achieved / copy_gbs, "stream_3r2w_GBps": mix_gbs,
                      "frac_of_3r2w_stream": achieved / mix_gbs},
     }
+    if w.algo == 1:        # DCD-PSGD has no second state array: its bare stream is 2 loads / 1 store
+        entry["roofline"]["stream_2r1w_GBps"] = mix21_gbs
+        entry["roofline"]["frac_of_2r1w_stream"] = achieved / mix21_gbs
     ds.ds_destroy()
     del gs
     torch.cuda.empty_cache()
@@ -228,9 +240,9 @@ def main():
 
     torch.cuda.set_device(0)
     K, Wm = args.steps, args.warmup
-    copy_gbs, mix_gbs = yardsticks(torch, b)
+    copy_gbs, mix_gbs, mix21_gbs = yardsticks(torch, b)
     if args.copy_only:
-        print(json.dumps({"copy_GBps": copy_gbs, "bytes_per_launch": 2 * (1 << 30), "stream_3r2w_GBps": mix_gbs}))
+        print(json.dumps({"copy_GBps": copy_gbs, "bytes_per_launch": 2 * (1 << 30), "stream_3r2w_GBps": mix_gbs, "stream_2r1w_GBps": mix21_gbs}))
         return
 
     traffic_table = {}
@@ -244,7 +256,7 @@ def main():
     entries = {}
     for idx in todo:
         # the cache-resident configuration 0 is launch-bound: more steps cost nothing and steady the figure
-        entries[idx] = run_config(torch, b, wl, all_w[idx], K, Wm, args.hip_graph, copy_gbs, mix_gbs, traffic_table)
+        entries[idx] = run_config(torch, b, wl, all_w[idx], K, Wm, args.hip_graph, copy_gbs, mix_gbs, mix21_gbs, traffic_table)
         print(f"bench: {entries[idx]['workload']}: {entries[idx]['ms_per_step']:.4f} ms/step, "
               f"{entries[idx]['roofline']['frac']:.3f} of peak", file=sys.stderr, flush=True)
     head = entries[head_idx]

@@ -333,6 +333,7 @@ ds_status ds_bench_copy(void* dst_dev, const void* src_dev, uint64_t bytes, void
 /* Measurement aid, not part of the method: the access mix of ds_step without its arithmetic -- per 16 bytes
  * three streaming loads (x, delta, g) and two stores (x += g, delta += g, in place) -- over three device arrays of
  * `bytes` each (a multiple of 16, 16-byte aligned), enqueued on hip_stream.  5 * bytes move per call.
+ * delta_dev == NULL: the mix of the DCD-PSGD step instead, two loads (x, g) and one store (x += g), 3 * bytes per call.
  * DS_EINVAL for bytes >= 64 GiB. */
 ds_status ds_bench_stream(void* x_dev, void* delta_dev, const void* g_dev, uint64_t bytes, void* hip_stream);
 

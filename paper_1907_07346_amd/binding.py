@@ -174,13 +174,14 @@ def ds_bench_copy(dst: "torch.Tensor", src: "torch.Tensor", stream=None):
         raise DsqError(st, "ds_bench_copy")
 
 
-def ds_bench_stream(x: "torch.Tensor", d: "torch.Tensor", g: "torch.Tensor", stream=None):
-    """x += g, d += g with the library's 3-loads / 2-stores streaming kernel (the access mix of ds_step)."""
+def ds_bench_stream(x: "torch.Tensor", d: "Optional[torch.Tensor]", g: "torch.Tensor", stream=None):
+    """x += g, d += g with the library's 3-loads / 2-stores streaming kernel (the access mix of ds_step); d = None:
+    x += g alone, 2 loads / 1 store (the mix of the DCD-PSGD step)."""
     nbytes = x.numel() * x.element_size()
-    assert d.numel() * d.element_size() == nbytes and g.numel() * g.element_size() == nbytes
-    assert x.is_cuda and d.is_cuda and g.is_cuda
+    assert (d is None or d.numel() * d.element_size() == nbytes) and g.numel() * g.element_size() == nbytes
+    assert x.is_cuda and (d is None or d.is_cuda) and g.is_cuda
     s = stream if stream is not None else torch.cuda.current_stream()
-    st = lib().ds_bench_stream(x.data_ptr(), d.data_ptr(), g.data_ptr(), nbytes, s.cuda_stream)
+    st = lib().ds_bench_stream(x.data_ptr(), d.data_ptr() if d is not None else None, g.data_ptr(), nbytes, s.cuda_stream)
     if st != DS_OK:
         raise DsqError(st, "ds_bench_stream")
 

@@ -260,6 +260,16 @@ __global__ void __launch_bounds__(256) stream_3r2w_kernel(f32x4* __restrict__ x,
     }
 }
 
+// The same for the DCD-PSGD step, which has no second state array: two loads, one store.
+__global__ void __launch_bounds__(256) stream_2r1w_kernel(f32x4* __restrict__ x, const f32x4* __restrict__ g, uint64_t n4) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) {
+        const f32x4 gv = __builtin_nontemporal_load(g + i);
+        const f32x4 xv = __builtin_nontemporal_load(x + i);
+        __builtin_nontemporal_store(xv + gv, x + i);
+    }
+}
+
 // ---- ds_step_static: one step with no handle and no allocation ------------------------------------------------
 // Everything the fused tile kernel needs beyond the caller's arrays -- the step-counter cells with its
 // finished-workgroup counters, and W - I in CSR form -- lives in this file-scope device array.  Every GPU the
@@ -387,12 +397,17 @@ ds_status ds_workload_gradient(const ds_workload* w, uint64_t t, const float* x_
 }
 
 ds_status ds_bench_stream(void* x_dev, void* delta_dev, const void* g_dev, uint64_t bytes, void* hip_stream) {
-    if (!x_dev || !delta_dev || !g_dev || (bytes & 15) ||
+    if (!x_dev || !g_dev || (bytes & 15) ||
         ((reinterpret_cast<uintptr_t>(x_dev) | reinterpret_cast<uintptr_t>(delta_dev) | reinterpret_cast<uintptr_t>(g_dev)) & 15))
         return DS_EINVAL;
     const uint64_t n4 = bytes / 16;
     if (n4 == 0) return DS_OK;
     if (n4 > 0xFFFFFF00ull) return DS_EINVAL;
+    if (!delta_dev) {
+        hipLaunchKernelGGL(stream_2r1w_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                           static_cast<f32x4*>(x_dev), static_cast<const f32x4*>(g_dev), n4);
+        return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
+    }
     hipLaunchKernelGGL(stream_3r2w_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<f32x4*>(x_dev), static_cast<f32x4*>(delta_dev), static_cast<const f32x4*>(g_dev), n4);
     return hipGetLastError() == hipSuccess ? DS_OK : DS_EHIP;
